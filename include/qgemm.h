@@ -1,0 +1,127 @@
+/*
+ * qgemm.h -- C ABI of the MI355X (gfx950) mixed-precision matmul library
+ *
+ *     C[M,N] = A[M,K] . dequant(W[K,N])
+ *
+ * A and C are fp16 or bf16, W holds 1..8-bit codes (uintk, intk, small floats)
+ * stored bit-packed with group-wise scales and zero-points.  The contraction is
+ * the problem statement of the Tilus paper (arXiv 2504.12984, Section "An
+ * Example of Tilus Program": C = A x B, A float16, B a low-bit type).  The
+ * operations below are the pieces of that paper's data path:
+ *
+ *   qg_pack_codes       compact, gap-free storage of sub-byte values in a byte
+ *                       array (Section "Storage of Low-Precision Data")
+ *   repack              the offline "Change Layout" step: tile the weight and
+ *                       store each tile as the byte string the threads will
+ *                       load (Section "Efficient Low-Precision Support in LLMs",
+ *                       "Efficient Low-Precision Weight Loading")
+ *   qdequant            load + reinterpret + vectorised cast/de-quantise
+ *                       (same section, "Efficient Casting"), written out to
+ *                       memory so it can be checked bit for bit
+ *   qgemm               the full kernel: pipelined weight load, in-register
+ *                       cast, matrix-core accumulate, store (Sections "Key
+ *                       Ideas" and "An Example of Tilus Program")
+ *
+ * Conventions common to every call
+ *   - every pointer is DEVICE memory owned by the caller, 16-byte aligned;
+ *   - work is enqueued on `stream` (a hipStream_t passed as void*; NULL is the
+ *     default stream) and the call returns without synchronising;
+ *   - the return value is a qg_status (0 = ok, negative = error, nothing was
+ *     enqueued); no call throws, none frees caller memory;
+ *   - qgemm may use a library-owned, lazily grown per-device workspace for
+ *     split-K partial sums; it is ordered on `stream`, so two qgemm calls that
+ *     overlap on DIFFERENT streams of one device race on it.
+ *
+ * De-quantisation (the paper names the step but prints no formula; this is the
+ * standard affine group form):
+ *        w[k,n] = rne_act( (value(code[k,n]) - z[k/g, n]) * s[k/g, n] )
+ *   value(): uintk -> code; intk -> two's complement (int1 = {0,-1});
+ *            floatk -> sign|exponent|mantissa, bias 2^(e-1)-1, subnormals, no
+ *            infinities; e4m3's S.1111.111 is NaN and must not be used
+ *   one rounding, to nearest even, to the activation type; the contraction
+ *   accumulates products of A with these ROUNDED weights in fp32 and rounds
+ *   the sum once (nearest even) to the activation type.
+ */
+#ifndef QGEMM_H_
+#define QGEMM_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#define QG_API __attribute__((visibility("default")))
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { QG_OK = 0, QG_EINVAL = -1, QG_EUNSUPPORTED = -2, QG_EHIP = -3 } qg_status;
+typedef enum { QG_UINT = 0, QG_INT = 1, QG_FLOAT = 2 } qg_kind;
+typedef enum { QG_F16 = 0, QG_BF16 = 1 } qg_dtype;      /* activation / scale dtype */
+
+/* Weight type.  uint/int: bits in 1..8, ebits = mbits = 0.  float: 1 + ebits +
+ * mbits == bits; supported splits are the paper's representative set
+ * e1m1, e2m1, e2m2, e3m2, e3m3, e4m3 (Section "Arbitrary Data Type Support"). */
+typedef struct { int32_t kind, bits, ebits, mbits; } qg_wtype;
+
+/* The one device layout implemented.  W is cut into tiles of 128 (K) x 64 (N)
+ * codes; a tile is 1024*bits bytes, read by one 64-lane wavefront as `bits`
+ * 16-byte loads per lane, and the lane's 16*bits bytes hold exactly the 128
+ * codes that lane feeds to the 16x16x32 matrix instruction (no exchange between
+ * lanes, no staging through LDS).  Tiles of one 64-column strip are contiguous
+ * along K.  intk codes are stored offset-binary (sign bit flipped). */
+#define QG_LAYOUT_TILE128x64 0
+#define QG_TILE_K 128
+#define QG_TILE_N 64
+
+QG_API const char* qg_status_string(int status);
+/* Text of the last HIP error seen by this library on the calling thread. */
+QG_API const char* qg_last_error(void);
+
+/* ceil(count*bits/8): bytes of the canonical little-endian bit stream. */
+QG_API size_t qg_canonical_bytes(int bits, int64_t count);
+
+/* Bytes of the device layout for a [K,N] weight (== K*N*bits/8), or 0 if the
+ * shape is not tileable (K % 128, N % 64) or the type is invalid. */
+QG_API size_t qgemm_packed_bytes(qg_wtype t, int layout, int64_t K, int64_t N);
+
+/* codes[count] (one code per byte, low `bits` bits) -> canonical stream:
+ * element e occupies stream bits [e*bits, (e+1)*bits), stream bit j is bit
+ * (j mod 8) of byte (j div 8).  `stream_out` must hold qg_canonical_bytes()
+ * bytes; pad bits are written as zero.  QG_EINVAL on bad bits / null. */
+QG_API int qg_pack_codes(const uint8_t* codes, int bits, int64_t count, uint8_t* stream_out, void* stream);
+
+/* Canonical row-major [K,N] stream -> device layout.  `packed_out` must hold
+ * qgemm_packed_bytes() bytes and must not alias the input.  QG_EINVAL on a
+ * non-tileable shape, bad type or layout, null pointers. */
+QG_API int repack(const void* canonical, qg_wtype t, int layout, int64_t K, int64_t N,
+           void* packed_out, void* stream);
+
+/* W_out[K,N] (row-major, `act` dtype) = rounded de-quantised weights.
+ *   scales [K/group, N] row-major, dtype `scale_dtype`
+ *   zeros  [K/group, N] row-major uint8, or NULL for zero-point 0
+ *   group  rows of W per scale: a multiple of 32 that divides 128 or is a
+ *          multiple of 128, dividing K (K itself = one scale per column)
+ * QG_EINVAL on shape/group violations, QG_EUNSUPPORTED on an unsupported
+ * float split. */
+QG_API int qdequant(const void* packed_W, const void* scales, const uint8_t* zeros, qg_wtype t,
+             int layout, int act, int scale_dtype, int64_t group, int64_t K, int64_t N,
+             void* W_out, void* stream);
+
+/* C[M,N] (row-major, `act`) = A[M,K] (row-major, `act`) . dequant(W).
+ * Arguments as for qdequant; M >= 1 is arbitrary, C is overwritten.
+ * Path choice (by M) is internal: M <= 64 streams the weights once through
+ * a split-K wavefront-per-tile kernel; larger M uses the LDS-staged tiled
+ * kernel. */
+QG_API int qgemm(const void* A, const void* packed_W, const void* scales, const uint8_t* zeros,
+          qg_wtype t, int layout, int act, int scale_dtype, int64_t group,
+          int64_t M, int64_t N, int64_t K, void* C, void* stream);
+
+/* Optional: path/tuning override for experiments (0 = automatic).  Returns the
+ * previous value.  knob 0: forced path (1 = small-M kernel, 2 = tiled kernel);
+ * knob 1: forced split-K factor of the small-M kernel. */
+QG_API int qg_set_knob(int knob, int value);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* QGEMM_H_ */

@@ -1,0 +1,162 @@
+"""ctypes binding of libqgemm.so -- argument marshalling only.
+
+Every function has the name and argument order of its C entry point in
+include/qgemm.h and takes torch CUDA tensors where the C call takes device
+pointers.  Work is enqueued on torch's current stream.  There is no fallback:
+if the library has not been built, importing this module raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libqgemm.so")
+
+QG_OK, QG_EINVAL, QG_EUNSUPPORTED, QG_EHIP = 0, -1, -2, -3
+QG_UINT, QG_INT, QG_FLOAT = 0, 1, 2
+QG_F16, QG_BF16 = 0, 1
+QG_LAYOUT_TILE128x64 = 0
+TILE_K, TILE_N = 128, 64
+
+EXPORTS = ("qg_status_string", "qg_last_error", "qg_canonical_bytes", "qgemm_packed_bytes",
+           "qg_pack_codes", "repack", "qdequant", "qgemm", "qg_set_knob")
+
+
+class QgWType(ctypes.Structure):
+    _fields_ = [("kind", ctypes.c_int32), ("bits", ctypes.c_int32),
+                ("ebits", ctypes.c_int32), ("mbits", ctypes.c_int32)]
+
+
+@dataclass(frozen=True)
+class WType:
+    kind: int
+    bits: int
+    ebits: int = 0
+    mbits: int = 0
+
+    def c(self) -> QgWType:
+        return QgWType(self.kind, self.bits, self.ebits, self.mbits)
+
+
+class QgError(RuntimeError):
+    def __init__(self, fn: str, status: int):
+        self.status = status
+        msg = _lib.qg_status_string(status).decode()
+        if status == QG_EHIP:
+            msg += " (" + _lib.qg_last_error().decode() + ")"
+        super().__init__(f"{fn}: {msg} [{status}]")
+
+
+def _load() -> ctypes.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_2504_12984_amd.build` "
+            "(there is no CPU fallback)")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i32, i64, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_size_t
+    lib.qg_status_string.restype = ctypes.c_char_p
+    lib.qg_status_string.argtypes = [i32]
+    lib.qg_last_error.restype = ctypes.c_char_p
+    lib.qg_last_error.argtypes = []
+    lib.qg_canonical_bytes.restype = sz
+    lib.qg_canonical_bytes.argtypes = [i32, i64]
+    lib.qgemm_packed_bytes.restype = sz
+    lib.qgemm_packed_bytes.argtypes = [QgWType, i32, i64, i64]
+    lib.qg_pack_codes.restype = i32
+    lib.qg_pack_codes.argtypes = [vp, i32, i64, vp, vp]
+    lib.repack.restype = i32
+    lib.repack.argtypes = [vp, QgWType, i32, i64, i64, vp, vp]
+    lib.qdequant.restype = i32
+    lib.qdequant.argtypes = [vp, vp, vp, QgWType, i32, i32, i32, i64, i64, i64, vp, vp]
+    lib.qgemm.restype = i32
+    lib.qgemm.argtypes = [vp, vp, vp, vp, QgWType, i32, i32, i32, i64, i64, i64, i64, vp, vp]
+    lib.qg_set_knob.restype = i32
+    lib.qg_set_knob.argtypes = [i32, i32]
+    return lib
+
+
+_lib = _load()
+
+_DT = {torch.float16: QG_F16, torch.bfloat16: QG_BF16}
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _ptr(t, name):
+    if t is None:
+        return None
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.is_contiguous()):
+        raise ValueError(f"{name} must be a contiguous CUDA tensor")
+    return t.data_ptr()
+
+
+def _check(fn, rc):
+    if rc != QG_OK:
+        raise QgError(fn, rc)
+
+
+def qg_canonical_bytes(bits: int, count: int) -> int:
+    return _lib.qg_canonical_bytes(bits, count)
+
+
+def qgemm_packed_bytes(t: WType, K: int, N: int, layout: int = QG_LAYOUT_TILE128x64) -> int:
+    return _lib.qgemm_packed_bytes(t.c(), layout, K, N)
+
+
+def qg_pack_codes(codes: torch.Tensor, bits: int) -> torch.Tensor:
+    """uint8 codes (any shape, row-major) -> canonical bit stream (uint8, 1-D)."""
+    if codes.dtype != torch.uint8:
+        raise ValueError("codes must be uint8")
+    count = codes.numel()
+    out = torch.empty(max(qg_canonical_bytes(bits, count), 1), dtype=torch.uint8, device=codes.device)
+    _check("qg_pack_codes", _lib.qg_pack_codes(_ptr(codes, "codes"), bits, count, _ptr(out, "out"), _stream()))
+    return out[:qg_canonical_bytes(bits, count)]
+
+
+def repack(canonical: torch.Tensor, t: WType, K: int, N: int, layout: int = QG_LAYOUT_TILE128x64) -> torch.Tensor:
+    """canonical [K,N] stream -> device layout (uint8, 1-D)."""
+    nbytes = qgemm_packed_bytes(t, K, N, layout)
+    if nbytes == 0:
+        raise QgError("qgemm_packed_bytes", QG_EINVAL)
+    if canonical.dtype != torch.uint8 or canonical.numel() < qg_canonical_bytes(t.bits, K * N):
+        raise ValueError("canonical stream too short or not uint8")
+    out = torch.empty(nbytes, dtype=torch.uint8, device=canonical.device)
+    _check("repack", _lib.repack(_ptr(canonical, "canonical"), t.c(), layout, K, N, _ptr(out, "out"), _stream()))
+    return out
+
+
+def qdequant(packed: torch.Tensor, scales: torch.Tensor, zeros, t: WType, act: torch.dtype,
+             group: int, K: int, N: int, layout: int = QG_LAYOUT_TILE128x64) -> torch.Tensor:
+    out = torch.empty((K, N), dtype=act, device=packed.device)
+    rc = _lib.qdequant(_ptr(packed, "packed"), _ptr(scales, "scales"), _ptr(zeros, "zeros"), t.c(), layout,
+                       _DT[act], _DT[scales.dtype], group, K, N, _ptr(out, "out"), _stream())
+    _check("qdequant", rc)
+    return out
+
+
+def qgemm(A: torch.Tensor, packed: torch.Tensor, scales: torch.Tensor, zeros, t: WType, group: int,
+          N: int, out: torch.Tensor | None = None, layout: int = QG_LAYOUT_TILE128x64) -> torch.Tensor:
+    """C[M,N] = A[M,K] . dequant(W); dtype of A is the activation dtype."""
+    if A.dim() != 2 or A.dtype not in _DT:
+        raise ValueError("A must be [M,K] fp16 or bf16")
+    M, K = A.shape
+    if scales.dtype not in _DT or tuple(scales.shape) != (K // group, N):
+        raise ValueError("scales must be [K/group, N] fp16 or bf16")
+    if zeros is not None and (zeros.dtype != torch.uint8 or tuple(zeros.shape) != (K // group, N)):
+        raise ValueError("zeros must be uint8 [K/group, N]")
+    if out is None:
+        out = torch.empty((M, N), dtype=A.dtype, device=A.device)
+    rc = _lib.qgemm(_ptr(A, "A"), _ptr(packed, "packed"), _ptr(scales, "scales"), _ptr(zeros, "zeros"), t.c(),
+                    layout, _DT[A.dtype], _DT[scales.dtype], group, M, N, K, _ptr(out, "C"), _stream())
+    _check("qgemm", rc)
+    return out
+
+
+def qg_set_knob(knob: int, value: int) -> int:
+    return _lib.qg_set_knob(knob, value)

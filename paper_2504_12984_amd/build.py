@@ -1,0 +1,69 @@
+"""Build libqgemm.so for gfx950 with hipcc (cross-compiles without a GPU).
+
+    python -m paper_2504_12984_amd.build [-j N]
+
+Per-weight-type sources (de-quantiser, small-M and tiled matmul kernels) are
+compiled once per weight type, in parallel, then linked into one shared library
+next to this file.  Objects go to _build/ (not tracked).
+"""
+from __future__ import annotations
+
+import os
+import subprocess
+import sys
+from concurrent.futures import ThreadPoolExecutor
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+CSRC = os.path.join(HERE, "csrc")
+OBJ = os.path.join(HERE, "_build")
+LIB = os.path.join(HERE, "libqgemm.so")
+NUM_WT = 14
+HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+FLAGS = ["--offload-arch=gfx950", "-std=c++20", "-O3", "-fPIC", "-fvisibility=hidden",
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         "-Wno-unused-command-line-argument"]
+
+
+def _jobs():
+    jobs = [("qg_pack.hip", None), ("qg_api.hip", None)]
+    for src in ("qg_dequant.hip", "qg_small.hip", "qg_large.hip"):
+        jobs += [(src, wt) for wt in range(NUM_WT)]
+    return jobs
+
+
+def _compile(job):
+    src, wt = job
+    stem = src[:-4] + ("" if wt is None else f"_wt{wt}")
+    obj = os.path.join(OBJ, stem + ".o")
+    cmd = [HIPCC, *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+    if wt is not None:
+        cmd.insert(-4, f"-DQG_WT={wt}")
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    err = "\n".join(ln for ln in r.stderr.splitlines() if "packed-fp32-ops" not in ln)
+    if r.returncode != 0:
+        raise RuntimeError(f"hipcc failed for {stem}:\n{err}")
+    return obj, err
+
+
+def build(jobs: int | None = None, verbose: bool = True) -> str:
+    os.makedirs(OBJ, exist_ok=True)
+    jobs = jobs or min(8, os.cpu_count() or 1)
+    with ThreadPoolExecutor(max_workers=jobs) as ex:
+        results = list(ex.map(_compile, _jobs()))
+    objs = [o for o, _ in results]
+    if verbose:
+        for _, err in results:
+            if err.strip():
+                print(err, file=sys.stderr)
+    cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("link failed:\n" + r.stderr)
+    return LIB
+
+
+if __name__ == "__main__":
+    n = None
+    if "-j" in sys.argv:
+        n = int(sys.argv[sys.argv.index("-j") + 1])
+    print(build(n))

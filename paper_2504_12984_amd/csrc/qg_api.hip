@@ -1,0 +1,227 @@
+// C ABI of the library: argument checks, kernel choice, workspace.  No compute
+// happens on the host.
+#include <mutex>
+#include <string>
+
+#include "qg_common.h"
+
+namespace qg {
+
+int launch_pack_codes(const uint8_t*, int, int64_t, uint8_t*, hipStream_t);
+int launch_repack(const uint8_t*, int, int, int, uint32_t, uint8_t*, hipStream_t);
+
+#define QG_FOR_ALL_WT(X) X(0) X(1) X(2) X(3) X(4) X(5) X(6) X(7) X(8) X(9) X(10) X(11) X(12) X(13)
+
+#define QG_DECL(i)                                                            \
+  int dequant_launch_wt##i(const DequantParams&, int, hipStream_t);           \
+  int small_launch_wt##i(const GemmParams&, int, int, hipStream_t);           \
+  int large_launch_wt##i(const GemmParams&, int, int, hipStream_t);
+QG_FOR_ALL_WT(QG_DECL)
+#undef QG_DECL
+
+typedef int (*dq_fn)(const DequantParams&, int, hipStream_t);
+typedef int (*gm_fn)(const GemmParams&, int, int, hipStream_t);
+#define QG_ENT(i) dequant_launch_wt##i,
+static const dq_fn kDequant[NUM_WT] = {QG_FOR_ALL_WT(QG_ENT)};
+#undef QG_ENT
+#define QG_ENT(i) small_launch_wt##i,
+static const gm_fn kSmall[NUM_WT] = {QG_FOR_ALL_WT(QG_ENT)};
+#undef QG_ENT
+#define QG_ENT(i) large_launch_wt##i,
+static const gm_fn kLarge[NUM_WT] = {QG_FOR_ALL_WT(QG_ENT)};
+#undef QG_ENT
+
+static thread_local std::string g_last_error;
+static int g_knob[4] = {0, 0, 0, 0};
+
+static int hip_fail(hipError_t e, const char* what) {
+  g_last_error = std::string(what) + ": " + hipGetErrorString(e);
+  return QG_EHIP;
+}
+
+// ---- per-device split-K workspace (partial sums + arrival counters) ------------
+struct Workspace {
+  float* partial = nullptr;
+  size_t partial_bytes = 0;
+  unsigned* tickets = nullptr;
+  size_t ticket_count = 0;
+};
+static std::mutex g_ws_mutex;
+static Workspace g_ws[64];
+
+static int get_workspace(size_t partial_bytes, size_t ticket_count, hipStream_t st, Workspace** out) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
+  if (dev < 0 || dev >= 64) return QG_EINVAL;
+  std::lock_guard<std::mutex> lock(g_ws_mutex);
+  Workspace& w = g_ws[dev];
+  if (w.partial_bytes < partial_bytes) {
+    // work already enqueued may still read the old buffer
+    if (w.partial) { e = hipDeviceSynchronize(); if (e != hipSuccess) return hip_fail(e, "hipDeviceSynchronize"); (void)hipFree(w.partial); w.partial = nullptr; w.partial_bytes = 0; }
+    size_t want = partial_bytes < (size_t(8) << 20) ? (size_t(8) << 20) : partial_bytes;
+    e = hipMalloc(&w.partial, want);
+    if (e != hipSuccess) return hip_fail(e, "hipMalloc(workspace)");
+    w.partial_bytes = want;
+  }
+  if (w.ticket_count < ticket_count) {
+    if (w.tickets) { e = hipDeviceSynchronize(); if (e != hipSuccess) return hip_fail(e, "hipDeviceSynchronize"); (void)hipFree(w.tickets); w.tickets = nullptr; w.ticket_count = 0; }
+    size_t want = ticket_count < 65536 ? 65536 : ticket_count;
+    e = hipMalloc(&w.tickets, want * sizeof(unsigned));
+    if (e != hipSuccess) return hip_fail(e, "hipMalloc(tickets)");
+    // counters start at zero; every kernel that uses them leaves them at zero
+    e = hipMemsetAsync(w.tickets, 0, want * sizeof(unsigned), st);
+    if (e != hipSuccess) return hip_fail(e, "hipMemsetAsync(tickets)");
+    e = hipStreamSynchronize(st);
+    if (e != hipSuccess) return hip_fail(e, "hipStreamSynchronize");
+    w.ticket_count = want;
+  }
+  *out = &w;
+  return QG_OK;
+}
+
+static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+static int check_common(qg_wtype t, int layout, int act, int scale_dtype, int64_t group, int64_t K, int64_t N,
+                        int* wt_out, int* route_out) {
+  if (layout != QG_LAYOUT_TILE128x64) return QG_EINVAL;
+  int wt = wt_index(t);
+  if (wt == -2) return QG_EUNSUPPORTED;
+  if (wt < 0) return QG_EINVAL;
+  if (K <= 0 || N <= 0 || K % TILE_K || N % TILE_N || K > (1 << 24) || N > (1 << 24)) return QG_EINVAL;
+  if (group <= 0 || K % group) return QG_EINVAL;
+  if (!((group % TILE_K) == 0 || group == 64)) return (group % 32 == 0 && TILE_K % group == 0) ? QG_EUNSUPPORTED : QG_EINVAL;
+  if ((act != QG_F16 && act != QG_BF16) || (scale_dtype != QG_F16 && scale_dtype != QG_BF16)) return QG_EINVAL;
+  if (act == QG_F16 && scale_dtype == QG_BF16) return QG_EUNSUPPORTED;
+  *wt_out = wt;
+  *route_out = (act == QG_F16) ? ROUTE_F16 : ROUTE_BF16;
+  return QG_OK;
+}
+
+}  // namespace qg
+
+using namespace qg;
+
+extern "C" {
+
+const char* qg_status_string(int status) {
+  switch (status) {
+    case QG_OK: return "ok";
+    case QG_EINVAL: return "invalid argument";
+    case QG_EUNSUPPORTED: return "valid request with no kernel";
+    case QG_EHIP: return "HIP runtime error";
+    default: return "unknown status";
+  }
+}
+
+const char* qg_last_error(void) { return g_last_error.c_str(); }
+
+size_t qg_canonical_bytes(int bits, int64_t count) {
+  if (bits < 1 || bits > 8 || count < 0) return 0;
+  return (size_t)((count * bits + 7) / 8);
+}
+
+size_t qgemm_packed_bytes(qg_wtype t, int layout, int64_t K, int64_t N) {
+  if (layout != QG_LAYOUT_TILE128x64 || wt_index(t) == -1) return 0;
+  if (K <= 0 || N <= 0 || K % TILE_K || N % TILE_N) return 0;
+  return (size_t)(K * N * t.bits / 8);
+}
+
+int qg_pack_codes(const uint8_t* codes, int bits, int64_t count, uint8_t* stream_out, void* stream) {
+  if (bits < 1 || bits > 8 || count < 0) return QG_EINVAL;
+  if (count == 0) return QG_OK;
+  if (!codes || !stream_out) return QG_EINVAL;
+  return launch_pack_codes(codes, bits, count, stream_out, static_cast<hipStream_t>(stream));
+}
+
+int repack(const void* canonical, qg_wtype t, int layout, int64_t K, int64_t N, void* packed_out, void* stream) {
+  if (layout != QG_LAYOUT_TILE128x64) return QG_EINVAL;
+  int wt = wt_index(t);
+  if (wt == -1) return QG_EINVAL;   // any float split can be re-laid out; only the type must be well formed
+  if (!canonical || !packed_out || canonical == packed_out) return QG_EINVAL;
+  if (K <= 0 || N <= 0 || K % TILE_K || N % TILE_N || K > (1 << 24) || N > (1 << 24)) return QG_EINVAL;
+  if (!aligned16(packed_out)) return QG_EINVAL;
+  uint32_t flip = (t.kind == QG_INT) ? (1u << (t.bits - 1)) : 0u;
+  return launch_repack(static_cast<const uint8_t*>(canonical), t.bits, (int)K, (int)N, flip,
+                       static_cast<uint8_t*>(packed_out), static_cast<hipStream_t>(stream));
+}
+
+int qdequant(const void* packed_W, const void* scales, const uint8_t* zeros, qg_wtype t, int layout, int act,
+             int scale_dtype, int64_t group, int64_t K, int64_t N, void* W_out, void* stream) {
+  int wt, route;
+  int rc = check_common(t, layout, act, scale_dtype, group, K, N, &wt, &route);
+  if (rc != QG_OK) return rc;
+  if (!packed_W || !scales || !W_out) return QG_EINVAL;
+  if (!aligned16(packed_W) || !aligned16(scales) || !aligned16(W_out) || (zeros && !aligned16(zeros))) return QG_EINVAL;
+  DequantParams p;
+  p.W = static_cast<const uint8_t*>(packed_W);
+  p.S = static_cast<const uint16_t*>(scales);
+  p.Z = zeros;
+  p.out = static_cast<uint16_t*>(W_out);
+  p.K = (int)K; p.N = (int)N; p.group = (int)group;
+  p.zbias = (t.kind == QG_INT) ? (1 << (t.bits - 1)) : 0;
+  p.scale_bf16 = (scale_dtype == QG_BF16);
+  return kDequant[wt](p, route, static_cast<hipStream_t>(stream));
+}
+
+int qgemm(const void* A, const void* packed_W, const void* scales, const uint8_t* zeros, qg_wtype t, int layout,
+          int act, int scale_dtype, int64_t group, int64_t M, int64_t N, int64_t K, void* C, void* stream) {
+  int wt, route;
+  int rc = check_common(t, layout, act, scale_dtype, group, K, N, &wt, &route);
+  if (rc != QG_OK) return rc;
+  if (M < 0 || M > (1 << 24)) return QG_EINVAL;
+  if (M == 0) return QG_OK;
+  if (!A || !packed_W || !scales || !C) return QG_EINVAL;
+  if (!aligned16(A) || !aligned16(packed_W) || !aligned16(scales) || !aligned16(C) || (zeros && !aligned16(zeros))) return QG_EINVAL;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+
+  GemmParams p;
+  p.A = static_cast<const uint16_t*>(A);
+  p.W = static_cast<const uint8_t*>(packed_W);
+  p.S = static_cast<const uint16_t*>(scales);
+  p.Z = zeros;
+  p.C = static_cast<uint16_t*>(C);
+  p.ws = nullptr; p.tickets = nullptr;
+  p.M = (int)M; p.N = (int)N; p.K = (int)K; p.group = (int)group;
+  p.zbias = (t.kind == QG_INT) ? (1 << (t.bits - 1)) : 0;
+  p.scale_bf16 = (scale_dtype == QG_BF16);
+  p.splitk = 1; p.chunks_per_split = (int)(K / TILE_K);
+
+  int path = g_knob[0];
+  if (path == 0) path = (M <= 64) ? 1 : 2;
+  if (path == 1 && M > 64) return QG_EINVAL;
+
+  if (path == 1) {
+    const int mt = M <= 16 ? 1 : (M <= 32 ? 2 : 4);
+    const int KC = (int)(K / TILE_K), NCH = (int)(N / TILE_N);
+    // split K over workgroups until the grid fills the chip (256 CUs) a few
+    // times over, keeping at least 2 chunks per wavefront (8 wavefronts per WG)
+    int splitk = g_knob[1];
+    if (splitk <= 0) {
+      splitk = 1;
+      while (NCH * splitk < 1024 && KC / (splitk * 2) >= 16) splitk *= 2;
+    }
+    if (splitk > KC) splitk = KC;
+    int cps = (KC + splitk - 1) / splitk;
+    splitk = (KC + cps - 1) / cps;
+    p.splitk = splitk; p.chunks_per_split = cps;
+    if (splitk > 1) {
+      Workspace* w = nullptr;
+      size_t pbytes = (size_t)splitk * NCH * (size_t)(mt * 16 * TILE_N) * sizeof(float);
+      rc = get_workspace(pbytes, (size_t)NCH, st, &w);
+      if (rc != QG_OK) return rc;
+      p.ws = w->partial; p.tickets = w->tickets;
+    }
+    return kSmall[wt](p, route, mt, st);
+  }
+  return kLarge[wt](p, route, g_knob[2], st);
+}
+
+int qg_set_knob(int knob, int value) {
+  if (knob < 0 || knob >= 4) return 0;
+  int old = g_knob[knob];
+  g_knob[knob] = value;
+  return old;
+}
+
+}  // extern "C"

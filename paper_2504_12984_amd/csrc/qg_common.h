@@ -1,0 +1,97 @@
+// Shared host/device definitions of the gfx950 quantised-matmul library.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/qgemm.h"
+
+namespace qg {
+
+// ---- the device layout ------------------------------------------------------
+// W[K,N] is cut into tiles ("chunks") of 128 (K) x 64 (N) codes.  One chunk is
+// read by one wavefront as BITS loads of 16 bytes per lane:
+//     load i, lane l  ->  bytes [i*1024 + l*16, +16) of the chunk
+// so a lane owns RAW = 4*BITS dwords r[0..RAW) = 128 codes, as 64 (lo, hi) pairs.
+// Pair t sits in two parallel 16-bit streams: the lo code occupies bits
+// [t*BITS, (t+1)*BITS) of the stream made of the LOW halves of r[0], r[1], ...,
+// the hi code the same bits of the stream made of the HIGH halves.  A single
+// mask operation therefore extracts both codes of a pair at once, already in
+// the two 16-bit lanes of the register the matrix instruction reads.
+//
+// Which element a pair is:   t = (j*4 + nt)*4 + v
+//     j  in 0..3   k-step of 32 inside the chunk
+//     nt in 0..3   16-column sub-tile
+//     v  in 0..3   register of the 4-register (8-element) MFMA operand
+// lane l = 16*b + i (b = k-block 0..3, i = 0..15):
+//     k = 128*kc + 32*j + 8*b + 2*v + {0 (lo), 1 (hi)}
+//     n = 64*nc + 4*i + nt
+// Chunks of one 64-column strip are contiguous along K:
+//     byte offset of chunk (kc, nc) = (nc * (K/128) + kc) * 1024 * BITS
+// This is the paper's "reinterpret each tile as the bytes each thread loads and
+// store the tile contiguously" (Section "Efficient Low-Precision Weight
+// Loading"), with T = 64 lanes and n = 16*BITS bytes per lane, so n1 = 16.
+constexpr int TILE_K = QG_TILE_K;
+constexpr int TILE_N = QG_TILE_N;
+constexpr int PAIRS = 64;
+
+// ---- weight-type index used to pick a kernel instantiation ---------------------
+// 0..7   integer codes of 1..8 bits (uintk; intk is stored offset-binary and
+//        differs only by a constant added to the zero-point)
+// 8..13  floats e1m1, e2m1, e2m2, e3m2, e3m3, e4m3 (3..8 bits)
+constexpr int NUM_WT = 14;
+
+__host__ __device__ constexpr int wt_bits(int wt) { return wt < 8 ? wt + 1 : wt - 8 + 3; }
+__host__ __device__ constexpr bool wt_is_float(int wt) { return wt >= 8; }
+__host__ __device__ constexpr int wt_ebits(int wt) {
+  return wt == 8 ? 1 : wt == 9 ? 2 : wt == 10 ? 2 : wt == 11 ? 3 : wt == 12 ? 3 : wt == 13 ? 4 : 0;
+}
+__host__ __device__ constexpr int wt_mbits(int wt) { return wt < 8 ? 0 : wt_bits(wt) - 1 - wt_ebits(wt); }
+
+inline int wt_index(const qg_wtype& t) {
+  if (t.bits < 1 || t.bits > 8) return -1;
+  if (t.kind == QG_UINT || t.kind == QG_INT) return (t.ebits == 0 && t.mbits == 0) ? t.bits - 1 : -1;
+  if (t.kind == QG_FLOAT) {
+    if (t.bits < 3 || 1 + t.ebits + t.mbits != t.bits || t.ebits < 1) return -1;
+    int wt = 8 + t.bits - 3;
+    return (wt_ebits(wt) == t.ebits) ? wt : -2;   // -2: valid split, no kernel
+  }
+  return -1;
+}
+
+// Rounding routes of the de-quantiser.
+//   ROUTE_F16  activations fp16, scales fp16: exact packed-half subtract, one
+//              packed-half multiply (rounds once, to nearest even)
+//   ROUTE_BF16 activations bf16, scales fp16 or bf16: exact fp32 product
+//              through fused multiply-add, one hardware fp32->bf16 rounding
+constexpr int ROUTE_F16 = 0;
+constexpr int ROUTE_BF16 = 1;
+constexpr int NUM_ROUTE = 2;
+
+struct DequantParams {
+  const uint8_t* W;
+  const uint16_t* S;
+  const uint8_t* Z;
+  uint16_t* out;
+  int K, N, group;
+  int zbias;        // added to every zero-point (2^(bits-1) for intk, else 0)
+  int scale_bf16;   // scales are bf16 (only with ROUTE_BF16)
+};
+
+struct GemmParams {
+  const uint16_t* A;
+  const uint8_t* W;
+  const uint16_t* S;
+  const uint8_t* Z;
+  uint16_t* C;
+  float* ws;            // split-K partial sums
+  unsigned* tickets;    // one arrival counter per output tile, zero between calls
+  int M, N, K, group;
+  int zbias, scale_bf16;
+  int splitk;           // number of K-slabs (grid.y)
+  int chunks_per_split; // K-chunks per slab (last slab may be shorter)
+};
+
+typedef int (*dequant_launch_fn)(const DequantParams&, hipStream_t);
+typedef int (*gemm_launch_fn)(const GemmParams&, int mt, hipStream_t);
+
+}  // namespace qg

@@ -1,0 +1,252 @@
+// In-register unpack + de-quantise of one lane's share of a weight chunk.
+//
+// This is the "reinterpret, then vectorised cast" half of the paper's weight
+// pipeline (Sections "Key Ideas" steps 3-4 and "Efficient Casting"): the bytes
+// a lane loaded ARE its codes, and turning them into fp16/bf16 MFMA operands
+// uses only shifts, masks and packed arithmetic inside the lane -- no exchange
+// with other lanes and no trip through LDS.  The instruction choices below are
+// gfx950's (v_and_or_b32, packed-half add/mul, v_fma_mix_f32, v_cvt_pk_bf16_f32)
+// rather than the PRMT/LOP3 sequences the paper uses on NVIDIA hardware.
+#pragma once
+#include "qg_common.h"
+
+namespace qg {
+
+typedef _Float16 h2_t __attribute__((ext_vector_type(2)));
+typedef __bf16 b2_t __attribute__((ext_vector_type(2)));
+typedef float f2_t __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ uint32_t u32(h2_t v) { return __builtin_bit_cast(uint32_t, v); }
+__device__ __forceinline__ h2_t as_h2(uint32_t v) { return __builtin_bit_cast(h2_t, v); }
+
+// (a & mask) | orv in one VALU op.  The mask lives in a scalar register, the
+// OR operand in a vector register (gfx9 VOP3 reads at most one scalar).
+__device__ __forceinline__ uint32_t and_or(uint32_t a, uint32_t mask, uint32_t orv) {
+  uint32_t d;
+  asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(d) : "v"(a), "s"(mask), "v"(orv));
+  return d;
+}
+
+template <int S>
+__device__ __forceinline__ uint32_t shr(uint32_t x) {
+  if constexpr (S == 0) return x;
+  else return x >> S;
+}
+// shift left for S > 0, right for S < 0
+template <int S>
+__device__ __forceinline__ uint32_t shl_signed(uint32_t x) {
+  if constexpr (S == 0) return x;
+  else if constexpr (S > 0) return x << S;
+  else return x >> (-S);
+}
+
+// ---- where pair t lives in the lane's two 16-bit streams -----------------------
+template <int BITS>
+struct Lay {
+  static constexpr int RAW = 4 * BITS;
+  // number of codes taken from one shifted view of a register: their bits must
+  // fit below bit 10 (the fp16 mantissa), capped at 4 to bound the constants
+  static constexpr int WN = (10 / BITS) > 4 ? 4 : (10 / BITS);
+  static constexpr uint32_t CODE = (1u << BITS) - 1u;
+};
+
+template <int BITS, int T>
+struct Pos {
+  static constexpr int bit = T * BITS;
+  static constexpr int h = bit >> 4;                 // register index
+  static constexpr int p = bit & 15;                 // offset inside each 16-bit half
+  static constexpr bool straddle = (p + BITS > 16);  // spills into register h+1
+  static constexpr int n1 = 16 - p;                  // bits in register h when straddling
+  static constexpr int p0 = (BITS - (16 * h) % BITS) % BITS;  // first code starting in h
+  static constexpr int idx = (p - p0) / BITS;
+  static constexpr int WN = Lay<BITS>::WN;
+  static constexpr int widx = straddle ? 0 : idx % WN;         // position inside the view
+  static constexpr int s = straddle ? p : p0 + (idx / WN) * WN * BITS;  // view shift
+  static constexpr int pp = widx * BITS;                       // offset inside the view
+  static_assert(straddle || (p - s == pp && pp + BITS <= 10), "window arithmetic");
+};
+
+// fp16 pattern of 2^(10-pp): OR-ing a code placed at mantissa bit pp onto it
+// gives the half-precision number 2^(10-pp) + code exactly.
+__host__ __device__ constexpr uint32_t magic16(int pp) { return (uint32_t)(25 - pp) << 10; }
+__host__ __device__ constexpr uint32_t dup16(uint32_t x) { return x | (x << 16); }
+
+// =============================== integer codes ==================================
+// Extract pair T as (2^(10-pp) + q_lo, 2^(10-pp) + q_hi) in packed fp16.
+template <int BITS, int T>
+__device__ __forceinline__ uint32_t int_pair_magic(const uint32_t (&r)[4 * BITS], const uint32_t (&magic)[Lay<BITS>::WN]) {
+  typedef Pos<BITS, T> P;
+  if constexpr (!P::straddle) {
+    return and_or(shr<P::s>(r[P::h]), dup16(Lay<BITS>::CODE << P::pp), magic[P::widx]);
+  } else {
+    constexpr int n1 = P::n1;
+    uint32_t x = and_or(shr<P::p>(r[P::h]), dup16((1u << n1) - 1u), magic[0]);
+    return and_or(r[P::h + 1] << n1, dup16(Lay<BITS>::CODE & ~((1u << n1) - 1u)), x);
+  }
+}
+
+// ================================ float codes ===================================
+// Extract pair T as raw fp16 patterns sign | E (low-aligned in the 5-bit
+// exponent field) | M (top-aligned in the mantissa).  The true value is that
+// half-precision number times 2^(15 - bias), applied by the caller.
+template <int BITS, int EB, int MB, int T>
+__device__ __forceinline__ uint32_t float_pair_raw(const uint32_t (&r)[4 * BITS]) {
+  typedef Pos<BITS, T> P;
+  constexpr uint32_t MAGMASK = dup16(((1u << (BITS - 1)) - 1u) << (10 - MB));
+  constexpr uint32_t SIGN = 0x80008000u;
+  if constexpr (!P::straddle) {
+    uint32_t mag = shl_signed<(10 - MB) - P::p>(r[P::h]) & MAGMASK;
+    return and_or(r[P::h] << (16 - P::p - BITS), SIGN, mag);
+  } else {
+    constexpr int n1 = P::n1;
+    uint32_t y = (r[P::h] >> P::p) & dup16((1u << n1) - 1u);
+    y = and_or(r[P::h + 1] << n1, dup16(Lay<BITS>::CODE & ~((1u << n1) - 1u)), y);
+    uint32_t mag = (y << (10 - MB)) & MAGMASK;
+    return and_or(y << (16 - BITS), SIGN, mag);
+  }
+}
+
+// ============================ per-group constants ================================
+// sraw: the lane's four 16-bit scales (columns 4*i + 0..3), zraw: its four
+// zero-point bytes.  Built once per (chunk, group), used by 8 or 16 pairs each.
+template <int WT, int ROUTE>
+struct Decoder;
+
+// ---- integers, fp16 route:  w = ((2^e + q) - (2^e + z')) * s ------------------
+template <int WT>
+struct Decoder<WT, ROUTE_F16> {
+  static constexpr int BITS = wt_bits(WT);
+  static constexpr bool IS_FLOAT = wt_is_float(WT);
+  static constexpr int EB = wt_ebits(WT), MB = wt_mbits(WT);
+  static constexpr int WN = Lay<BITS>::WN;
+  static constexpr int RAW = 4 * BITS;
+
+  struct Consts {
+    h2_t s[4];
+    h2_t c[WN][4];   // integers: 2^(10-pp) + z'   (floats: unused)
+  };
+  struct Uniform {
+    uint32_t magic[WN];
+    __device__ __forceinline__ void init() {
+#pragma unroll
+      for (int w = 0; w < WN; ++w) magic[w] = dup16(magic16(w * BITS));
+    }
+  };
+
+  static __device__ __forceinline__ void make_consts(Consts& gc, uint2 sraw, uint32_t zraw, int zbias, int /*scale_bf16*/) {
+    uint32_t sw[2] = {sraw.x, sraw.y};
+#pragma unroll
+    for (int nt = 0; nt < 4; ++nt) {
+      uint32_t s16 = (nt & 1) ? (sw[nt >> 1] >> 16) : (sw[nt >> 1] & 0xffffu);
+      gc.s[nt] = as_h2(s16 | (s16 << 16));
+      if constexpr (!IS_FLOAT) {
+        uint32_t z = ((zraw >> (8 * nt)) & 0xffu) + (uint32_t)zbias;   // < 1024
+        h2_t c0 = as_h2(dup16(0x6400u) | z | (z << 16));               // 1024 + z', exact
+        gc.c[0][nt] = c0;
+#pragma unroll
+        for (int w = 1; w < WN; ++w) {
+          const _Float16 d = (_Float16)(float)((1 << (10 - w * BITS)) - 1024);
+          gc.c[w][nt] = c0 + (h2_t){d, d};                             // exact: integers < 2048
+        }
+      }
+    }
+  }
+
+  // the four registers (8 values) lane feeds to the MFMA for k-step J, sub-tile NT
+  template <int J, int NT>
+  static __device__ __forceinline__ void frag(const uint32_t (&r)[RAW], const Consts& gc, const Uniform& u, uint32_t (&out)[4]) {
+    constexpr int T0 = (J * 4 + NT) * 4;
+    if constexpr (!IS_FLOAT) {
+      uint32_t x0 = int_pair_magic<BITS, T0 + 0>(r, u.magic);
+      uint32_t x1 = int_pair_magic<BITS, T0 + 1>(r, u.magic);
+      uint32_t x2 = int_pair_magic<BITS, T0 + 2>(r, u.magic);
+      uint32_t x3 = int_pair_magic<BITS, T0 + 3>(r, u.magic);
+      out[0] = u32((as_h2(x0) - gc.c[Pos<BITS, T0 + 0>::widx][NT]) * gc.s[NT]);
+      out[1] = u32((as_h2(x1) - gc.c[Pos<BITS, T0 + 1>::widx][NT]) * gc.s[NT]);
+      out[2] = u32((as_h2(x2) - gc.c[Pos<BITS, T0 + 2>::widx][NT]) * gc.s[NT]);
+      out[3] = u32((as_h2(x3) - gc.c[Pos<BITS, T0 + 3>::widx][NT]) * gc.s[NT]);
+    } else {
+      // value = raw * 2^(15-bias) exactly (every supported format fits fp16),
+      // then one rounding multiply by the scale
+      constexpr int ADJ = 15 - ((1 << (EB - 1)) - 1);
+      const _Float16 a = (_Float16)(float)(1 << ADJ);
+      const h2_t adj = {a, a};
+      out[0] = u32((as_h2(float_pair_raw<BITS, EB, MB, T0 + 0>(r)) * adj) * gc.s[NT]);
+      out[1] = u32((as_h2(float_pair_raw<BITS, EB, MB, T0 + 1>(r)) * adj) * gc.s[NT]);
+      out[2] = u32((as_h2(float_pair_raw<BITS, EB, MB, T0 + 2>(r)) * adj) * gc.s[NT]);
+      out[3] = u32((as_h2(float_pair_raw<BITS, EB, MB, T0 + 3>(r)) * adj) * gc.s[NT]);
+    }
+  }
+};
+
+// ---- bf16 route:  w = bf16_rne( fma(x, s, -(2^e + z') * s) ), all exact in fp32 --
+template <int WT>
+struct Decoder<WT, ROUTE_BF16> {
+  static constexpr int BITS = wt_bits(WT);
+  static constexpr bool IS_FLOAT = wt_is_float(WT);
+  static constexpr int EB = wt_ebits(WT), MB = wt_mbits(WT);
+  static constexpr int WN = Lay<BITS>::WN;
+  static constexpr int RAW = 4 * BITS;
+
+  struct Consts {
+    float s[4];       // integers: scale; floats: scale * 2^(15-bias)
+    float ncs[WN][4];  // integers: -(2^(10-pp) + z') * s, exact (<= 22 bits)
+  };
+  struct Uniform {
+    uint32_t magic[WN];
+    __device__ __forceinline__ void init() {
+#pragma unroll
+      for (int w = 0; w < WN; ++w) magic[w] = dup16(magic16(w * BITS));
+    }
+  };
+
+  static __device__ __forceinline__ void make_consts(Consts& gc, uint2 sraw, uint32_t zraw, int zbias, int scale_bf16) {
+    uint32_t sw[2] = {sraw.x, sraw.y};
+#pragma unroll
+    for (int nt = 0; nt < 4; ++nt) {
+      uint32_t s16 = (nt & 1) ? (sw[nt >> 1] >> 16) : (sw[nt >> 1] & 0xffffu);
+      float s = scale_bf16 ? __builtin_bit_cast(float, s16 << 16)
+                           : (float)__builtin_bit_cast(_Float16, (uint16_t)s16);
+      if constexpr (!IS_FLOAT) {
+        gc.s[nt] = s;
+        float z = (float)(int)(((zraw >> (8 * nt)) & 0xffu) + (uint32_t)zbias);
+#pragma unroll
+        for (int w = 0; w < WN; ++w) gc.ncs[w][nt] = -((float)(1 << (10 - w * BITS)) + z) * s;
+      } else {
+        constexpr int ADJ = 15 - ((1 << (EB - 1)) - 1);
+        gc.s[nt] = s * (float)(1 << ADJ);
+      }
+    }
+  }
+
+  static __device__ __forceinline__ uint32_t pk_bf16(float lo, float hi) {
+    f2_t f = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, b2_t));
+  }
+
+  template <int J, int NT>
+  static __device__ __forceinline__ void frag(const uint32_t (&r)[RAW], const Consts& gc, const Uniform& u, uint32_t (&out)[4]) {
+    constexpr int T0 = (J * 4 + NT) * 4;
+    if constexpr (!IS_FLOAT) {
+#define QG_ONE(V)                                                                         \
+  {                                                                                       \
+    h2_t x = as_h2(int_pair_magic<BITS, T0 + V>(r, u.magic));                            \
+    constexpr int w = Pos<BITS, T0 + V>::widx;                                            \
+    out[V] = pk_bf16(__builtin_fmaf((float)x.x, gc.s[NT], gc.ncs[w][NT]),                 \
+                     __builtin_fmaf((float)x.y, gc.s[NT], gc.ncs[w][NT]));                \
+  }
+      QG_ONE(0) QG_ONE(1) QG_ONE(2) QG_ONE(3)
+#undef QG_ONE
+    } else {
+#define QG_ONE(V)                                                                         \
+  {                                                                                       \
+    h2_t x = as_h2(float_pair_raw<BITS, EB, MB, T0 + V>(r));                             \
+    out[V] = pk_bf16((float)x.x * gc.s[NT], (float)x.y * gc.s[NT]);                       \
+  }
+      QG_ONE(0) QG_ONE(1) QG_ONE(2) QG_ONE(3)
+#undef QG_ONE
+    }
+  }
+};
+
+}  // namespace qg

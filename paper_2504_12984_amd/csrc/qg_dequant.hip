@@ -1,0 +1,67 @@
+// De-quantise the packed weight back to a row-major [K,N] fp16/bf16 matrix.
+// Same load + reinterpret + cast code as the matmul kernels (paper, Section
+// "Efficient Low-Precision Support in LLMs"); the result is written to memory so
+// that it can be compared bit for bit.  Compiled once per weight type (QG_WT).
+#include "qg_decode.h"
+#include "qg_static_for.h"
+
+#ifndef QG_WT
+#error "compile with -DQG_WT=<weight type index>"
+#endif
+
+namespace qg {
+
+template <int WT, int ROUTE>
+__global__ __launch_bounds__(256) void dequant_kernel(DequantParams p) {
+  typedef Decoder<WT, ROUTE> D;
+  constexpr int BITS = D::BITS, RAW = D::RAW;
+  const int l = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int KC = p.K / TILE_K;
+  const int64_t chunk = (int64_t)blockIdx.x * 4 + wave;
+  if (chunk >= (int64_t)KC * (p.N / TILE_N)) return;
+  const int nc = (int)(chunk / KC), kc = (int)(chunk % KC);
+  const int b = l >> 4, i16 = l & 15;
+
+  uint32_t r[RAW];
+  const uint4* src = reinterpret_cast<const uint4*>(p.W + chunk * (1024 * BITS));
+#pragma unroll
+  for (int i = 0; i < BITS; ++i) {
+    uint4 q = src[i * 64 + l];
+    r[4 * i + 0] = q.x; r[4 * i + 1] = q.y; r[4 * i + 2] = q.z; r[4 * i + 3] = q.w;
+  }
+  typename D::Uniform u;
+  u.init();
+  const int n0 = TILE_N * nc + 4 * i16;
+  static_for<4>([&](auto Jc) {
+    constexpr int J = decltype(Jc)::value;
+    const int g = (TILE_K * kc + 32 * J) / p.group;
+    uint2 sraw = *reinterpret_cast<const uint2*>(p.S + (int64_t)g * p.N + n0);
+    uint32_t zraw = p.Z ? *reinterpret_cast<const uint32_t*>(p.Z + (int64_t)g * p.N + n0) : 0u;
+    typename D::Consts gc;
+    D::make_consts(gc, sraw, zraw, p.zbias, p.scale_bf16);
+    static_for<4>([&](auto NTc) {
+      constexpr int NT = decltype(NTc)::value;
+      uint32_t o[4];
+      D::template frag<J, NT>(r, gc, u, o);
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        int k = TILE_K * kc + 32 * J + 8 * b + 2 * v;
+        p.out[(int64_t)k * p.N + n0 + NT] = (uint16_t)(o[v] & 0xffffu);
+        p.out[(int64_t)(k + 1) * p.N + n0 + NT] = (uint16_t)(o[v] >> 16);
+      }
+    });
+  });
+}
+
+#define QG_CAT2(a, b) a##b
+#define QG_CAT(a, b) QG_CAT2(a, b)
+
+int QG_CAT(dequant_launch_wt, QG_WT)(const DequantParams& p, int route, hipStream_t st) {
+  int64_t nchunks = (int64_t)(p.K / TILE_K) * (p.N / TILE_N);
+  dim3 grid((unsigned)((nchunks + 3) / 4)), block(256);
+  if (route == ROUTE_F16) hipLaunchKernelGGL((dequant_kernel<QG_WT, ROUTE_F16>), grid, block, 0, st, p);
+  else                    hipLaunchKernelGGL((dequant_kernel<QG_WT, ROUTE_BF16>), grid, block, 0, st, p);
+  return hipGetLastError() == hipSuccess ? QG_OK : QG_EHIP;
+}
+
+}  // namespace qg

@@ -1,0 +1,103 @@
+"""GPU parity, part 1: canonical packing, re-layout and de-quantisation are
+bit-exact against the oracle (integer/byte work and the single RNE rounding of
+the weights admit exactly one answer)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import qgemm_oracle as O
+from paper_2504_12984_amd import workloads as WL
+from gpu_util import Prepared, bits_of
+
+pytestmark = pytest.mark.gpu
+
+U, I, F = WL.KIND_UINT, WL.KIND_INT, WL.KIND_FLOAT
+FLOATS = [(3, 1, 1), (4, 2, 1), (5, 2, 2), (6, 3, 2), (7, 3, 3), (8, 4, 3)]
+
+
+@pytest.mark.parametrize("bits", range(1, 9))
+def test_pack_codes_equals_oracle_stream(bits):
+    from paper_2504_12984_amd import binding as B
+    rng = np.random.default_rng(bits)
+    for count in (1, 7, 8, 9, 1000, 128 * 64 * 3 + 5):
+        codes = rng.integers(0, 1 << bits, size=count, dtype=np.uint8)
+        got = B.qg_pack_codes(torch.from_numpy(codes).cuda(), bits).cpu().numpy()
+        assert got.tolist() == O.pack_canonical(codes, bits).tolist(), (bits, count)
+
+
+def _check_w(case, inputs=None):
+    P = Prepared(case, inputs)
+    _, want = P.oracle_w()
+    got = bits_of(P.gpu_w())
+    if not np.array_equal(got, want):
+        bad = np.argwhere(got != want)
+        k, n = bad[0]
+        raise AssertionError(f"{case.name}: {len(bad)} of {want.size} weights differ; first at k={k} n={n}: "
+                             f"gpu={got[k, n]:#06x} oracle={want[k, n]:#06x} code={P.inp['codes'][k, n]}")
+
+
+@pytest.mark.parametrize("act", ["f16", "bf16"])
+@pytest.mark.parametrize("bits", range(1, 9))
+@pytest.mark.parametrize("kind", [U, I])
+def test_integer_weights_bit_exact(kind, bits, act):
+    zero = (1 << (bits - 1)) if kind == U else None
+    for group in (64, 128, 256):
+        case = WL.Case(f"dq_{kind}_{bits}_{act}_{group}", 1, 256, 192, kind, bits, group=group, act=act,
+                       scale_dtype="f16", zero=zero, seed=7000 + 10 * bits + kind)
+        _check_w(case)
+
+
+@pytest.mark.parametrize("act,sdt", [("f16", "f16"), ("bf16", "f16"), ("bf16", "bf16")])
+@pytest.mark.parametrize("bits,e,m", FLOATS)
+def test_float_weights_bit_exact(bits, e, m, act, sdt):
+    case = WL.Case(f"dq_f{bits}_{act}", 1, 256, 128, F, bits, e, m, group=256, act=act, scale_dtype=sdt,
+                   zero=None, scale_lo=0.01, scale_hi=0.1, seed=7100 + bits)
+    _check_w(case)
+
+
+@pytest.mark.parametrize("bits", range(1, 9))
+def test_every_code_in_every_lane_position(bits):
+    """codes[k, n] cycles through all 2^bits values with a stride coprime to the
+    tile, and the zero-points / scales vary per group and column."""
+    K, N, g = 384, 128, 128
+    case = WL.Case(f"dq_cycle_{bits}", 1, K, N, U, bits, group=g, act="f16", zero=0, seed=7200 + bits)
+    inp = WL.make_inputs(case)
+    kk, nn = np.meshgrid(np.arange(K), np.arange(N), indexing="ij")
+    inp["codes"] = ((kk * 7 + nn * 3 + (kk // 8)) % (1 << bits)).astype(np.uint8)
+    rng = np.random.default_rng(bits)
+    inp["zeros"] = rng.integers(0, 256, size=(K // g, N), dtype=np.uint8)
+    _check_w(case, inp)
+    case_b = WL.shrink(case, act="bf16", scale_dtype="bf16", name=case.name + "_bf16")
+    inp_b = dict(inp)
+    inp_b["scales"] = inp["scales"].to(torch.bfloat16)
+    inp_b["A"] = inp["A"].to(torch.bfloat16)
+    _check_w(case_b, inp_b)
+
+
+def test_extreme_scales_subnormal_results_and_signed_zero():
+    # tiny scales push products into the fp16 subnormal range (gradual underflow
+    # must be kept); negative scales flip signs; e2m1 has a -0 code
+    K, N = 128, 64
+    for kind, bits, e, m in [(U, 4, 0, 0), (I, 8, 0, 0), (F, 4, 2, 1), (F, 8, 4, 3)]:
+        case = WL.Case(f"dq_tiny_{kind}_{bits}", 1, K, N, kind, bits, e, m, group=128, act="f16",
+                       zero=(8 if kind == U else None), seed=7300 + bits)
+        inp = WL.make_inputs(case)
+        s = inp["scales"].clone()
+        s[:, 0::4] = 3.0e-6
+        s[:, 1::4] = -0.013
+        s[:, 2::4] = 6.2e-5
+        inp["scales"] = s
+        _check_w(case, inp)
+
+
+def test_config1_weights_full_size():
+    _check_w(WL.cfg1())
+
+
+def test_repack_rejects_bad_shapes():
+    from paper_2504_12984_amd import binding as B
+    buf = torch.zeros(128 * 64, dtype=torch.uint8, device="cuda")
+    with pytest.raises(B.QgError):
+        B.repack(buf, B.WType(U, 8), 100, 64)
+    with pytest.raises(B.QgError):
+        B.repack(buf, B.WType(U, 9), 128, 64)

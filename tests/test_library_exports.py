@@ -1,0 +1,55 @@
+"""The C-ABI library loads and exports every symbol include/qgemm.h declares.
+No compute call is made here (runs without a GPU)."""
+import ctypes
+import os
+import re
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "qgemm.h")).read()
+    return sorted(set(re.findall(r"^QG_API\s+[\w\s\*]+?\b(\w+)\s*\(", text, flags=re.M)))
+
+
+def test_header_declares_the_expected_entry_points():
+    names = _declared()
+    for must in ("qgemm", "repack", "qdequant", "qgemm_packed_bytes", "qg_pack_codes"):
+        assert must in names
+
+
+def test_library_exports_every_declared_symbol():
+    from paper_2504_12984_amd import binding as B
+    lib = ctypes.CDLL(B.LIB_PATH)
+    for name in _declared():
+        assert hasattr(lib, name), name
+    assert sorted(B.EXPORTS) == _declared()
+
+
+def test_host_side_size_queries_and_status_strings():
+    from paper_2504_12984_amd import binding as B
+    assert B.qg_canonical_bytes(3, 8) == 3 and B.qg_canonical_bytes(5, 5) == 4
+    assert B.qg_canonical_bytes(9, 8) == 0
+    t = B.WType(B.QG_INT, 6)
+    assert B.qgemm_packed_bytes(t, 128, 64) == 128 * 64 * 6 // 8      # BK*BN*6/8 bytes per tile
+    assert B.qgemm_packed_bytes(t, 8192, 57344) == 8192 * 57344 * 6 // 8
+    assert B.qgemm_packed_bytes(t, 100, 64) == 0 and B.qgemm_packed_bytes(t, 128, 65) == 0
+    assert B.qgemm_packed_bytes(B.WType(B.QG_FLOAT, 6, 3, 2), 128, 64) == 6144
+    assert B.qgemm_packed_bytes(B.WType(B.QG_FLOAT, 6, 3, 3), 128, 64) == 0   # 1+e+m != bits
+    assert B._lib.qg_status_string(0) == b"ok"
+    assert b"invalid" in B._lib.qg_status_string(-1)
+
+
+def test_argument_errors_are_reported_before_anything_is_enqueued():
+    from paper_2504_12984_amd import binding as B
+    t = B.WType(B.QG_UINT, 4).c()
+    # null pointers, bad shapes, bad bits: all rejected on the host
+    assert B._lib.repack(None, t, 0, 128, 64, None, None) == B.QG_EINVAL
+    assert B._lib.qgemm(None, None, None, None, t, 0, 0, 0, 128, 1, 64, 128, None, None) == B.QG_EINVAL
+    assert B._lib.qgemm(None, None, None, None, t, 0, 0, 0, 128, 1, 64, 100, None, None) == B.QG_EINVAL
+    assert B._lib.qgemm(None, None, None, None, B.WType(B.QG_UINT, 9).c(), 0, 0, 0, 128, 1, 64, 128, None, None) == B.QG_EINVAL
+    assert B._lib.qdequant(None, None, None, t, 0, 0, 0, 96, 128, 64, None, None) == B.QG_EINVAL   # K % group
+    assert B._lib.qdequant(None, None, None, t, 7, 0, 0, 128, 128, 64, None, None) == B.QG_EINVAL  # layout
+    assert B._lib.qdequant(None, None, None, B.WType(B.QG_FLOAT, 8, 5, 2).c(), 0, 0, 0, 128, 128, 64, None, None) == B.QG_EUNSUPPORTED
+    assert B._lib.qg_pack_codes(None, 0, 8, None, None) == B.QG_EINVAL
+    assert B._lib.qg_pack_codes(None, 3, 0, None, None) == B.QG_OK
