@@ -1,0 +1,204 @@
+#!/usr/bin/env python3
+"""Benchmark of the quantised matmul hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-cpu]
+
+Default workload is the W3A16 decode configuration (uint3 weights, K=4096,
+N=14336, group 128, fp16): one step = qgemm at M=1, M=4 and M=16, each call
+streaming a different resident copy of the packed weight so that no call finds
+its weights in a cache (the paper clears L2 before each run; rotating through
+more copies than the last-level cache holds has the same effect without a
+second kernel inside the timed region).  Inputs are seeded and synthetic and
+already in HBM when the timed region starts.  Prints one JSON line.
+
+Other workloads (for the tables in the design doc): cfg1, cfg3_i<k>, cfg4_f<bits>_M<m>,
+cfg5_u<k>_M<m>.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
+MFMA_PEAK_TFLOPS = 2500.0      # dense fp16/bf16
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="cfg2")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--copies", type=int, default=0, help="resident weight copies to rotate through")
+    return ap.parse_args()
+
+
+def cases_for(name):
+    from paper_2504_12984_amd import workloads as WL
+    if name == "cfg1":
+        return [WL.cfg1()]
+    if name == "cfg2":
+        return [WL.cfg2(1), WL.cfg2(4), WL.cfg2(16)]
+    if name.startswith("cfg2_M"):
+        return [WL.cfg2(int(name[6:]))]
+    if name.startswith("cfg3_i"):
+        if "_M" in name:                              # cfg3 recipe at another M (tables only)
+            bits, m = name[6:].split("_M")
+            return [WL.shrink(WL.cfg3(int(bits)), M=int(m), name=f"cfg3_i{bits}_M{m}")]
+        return [WL.cfg3(int(name[6:]))]
+    if name.startswith("cfg4_f"):
+        bits, m = name[6:].split("_M")
+        return [WL.cfg4(int(bits), int(m))]
+    if name.startswith("cfg5_u"):
+        bits, m = name[6:].split("_M")
+        return [WL.cfg5(int(bits), int(m))]
+    raise SystemExit(f"unknown workload {name}")
+
+
+def algorithmic_bytes(c):
+    """Bytes one call must move: packed W once, scales, zero-points, A, C."""
+    P = c.K * c.N * c.bits // 8
+    G = c.K // c.group
+    S = G * c.N * 2
+    Z = G * c.N if c.zero is not None else 0
+    return P, P + S + Z + c.M * c.K * 2 + c.M * c.N * 2
+
+
+def cpu_baseline(case, budget_s=20.0):
+    """Time the oracle, as it stands, on a column sample of the same workload."""
+    import numpy as np
+    import psutil
+    from oracle import qgemm_oracle as O
+    from paper_2504_12984_amd import workloads as WL
+    inp = WL.make_inputs(case)
+    stream = O.pack_canonical(inp["codes"], case.bits)
+    A = inp["A"].double().numpy()
+    S = inp["scales"].double().numpy()
+    proc = psutil.Process()
+    cols_done, t_used, cpu_used = 0, 0.0, 0.0
+    block = 1024
+    while cols_done < case.N and t_used < budget_s:
+        cols = np.arange(cols_done, min(case.N, cols_done + block))
+        c0 = proc.cpu_times()
+        t0 = time.perf_counter()
+        O.qgemm_from_stream(A, stream, case.kind, case.bits, case.ebits, case.mbits, S, inp["zeros"],
+                            case.group, case.K, case.N, case.act, cols=cols)
+        t_used += time.perf_counter() - t0
+        c1 = proc.cpu_times()
+        cpu_used += (c1.user + c1.system) - (c0.user + c0.system)
+        cols_done += cols.size
+    frac = cols_done / case.N
+    return frac, t_used, max(1, round(cpu_used / max(t_used, 1e-9)))
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
+              "(no collectives or sharding are part of it)", file=sys.stderr)
+        raise SystemExit(2)
+    import torch
+    from paper_2504_12984_amd import binding as B
+    from paper_2504_12984_amd import workloads as WL
+
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    torch.cuda.set_device(0)
+    dev = "cuda:0"
+    cases = cases_for(args.workload)
+    c0 = cases[0]
+    wt = B.WType(c0.kind, c0.bits, c0.ebits, c0.mbits)
+    P, _ = algorithmic_bytes(c0)
+
+    # ---- resident inputs: one weight draw, many copies -------------------------
+    inp0 = WL.make_inputs(c0)
+    codes = torch.from_numpy(inp0["codes"]).to(dev)
+    packed0 = B.repack(B.qg_pack_codes(codes, c0.bits), wt, c0.K, c0.N)
+    del codes
+    copies = args.copies or int(min(64, max(3, -(-(3 << 29) // P))))     # ~1.5 GB of packed weights
+    packed = [packed0] + [packed0.clone() for _ in range(copies - 1)]
+    scales = [inp0["scales"].to(dev).clone() for _ in range(copies)]
+    zeros = [None if inp0["zeros"] is None else torch.from_numpy(inp0["zeros"]).to(dev).clone()
+             for _ in range(copies)]
+    As = [WL.make_inputs(c)["A"].to(dev) if i else inp0["A"].to(dev) for i, c in enumerate(cases)]
+    Cs = [torch.empty((c.M, c.N), dtype=a.dtype, device=dev) for c, a in zip(cases, As)]
+    torch.cuda.synchronize()
+
+    rot = [0]
+
+    def step():
+        for c, A, C in zip(cases, As, Cs):
+            i = rot[0] % copies
+            rot[0] += 1
+            B.qgemm(A, packed[i], scales[i], zeros[i], wt, c.group, c.N, out=C)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record()
+    for _ in range(args.steps):
+        step()
+    ev1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    gpu_ms = ev0.elapsed_time(ev1)
+    ms_per_step = gpu_ms / args.steps
+    launches = len(cases)
+    launch_ms = ms_per_step / launches
+
+    small = all(c.M <= 64 for c in cases)
+    flops_step = sum(2.0 * c.M * c.N * c.K for c in cases)
+    alg_bytes = sum(algorithmic_bytes(c)[1] for c in cases) / launches
+    gbs_packed = launches * P / (ms_per_step * 1e-3) / 1e9
+    tflops = flops_step / (ms_per_step * 1e-3) / 1e12
+    if small:
+        metric, unit, value = "packed_weight_hbm_gbps", "GB/s", gbs_packed
+        ach = alg_bytes / (launch_ms * 1e-3) / 1e9
+        roof = {"bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": None,
+                "kernel": "qg::small_kernel", "avg_launch_us": round(launch_ms * 1e3, 3),
+                "algorithmic_bytes_per_launch": int(alg_bytes)}
+    else:
+        metric, unit, value = "effective_tflops", "TFLOP/s", tflops
+        roof = {"bound": "mfma", "achieved": round(tflops, 1), "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                "frac": round(tflops / MFMA_PEAK_TFLOPS, 4), "traffic": None,
+                "kernel": "qg::large_kernel", "avg_launch_us": round(launch_ms * 1e3, 3),
+                "algorithmic_flops_per_launch": flops_step / launches}
+
+    out = {
+        "metric": metric, "value": round(value, 2), "unit": unit, "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if c0.act == "bf16" else "f16", "data": "synthetic",
+        "config": {"workload": args.workload, "cases": [c.name for c in cases], "weight": c0.wname,
+                   "K": c0.K, "N": c0.N, "group": c0.group, "M": [c.M for c in cases],
+                   "launches_per_step": launches, "weight_copies_rotated": copies,
+                   "packed_bytes": P},
+        "roofline": roof,
+        "extra": {"packed_gbps": round(gbs_packed, 1), "tflops": round(tflops, 3),
+                  "host_wall_ms_per_step": round(wall_ms / args.steps, 5)},
+    }
+    if not args.no_cpu:
+        cb = cases[-1]
+        frac, t_used, cores = cpu_baseline(cb)
+        Pb = cb.K * cb.N * cb.bits // 8
+        if small:
+            v, u = Pb * frac / t_used / 1e9, "GB/s"
+        else:
+            v, u = 2.0 * cb.M * cb.N * cb.K * frac / t_used / 1e12, "TFLOP/s"
+        out["cpu_baseline"] = {"value": round(v, 6), "unit": u, "cores": cores, "kind": "oracle",
+                               "sample": f"{cb.name}: first {frac * 100:.1f}% of the N columns, all M rows, "
+                                         f"{t_used:.1f} s (unpack+dequant+round+fp64 GEMM)"}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

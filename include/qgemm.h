@@ -118,7 +118,9 @@ QG_API int qgemm(const void* A, const void* packed_W, const void* scales, const 
 
 /* Optional: path/tuning override for experiments (0 = automatic).  Returns the
  * previous value.  knob 0: forced path (1 = small-M kernel, 2 = tiled kernel);
- * knob 1: forced split-K factor of the small-M kernel. */
+ * knob 1: forced split-K factor of the small-M kernels; knob 2: forced row-tile
+ * (128 / 256) of the tiled kernel; knob 3: pipeline variant + 1 of the M <= 16
+ * kernel. */
 QG_API int qg_set_knob(int knob, int value);
 
 #ifdef __cplusplus

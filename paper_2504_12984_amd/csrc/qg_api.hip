@@ -15,6 +15,8 @@ int launch_repack(const uint8_t*, int, int, int, uint32_t, uint8_t*, hipStream_t
 #define QG_DECL(i)                                                            \
   int dequant_launch_wt##i(const DequantParams&, int, hipStream_t);           \
   int small_launch_wt##i(const GemmParams&, int, int, hipStream_t);           \
+  int decode_launch_wt##i(const GemmParams&, int, int, hipStream_t);          \
+  int decode_waves_wt##i(int);                                                \
   int large_launch_wt##i(const GemmParams&, int, int, hipStream_t);
 QG_FOR_ALL_WT(QG_DECL)
 #undef QG_DECL
@@ -29,6 +31,13 @@ static const gm_fn kSmall[NUM_WT] = {QG_FOR_ALL_WT(QG_ENT)};
 #undef QG_ENT
 #define QG_ENT(i) large_launch_wt##i,
 static const gm_fn kLarge[NUM_WT] = {QG_FOR_ALL_WT(QG_ENT)};
+#undef QG_ENT
+#define QG_ENT(i) decode_launch_wt##i,
+static const gm_fn kDecode[NUM_WT] = {QG_FOR_ALL_WT(QG_ENT)};
+#undef QG_ENT
+typedef int (*waves_fn)(int);
+#define QG_ENT(i) decode_waves_wt##i,
+static const waves_fn kDecodeWaves[NUM_WT] = {QG_FOR_ALL_WT(QG_ENT)};
 #undef QG_ENT
 
 static thread_local std::string g_last_error;
@@ -192,14 +201,19 @@ int qgemm(const void* A, const void* packed_W, const void* scales, const uint8_t
   if (path == 1 && M > 64) return QG_EINVAL;
 
   if (path == 1) {
+    const bool decode = (M <= 16);            // M <= 16: streaming kernel; 17..64: register-blocked kernel
     const int mt = M <= 16 ? 1 : (M <= 32 ? 2 : 4);
     const int KC = (int)(K / TILE_K), NCH = (int)(N / TILE_N);
-    // split K over workgroups until the grid fills the chip (256 CUs) a few
-    // times over, keeping at least 2 chunks per wavefront (8 wavefronts per WG)
+    // M <= 16 pipeline variants: 8 wavefronts per strip for short K (few chunks per
+    // wavefront, more loads in flight at once), 4 wavefronts otherwise
+    const int variant = g_knob[3] > 0 ? g_knob[3] - 1 : (KC <= 32 ? 1 : 3);
+    const int waves = decode ? kDecodeWaves[wt](variant) : 8;
+    // Split K over workgroups only when the column strips alone cannot fill the
+    // 256 CUs, and never below 4 chunks per wavefront.
     int splitk = g_knob[1];
     if (splitk <= 0) {
       splitk = 1;
-      while (NCH * splitk < 1024 && KC / (splitk * 2) >= 16) splitk *= 2;
+      while (NCH * splitk < 256 && KC / (splitk * 2) >= 4 * waves) splitk *= 2;
     }
     if (splitk > KC) splitk = KC;
     int cps = (KC + splitk - 1) / splitk;
@@ -212,7 +226,7 @@ int qgemm(const void* A, const void* packed_W, const void* scales, const uint8_t
       if (rc != QG_OK) return rc;
       p.ws = w->partial; p.tickets = w->tickets;
     }
-    return kSmall[wt](p, route, mt, st);
+    return decode ? kDecode[wt](p, route, variant, st) : kSmall[wt](p, route, mt, st);
   }
   return kLarge[wt](p, route, g_knob[2], st);
 }

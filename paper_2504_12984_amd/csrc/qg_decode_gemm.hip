@@ -1,0 +1,239 @@
+// Decode-sized matmul, M <= 16: the weights are streamed from HBM exactly once
+// and the kernel is built to keep that stream saturated.
+//
+// One workgroup of NW wavefronts owns one 64-column strip of W and one slab of
+// K; wavefront w takes every NW-th 128x64 chunk of the slab.  A wavefront keeps
+// DEPTH chunks in flight at all times in a ring of registers (the software
+// pipelining the paper calls essential, Sections "An Example of Tilus Program"
+// and "End-to-End Performance"): per chunk BITS 16-byte loads of packed codes,
+// four 16-byte loads of A (one per k-step, L2-resident), one load each of
+// scales and zero-points.  The steady-state loop has no branches and refills a
+// ring entry right after it has been consumed, so the compiler waits on exact
+// outstanding-load counts instead of draining the queue.
+// Codes are unpacked in registers and fed to the 16x16x32 matrix instruction
+// with W as the row operand (the paper's load -> reinterpret -> cast -> mma
+// pipeline, Section "Key Ideas", with no layout conversion and no trip through
+// LDS).  The K reduction runs inside the MFMA (across the four 8-wide k-blocks
+// of lanes), then across the wavefronts through LDS, then -- when K is also
+// split over workgroups -- through fp32 partial tiles summed in split order by
+// the last workgroup to arrive (the k-dimension parallelisation the paper names
+// in Section "End-to-End Performance").
+// Compiled once per weight type (QG_WT).
+#include "qg_decode.h"
+#include "qg_static_for.h"
+
+#ifndef QG_WT
+#error "compile with -DQG_WT=<weight type index>"
+#endif
+
+namespace qg {
+
+typedef uint32_t u4_t __attribute__((ext_vector_type(4)));
+typedef _Float16 h8_t __attribute__((ext_vector_type(8)));
+typedef __bf16 b8_t __attribute__((ext_vector_type(8)));
+typedef float f4_t __attribute__((ext_vector_type(4)));
+
+template <int ROUTE>
+__device__ __forceinline__ f4_t mfma16(u4_t w, u4_t a, f4_t c) {
+  if constexpr (ROUTE == ROUTE_F16)
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(h8_t, w), __builtin_bit_cast(h8_t, a), c, 0, 0, 0);
+  else
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(b8_t, w), __builtin_bit_cast(b8_t, a), c, 0, 0, 0);
+}
+
+template <int ROUTE>
+__device__ __forceinline__ uint32_t pack_out(float lo, float hi) {
+  f2_t f = {lo, hi};
+  if constexpr (ROUTE == ROUTE_F16) return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, h2_t));
+  else return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, b2_t));
+}
+
+template <int WT, int ROUTE, bool TWO_GROUPS, int NW, int DEPTH>
+__global__ __launch_bounds__(NW * 64) void decode_kernel(GemmParams p) {
+  typedef Decoder<WT, ROUTE> D;
+  constexpr int BITS = D::BITS, RAW = D::RAW;
+
+  const int tid = threadIdx.x, l = tid & 63;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, kept in a scalar register
+  const int b = l >> 4, i16 = l & 15;
+  const int nc = blockIdx.x, split = blockIdx.y;
+  const int KC = p.K / TILE_K, NCH = p.N / TILE_N;
+  const int c0 = split * p.chunks_per_split;
+  const int c1 = min(KC, c0 + p.chunks_per_split);
+  const int mine = (c1 - c0 > w) ? (c1 - c0 - w + NW - 1) / NW : 0;
+  const int n0 = TILE_N * nc + 4 * i16;
+
+  const uint4* wstrip = reinterpret_cast<const uint4*>(p.W + (int64_t)nc * KC * (1024 * BITS)) + l;
+  // rows past M re-read row M-1; their results are never stored
+  const uint16_t* arow = p.A + (int64_t)min(i16, p.M - 1) * p.K + 8 * b;
+  // no zero-points: read (valid) scale bytes instead and mask them away
+  const uint8_t* zbase = p.Z ? p.Z : reinterpret_cast<const uint8_t*>(p.S);
+  const uint32_t zmask = p.Z ? 0xffffffffu : 0u;
+
+  struct Stage {
+    uint32_t r[RAW];
+    u4_t a[4];
+    uint2 s0, s1;
+    uint32_t z0, z1;
+  };
+  Stage st[DEPTH];
+
+  auto issue = [&](auto Sc, int c) __attribute__((always_inline)) {
+    constexpr int S = decltype(Sc)::value;
+    Stage& s = st[S];
+    __builtin_amdgcn_sched_barrier(0);         // stay below the last use of the entry being refilled,
+                                               // so that the refill reuses the same registers
+#pragma unroll
+    for (int j = 0; j < 4; ++j) s.a[j] = *reinterpret_cast<const u4_t*>(arow + c * TILE_K + 32 * j);
+    const uint4* src = wstrip + (int64_t)c * (64 * BITS);
+#pragma unroll
+    for (int i = 0; i < BITS; ++i) {
+      uint4 q = src[i * 64];
+      s.r[4 * i + 0] = q.x; s.r[4 * i + 1] = q.y; s.r[4 * i + 2] = q.z; s.r[4 * i + 3] = q.w;
+    }
+    const int g0 = (c * TILE_K) / p.group;
+    s.s0 = *reinterpret_cast<const uint2*>(p.S + (int64_t)g0 * p.N + n0);
+    if constexpr (TWO_GROUPS) {
+      s.s1 = *reinterpret_cast<const uint2*>(p.S + (int64_t)(g0 + 1) * p.N + n0);
+      s.z1 = *reinterpret_cast<const uint32_t*>(zbase + (int64_t)(g0 + 1) * p.N + n0);
+    }
+    s.z0 = *reinterpret_cast<const uint32_t*>(zbase + (int64_t)g0 * p.N + n0);
+    __builtin_amdgcn_sched_barrier(0);
+  };
+
+  f4_t acc[4];
+#pragma unroll
+  for (int nt = 0; nt < 4; ++nt) acc[nt] = (f4_t){0.f, 0.f, 0.f, 0.f};
+
+  typename D::Uniform u;
+  u.init();
+
+  auto compute = [&](auto Sc) __attribute__((always_inline)) {
+    constexpr int S = decltype(Sc)::value;
+    Stage& s = st[S];
+    typename D::Consts gc0, gc1;
+    D::make_consts(gc0, s.s0, s.z0 & zmask, p.zbias, p.scale_bf16);
+    if constexpr (TWO_GROUPS) D::make_consts(gc1, s.s1, s.z1 & zmask, p.zbias, p.scale_bf16);
+    static_for<4>([&](auto Jc) __attribute__((always_inline)) {
+      constexpr int J = decltype(Jc)::value;
+      static_for<4>([&](auto NTc) __attribute__((always_inline)) {
+        constexpr int NT = decltype(NTc)::value;
+        uint32_t o[4];
+        D::template frag<J, NT>(s.r, (TWO_GROUPS && J >= 2) ? gc1 : gc0, u, o);
+        acc[NT] = mfma16<ROUTE>((u4_t){o[0], o[1], o[2], o[3]}, s.a[J], acc[NT]);
+      });
+    });
+  };
+
+  auto chunk_of = [&](int i) __attribute__((always_inline)) { return c0 + w + min(i, mine - 1) * NW; };
+
+  if (mine > 0) {
+    // prologue: DEPTH chunks in flight (past-the-end stages re-load my last chunk)
+    static_for<DEPTH>([&](auto Sc) __attribute__((always_inline)) { issue(Sc, chunk_of(decltype(Sc)::value)); });
+    int i = 0;
+    // steady state: no branches, so the compiler can wait on exact load counts
+    for (; i + 2 * DEPTH <= mine; i += DEPTH)
+      static_for<DEPTH>([&](auto Sc) __attribute__((always_inline)) {
+        compute(Sc);
+        issue(Sc, chunk_of(i + decltype(Sc)::value + DEPTH));
+      });
+    // drain
+    static_for<DEPTH>([&](auto Sc) __attribute__((always_inline)) {
+      constexpr int S = decltype(Sc)::value;
+      if (i + S < mine) {
+        compute(Sc);
+        if (i + S + DEPTH < mine) issue(Sc, chunk_of(i + S + DEPTH));
+      }
+    });
+    i += DEPTH;
+    static_for<DEPTH>([&](auto Sc) __attribute__((always_inline)) {
+      if (i + decltype(Sc)::value < mine) compute(Sc);
+    });
+  }
+
+  // ---- reduce over the NW wavefronts through LDS ---------------------------------------
+  __shared__ float red[NW * 16 * 64];                      // [NW][16 column offsets][64 lanes]
+  __shared__ int s_last;
+  constexpr int PER = 16 / NW;                             // column offsets per thread
+  const int idx0 = PER * w;
+#pragma unroll
+  for (int nt = 0; nt < 4; ++nt)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) red[(w * 16 + 4 * r + nt) * 64 + l] = acc[nt][r];   // column offset 4r + nt
+  __syncthreads();
+  float sum[PER];
+#pragma unroll
+  for (int e = 0; e < PER; ++e) {
+    float t = 0.f;
+#pragma unroll
+    for (int ww = 0; ww < NW; ++ww) t += red[(ww * 16 + idx0 + e) * 64 + l];
+    sum[e] = t;
+  }
+
+  if (p.splitk > 1) {
+    // Partial tiles cross workgroups (and XCDs, whose L2s are not coherent with
+    // each other) through device-scope relaxed atomics: such stores write
+    // through and such loads bypass the local caches, so no cache-wide
+    // write-back or invalidate is needed.  Order: my stores complete, barrier,
+    // one arrival count per workgroup; the workgroup that counts splitk-1
+    // earlier arrivals sums all tiles in split order, so the result does not
+    // depend on arrival order.
+    float* tile = p.ws + ((int64_t)split * NCH + nc) * 1024;
+#pragma unroll
+    for (int e = 0; e < PER; ++e)
+      __hip_atomic_store(tile + (idx0 + e) * 64 + l, sum[e], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // a workgroup barrier alone does not wait for global stores
+    __syncthreads();
+    if (tid == 0)
+      s_last = (__hip_atomic_fetch_add(&p.tickets[nc], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (unsigned)(p.splitk - 1));
+    __syncthreads();
+    if (!s_last) return;
+#pragma unroll
+    for (int e = 0; e < PER; ++e) {
+      float t = 0.f;
+      for (int sp = 0; sp < p.splitk; ++sp)
+        t += __hip_atomic_load(p.ws + ((int64_t)sp * NCH + nc) * 1024 + (idx0 + e) * 64 + l, __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_AGENT);
+      sum[e] = t;
+    }
+    if (tid == 0) __hip_atomic_store(&p.tickets[nc], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next call
+  }
+  if (i16 < p.M) {
+    uint16_t* dst = p.C + (int64_t)i16 * p.N + TILE_N * nc + 16 * b + idx0;
+#pragma unroll
+    for (int e = 0; e < PER; e += 2) *reinterpret_cast<uint32_t*>(dst + e) = pack_out<ROUTE>(sum[e], sum[e + 1]);
+  }
+}
+
+#define QG_CAT2(a, b) a##b
+#define QG_CAT(a, b) QG_CAT2(a, b)
+
+template <int ROUTE, bool TG, int NW, int DEPTH>
+static int launch_cfg(const GemmParams& p, hipStream_t st) {
+  auto kern = decode_kernel<QG_WT, ROUTE, TG, NW, DEPTH>;
+  dim3 grid((unsigned)(p.N / TILE_N), (unsigned)p.splitk), block(NW * 64);
+  hipLaunchKernelGGL(kern, grid, block, 0, st, p);
+  return hipGetLastError() == hipSuccess ? QG_OK : QG_EHIP;
+}
+
+template <int ROUTE, bool TG>
+static int launch_variant(const GemmParams& p, int variant, hipStream_t st) {
+  switch (variant) {
+    case 0: return launch_cfg<ROUTE, TG, 4, (wt_bits(QG_WT) <= 5 ? 4 : 3)>(p, st);
+    case 1: return launch_cfg<ROUTE, TG, 8, 2>(p, st);
+    case 2: return launch_cfg<ROUTE, TG, 8, 3>(p, st);
+    case 3: return launch_cfg<ROUTE, TG, 4, 2>(p, st);
+    default: return QG_EINVAL;
+  }
+}
+
+// number of wavefronts per workgroup of a variant (the host sizes split-K with it)
+int QG_CAT(decode_waves_wt, QG_WT)(int variant) { return (variant == 1 || variant == 2) ? 8 : 4; }
+
+int QG_CAT(decode_launch_wt, QG_WT)(const GemmParams& p, int route, int variant, hipStream_t st) {
+  const bool tg = (p.group == 64);
+  if (route == ROUTE_F16) return tg ? launch_variant<ROUTE_F16, true>(p, variant, st) : launch_variant<ROUTE_F16, false>(p, variant, st);
+  return tg ? launch_variant<ROUTE_BF16, true>(p, variant, st) : launch_variant<ROUTE_BF16, false>(p, variant, st);
+}
+
+}  // namespace qg

@@ -15,7 +15,8 @@ template <int WT, int ROUTE>
 __global__ __launch_bounds__(256) void dequant_kernel(DequantParams p) {
   typedef Decoder<WT, ROUTE> D;
   constexpr int BITS = D::BITS, RAW = D::RAW;
-  const int l = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int l = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int KC = p.K / TILE_K;
   const int64_t chunk = (int64_t)blockIdx.x * 4 + wave;
   if (chunk >= (int64_t)KC * (p.N / TILE_N)) return;
@@ -32,14 +33,14 @@ __global__ __launch_bounds__(256) void dequant_kernel(DequantParams p) {
   typename D::Uniform u;
   u.init();
   const int n0 = TILE_N * nc + 4 * i16;
-  static_for<4>([&](auto Jc) {
+  static_for<4>([&](auto Jc) __attribute__((always_inline)) {
     constexpr int J = decltype(Jc)::value;
     const int g = (TILE_K * kc + 32 * J) / p.group;
     uint2 sraw = *reinterpret_cast<const uint2*>(p.S + (int64_t)g * p.N + n0);
     uint32_t zraw = p.Z ? *reinterpret_cast<const uint32_t*>(p.Z + (int64_t)g * p.N + n0) : 0u;
     typename D::Consts gc;
     D::make_consts(gc, sraw, zraw, p.zbias, p.scale_bf16);
-    static_for<4>([&](auto NTc) {
+    static_for<4>([&](auto NTc) __attribute__((always_inline)) {
       constexpr int NT = decltype(NTc)::value;
       uint32_t o[4];
       D::template frag<J, NT>(r, gc, u, o);

@@ -1,10 +1,243 @@
-// placeholder until the tiled kernel lands
-#include "qg_common.h"
+// Prefill-sized matmul: LDS-staged A, register-resident W, 16x16x32 MFMA.
+//
+// A workgroup of 4 wavefronts computes a BM x 256 tile of C.  Wavefront w owns
+// 64 columns: it loads its own 128x64 weight chunk straight from global memory
+// into registers (BITS 16-byte loads per lane, one chunk ahead of use), unpacks
+// it in registers and uses it as the row operand of the matrix instruction --
+// the weights never pass through LDS and are never exchanged between lanes,
+// which is the paper's weight pipeline (Section "Key Ideas", steps 1-4) with the
+// shared-memory hop removed because every wavefront needs different columns.
+// The BM x 128 slab of A for the same K range is shared by the four wavefronts
+// through LDS (double-buffered per chunk, XOR-swizzled 16-byte pieces, filled
+// through a small register ring two k-steps ahead), so each unpacked weight is
+// used BM times and each weight is unpacked M/BM times in total.
+// Workgroup ids are remapped so that the workgroups resident on one XCD (ids
+// congruent mod 8) form 4 x 8 panels of tiles that share A and W in that XCD's L2.
+// Compiled once per weight type (QG_WT).
+#include "qg_decode.h"
+#include "qg_static_for.h"
+
 #ifndef QG_WT
 #error "compile with -DQG_WT=<weight type index>"
 #endif
+
 namespace qg {
+
+typedef uint32_t u4_t __attribute__((ext_vector_type(4)));
+typedef _Float16 h8_t __attribute__((ext_vector_type(8)));
+typedef __bf16 b8_t __attribute__((ext_vector_type(8)));
+typedef float f4_t __attribute__((ext_vector_type(4)));
+
+template <int ROUTE>
+__device__ __forceinline__ f4_t mfma16(u4_t w, u4_t a, f4_t c) {
+  if constexpr (ROUTE == ROUTE_F16)
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(h8_t, w), __builtin_bit_cast(h8_t, a), c, 0, 0, 0);
+  else
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(b8_t, w), __builtin_bit_cast(b8_t, a), c, 0, 0, 0);
+}
+
+template <int ROUTE>
+__device__ __forceinline__ uint32_t pack_out(float lo, float hi) {
+  f2_t f = {lo, hi};
+  if constexpr (ROUTE == ROUTE_F16) return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, h2_t));
+  else return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, b2_t));
+}
+
+constexpr int LARGE_BN = 256;
+constexpr int LARGE_GROUP_M = 4;   // m-tiles per L2 panel
+
+// LDS: A slab of one chunk = 4 k-step slices, each [BM rows][4 pieces of 16 B];
+// piece p of row r is stored at slot p ^ ((r >> 2) & 3): the 16 lanes that read
+// one piece column of 16 consecutive rows then hit 16 different 4-bank groups.
+template <int BM>
+struct LargeLds {
+  static constexpr int SLICE = BM * 64;        // bytes
+  static constexpr int BUF = 4 * SLICE;
+};
+
+template <int WT, int ROUTE, int BM>
+__global__ __launch_bounds__(256) void large_kernel(GemmParams p, int tiles_m, int tiles_n, int per_xcd) {
+  typedef Decoder<WT, ROUTE> D;
+  constexpr int BITS = D::BITS, RAW = D::RAW;
+  constexpr int MTS = BM / 16;                 // 16-row MFMA tiles per workgroup
+  constexpr int PIECES = BM * 4 / 256;         // 16-byte pieces per thread per slice
+  typedef LargeLds<BM> L;
+  extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+
+  // ---- which tile ----------------------------------------------------------------
+  const int total = tiles_m * tiles_n;
+  const int logical = (int)(blockIdx.x % 8) * per_xcd + (int)(blockIdx.x / 8);
+  if (logical >= total) return;
+  const int panel = LARGE_GROUP_M * tiles_n;
+  const int first_m = (logical / panel) * LARGE_GROUP_M;
+  const int gsize = min(tiles_m - first_m, LARGE_GROUP_M);
+  const int tm = first_m + (logical % panel) % gsize;
+  const int tn = (logical % panel) / gsize;
+
+  const int tid = threadIdx.x, l = tid & 63;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, kept in a scalar register
+  const int b = l >> 4, i16 = l & 15;
+  const int KC = p.K / TILE_K, NCH = p.N / TILE_N;
+  const int m0 = tm * BM;
+  const int ncw = tn * (LARGE_BN / TILE_N) + w;          // my 64-column strip
+  const bool active = ncw < NCH;
+  const int nc = active ? ncw : NCH - 1;                 // idle wavefronts shadow a valid strip
+  const int n0 = TILE_N * nc + 4 * i16;
+  const bool two_groups = (p.group == 64);
+
+  // ---- A staging: thread t moves pieces q = t + 256*i, row = q/4, piece = q%4 ---------
+  const uint16_t* a_src[PIECES];
+  int a_dst[PIECES];
+#pragma unroll
+  for (int i = 0; i < PIECES; ++i) {
+    const int q = tid + 256 * i, row = q >> 2, pc = q & 3;
+    a_src[i] = p.A + (int64_t)min(m0 + row, p.M - 1) * p.K + 8 * pc;
+    a_dst[i] = row * 64 + 16 * (pc ^ ((row >> 2) & 3));
+  }
+  u4_t stage[2][PIECES];
+  auto a_issue = [&](int set, int kstep) __attribute__((always_inline)) {   // kstep = 4*chunk + slice, clamped to the last one
+    const int ks = min(kstep, 4 * KC - 1);
+#pragma unroll
+    for (int i = 0; i < PIECES; ++i) stage[set][i] = *reinterpret_cast<const u4_t*>(a_src[i] + ks * 32);
+  };
+  auto a_commit = [&](int set, int buf, int slice) __attribute__((always_inline)) {
+#pragma unroll
+    for (int i = 0; i < PIECES; ++i)
+      *reinterpret_cast<u4_t*>(lds + buf * L::BUF + slice * L::SLICE + a_dst[i]) = stage[set][i];
+  };
+
+  // ---- W prefetch: raw chunk + its scales / zero-points -------------------------------
+  struct WStage {
+    uint32_t r[RAW];
+    uint2 s0, s1;
+    uint32_t z0, z1;
+  };
+  WStage wcur, wnxt;
+  const uint4* wstrip = reinterpret_cast<const uint4*>(p.W + (int64_t)nc * KC * (1024 * BITS));
+  auto w_issue = [&](WStage& s, int c) __attribute__((always_inline)) {
+    c = min(c, KC - 1);
+    const uint4* src = wstrip + (int64_t)c * (64 * BITS) + l;
+#pragma unroll
+    for (int i = 0; i < BITS; ++i) {
+      uint4 q = src[i * 64];
+      s.r[4 * i + 0] = q.x; s.r[4 * i + 1] = q.y; s.r[4 * i + 2] = q.z; s.r[4 * i + 3] = q.w;
+    }
+    const int g0 = (c * TILE_K) / p.group;
+    s.s0 = *reinterpret_cast<const uint2*>(p.S + (int64_t)g0 * p.N + n0);
+    s.z0 = p.Z ? *reinterpret_cast<const uint32_t*>(p.Z + (int64_t)g0 * p.N + n0) : 0u;
+    if (two_groups) {
+      s.s1 = *reinterpret_cast<const uint2*>(p.S + (int64_t)(g0 + 1) * p.N + n0);
+      s.z1 = p.Z ? *reinterpret_cast<const uint32_t*>(p.Z + (int64_t)(g0 + 1) * p.N + n0) : 0u;
+    } else {
+      s.s1 = s.s0; s.z1 = s.z0;
+    }
+  };
+
+  f4_t acc[MTS][4];
+#pragma unroll
+  for (int mt = 0; mt < MTS; ++mt)
+#pragma unroll
+    for (int nt = 0; nt < 4; ++nt) acc[mt][nt] = (f4_t){0.f, 0.f, 0.f, 0.f};
+
+  typename D::Uniform u;
+  u.init();
+
+  // ---- prologue: chunk 0's A slab into buffer 0, ring primed for chunk 1 --------------
+  w_issue(wcur, 0);
+  a_issue(0, 0); a_issue(1, 1);
+  a_commit(0, 0, 0); a_issue(0, 2);
+  a_commit(1, 0, 1); a_issue(1, 3);
+  a_commit(0, 0, 2); a_issue(0, 4);     // slice 0 of chunk 1
+  a_commit(1, 0, 3); a_issue(1, 5);     // slice 1 of chunk 1
+  __syncthreads();
+
+  // my A fragment of row-tile mt, k-step slice j: piece b of row mt*16 + i16
+  const int a_rd = i16 * 64 + 16 * (b ^ ((i16 >> 2) & 3));
+
+  for (int kc = 0; kc < KC; ++kc) {
+    const int cur = kc & 1, nxt = cur ^ 1;
+    w_issue(wnxt, kc + 1);
+    typename D::Consts gc0, gc1;
+    D::make_consts(gc0, wcur.s0, wcur.z0, p.zbias, p.scale_bf16);
+    if (two_groups) D::make_consts(gc1, wcur.s1, wcur.z1, p.zbias, p.scale_bf16);
+    else gc1 = gc0;
+    static_for<4>([&](auto Jc) __attribute__((always_inline)) {
+      constexpr int J = decltype(Jc)::value;
+      // A slab of the next chunk: commit the slice loaded two k-steps ago, then
+      // start the load that will be committed two k-steps from now
+      a_commit(J & 1, nxt, J);
+      a_issue(J & 1, 4 * (kc + 1) + J + 2);
+      u4_t wf[4];
+      static_for<4>([&](auto NTc) __attribute__((always_inline)) {
+        constexpr int NT = decltype(NTc)::value;
+        uint32_t o[4];
+        D::template frag<J, NT>(wcur.r, (J < 2) ? gc0 : gc1, u, o);
+        wf[NT] = (u4_t){o[0], o[1], o[2], o[3]};
+      });
+      const uint8_t* abase = lds + cur * L::BUF + J * L::SLICE + a_rd;
+#pragma unroll
+      for (int mt = 0; mt < MTS; ++mt) {
+        u4_t a = *reinterpret_cast<const u4_t*>(abase + mt * (16 * 64));
+#pragma unroll
+        for (int nt = 0; nt < 4; ++nt) acc[mt][nt] = mfma16<ROUTE>(wf[nt], a, acc[mt][nt]);
+      }
+    });
+    wcur = wnxt;
+    __syncthreads();
+  }
+
+  // ---- epilogue: a lane holds 16 consecutive columns of row mt*16 + i16 ---------------
+  if (!active) return;
+  const int ncol = TILE_N * nc + 16 * b;
+#pragma unroll
+  for (int mt = 0; mt < MTS; ++mt) {
+    const int m = m0 + mt * 16 + i16;
+    if (m < p.M) {
+      uint32_t o[8];
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {          // column offset 4r + nt
+        o[2 * r + 0] = pack_out<ROUTE>(acc[mt][0][r], acc[mt][1][r]);
+        o[2 * r + 1] = pack_out<ROUTE>(acc[mt][2][r], acc[mt][3][r]);
+      }
+      u4_t* dst = reinterpret_cast<u4_t*>(p.C + (int64_t)m * p.N + ncol);
+      dst[0] = (u4_t){o[0], o[1], o[2], o[3]};
+      dst[1] = (u4_t){o[4], o[5], o[6], o[7]};
+    }
+  }
+}
+
 #define QG_CAT2(a, b) a##b
 #define QG_CAT(a, b) QG_CAT2(a, b)
-int QG_CAT(large_launch_wt, QG_WT)(const GemmParams&, int, int, hipStream_t) { return QG_EUNSUPPORTED; }
+
+template <int ROUTE, int BM>
+static int launch_bm(const GemmParams& p, hipStream_t st) {
+  const int tiles_m = (p.M + BM - 1) / BM;
+  const int tiles_n = (p.N + LARGE_BN - 1) / LARGE_BN;
+  const int total = tiles_m * tiles_n;
+  const int per_xcd = (total + 7) / 8;
+  const size_t lds_bytes = 2 * LargeLds<BM>::BUF;
+  auto kern = large_kernel<QG_WT, ROUTE, BM>;
+  static bool attr_done = false;   // raise the dynamic LDS limit once per instantiation
+  if (!attr_done) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)lds_bytes) != hipSuccess)
+      return QG_EHIP;
+    attr_done = true;
+  }
+  hipLaunchKernelGGL(kern, dim3((unsigned)(8 * per_xcd)), dim3(256), lds_bytes, st, p, tiles_m, tiles_n, per_xcd);
+  return hipGetLastError() == hipSuccess ? QG_OK : QG_EHIP;
 }
+
+template <int ROUTE>
+static int launch_route(const GemmParams& p, int bm, hipStream_t st) {
+  if (bm == 0) bm = (p.M > 128) ? 256 : 128;
+  if (bm == 128) return launch_bm<ROUTE, 128>(p, st);
+  if (bm == 256) return launch_bm<ROUTE, 256>(p, st);
+  return QG_EINVAL;
+}
+
+int QG_CAT(large_launch_wt, QG_WT)(const GemmParams& p, int route, int bm, hipStream_t st) {
+  return route == ROUTE_F16 ? launch_route<ROUTE_F16>(p, bm, st) : launch_route<ROUTE_BF16>(p, bm, st);
+}
+
+}  // namespace qg

@@ -56,7 +56,8 @@ __global__ __launch_bounds__(SMALL_WAVES * 64) void small_kernel(GemmParams p) {
   constexpr int BITS = D::BITS, RAW = D::RAW;
   constexpr int STAGES = SmallCfg<BITS, MT>::STAGES;
 
-  const int tid = threadIdx.x, l = tid & 63, w = tid >> 6;
+  const int tid = threadIdx.x, l = tid & 63;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, kept in a scalar register
   const int b = l >> 4, i16 = l & 15;
   const int nc = blockIdx.x, split = blockIdx.y;
   const int KC = p.K / TILE_K, NCH = p.N / TILE_N;
@@ -80,7 +81,7 @@ __global__ __launch_bounds__(SMALL_WAVES * 64) void small_kernel(GemmParams p) {
   };
   Stage st[STAGES];
 
-  auto issue = [&](Stage& s, int c) {
+  auto issue = [&](Stage& s, int c) __attribute__((always_inline)) {
     const uint4* src = wstrip + (int64_t)c * (64 * BITS) + l;
 #pragma unroll
     for (int i = 0; i < BITS; ++i) {
@@ -112,14 +113,14 @@ __global__ __launch_bounds__(SMALL_WAVES * 64) void small_kernel(GemmParams p) {
   typename D::Uniform u;
   u.init();
 
-  auto compute = [&](const Stage& s) {
+  auto compute = [&](const Stage& s) __attribute__((always_inline)) {
     typename D::Consts gc0, gc1;
     D::make_consts(gc0, s.s0, s.z0, p.zbias, p.scale_bf16);
     if (two_groups) D::make_consts(gc1, s.s1, s.z1, p.zbias, p.scale_bf16);
     else gc1 = gc0;
-    static_for<4>([&](auto Jc) {
+    static_for<4>([&](auto Jc) __attribute__((always_inline)) {
       constexpr int J = decltype(Jc)::value;
-      static_for<4>([&](auto NTc) {
+      static_for<4>([&](auto NTc) __attribute__((always_inline)) {
         constexpr int NT = decltype(NTc)::value;
         uint32_t o[4];
         D::template frag<J, NT>(s.r, (J < 2) ? gc0 : gc1, u, o);
@@ -132,7 +133,7 @@ __global__ __launch_bounds__(SMALL_WAVES * 64) void small_kernel(GemmParams p) {
 
   // chunk index of my i-th chunk; indices past the end re-load my last chunk
   // (valid memory, result unused) so that the ring needs no branches on loads
-  auto chunk_of = [&](int i) { return c0 + w + min(i, mine - 1) * SMALL_WAVES; };
+  auto chunk_of = [&](int i) __attribute__((always_inline)) { return c0 + w + min(i, mine - 1) * SMALL_WAVES; };
 
   if (mine > 0) {
 #pragma unroll
@@ -173,27 +174,37 @@ __global__ __launch_bounds__(SMALL_WAVES * 64) void small_kernel(GemmParams p) {
 
   const int ncol = TILE_N * nc + 16 * b + idx0;   // columns ncol, ncol+1 of row mt*16 + i16
   if (p.splitk > 1) {
+    // Partial tiles cross workgroups (and XCDs, whose L2s are not coherent with
+    // each other) through device-scope relaxed atomics: such stores write
+    // through and such loads bypass the local caches, so no cache-wide
+    // write-back or invalidate is needed.  Order: my stores complete (the
+    // barrier waits for them), then one arrival count per workgroup; the
+    // workgroup that counts splitk-1 earlier arrivals sums all tiles in split
+    // order, so the result does not depend on arrival order.
     float* tile = p.ws + ((int64_t)split * NCH + nc) * (MT * 1024);
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-      for (int e = 0; e < 2; ++e) tile[mt * 1024 + (idx0 + e) * 64 + l] = sum[mt][e];
-    __threadfence();
+      for (int e = 0; e < 2; ++e)
+        __hip_atomic_store(tile + mt * 1024 + (idx0 + e) * 64 + l, sum[mt][e], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    // a workgroup barrier alone does not wait for outstanding global stores
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
-    if (tid == 0) s_last = (atomicAdd(&p.tickets[nc], 1u) == (unsigned)(p.splitk - 1));
+    if (tid == 0)
+      s_last = (__hip_atomic_fetch_add(&p.tickets[nc], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (unsigned)(p.splitk - 1));
     __syncthreads();
     if (!s_last) return;
-    __threadfence();
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
       for (int e = 0; e < 2; ++e) {
         float t = 0.f;
         for (int sp = 0; sp < p.splitk; ++sp)
-          t += __builtin_nontemporal_load(p.ws + ((int64_t)sp * NCH + nc) * (MT * 1024) + mt * 1024 + (idx0 + e) * 64 + l);
+          t += __hip_atomic_load(p.ws + ((int64_t)sp * NCH + nc) * (MT * 1024) + mt * 1024 + (idx0 + e) * 64 + l,
+                                 __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         sum[mt][e] = t;
       }
-    if (tid == 0) p.tickets[nc] = 0u;             // leave the counter ready for the next call
+    if (tid == 0) __hip_atomic_store(&p.tickets[nc], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next call
   }
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) {

@@ -6,7 +6,7 @@
 namespace qg {
 template <int N, class F>
 __device__ __forceinline__ void static_for(F&& f) {
-  [&]<int... I>(std::integer_sequence<int, I...>) {
+  [&]<int... I>(std::integer_sequence<int, I...>) __attribute__((always_inline)) {
     (f(std::integral_constant<int, I>{}), ...);
   }(std::make_integer_sequence<int, N>{});
 }

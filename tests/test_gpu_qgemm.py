@@ -109,3 +109,48 @@ def test_empty_m_and_bad_arguments():
     with pytest.raises(B.QgError):      # group 32 has no kernel
         s = torch.ones((4, 64), dtype=torch.float16, device="cuda")
         B.qgemm(P.d_A, P.d_packed, s, None, P.wtype, 32, 64)
+
+
+# ------------------------------------------------------------------ tiled path
+@pytest.mark.parametrize("bm", [128, 256])
+@pytest.mark.parametrize("M,K,N", [(200, 512, 256), (257, 384, 320), (65, 128, 64), (512, 1024, 512)])
+def test_tiled_path_ragged_shapes(M, K, N, bm):
+    from paper_2504_12984_amd import binding as B
+    case = WL.Case(f"tiled_{M}_{K}_{N}_{bm}", M, K, N, U, 5, group=64, act="bf16", scale_dtype="bf16",
+                   zero=16, seed=8700 + M)
+    P = Prepared(case)
+    B.qg_set_knob(2, bm)
+    assert_c_close(P.gpu_c(), P.oracle_c(), case.name)
+
+
+@pytest.mark.parametrize("act", ["f16", "bf16"])
+@pytest.mark.parametrize("kind,bits,e,m", [(U, 1, 0, 0), (I, 2, 0, 0), (U, 3, 0, 0), (I, 4, 0, 0), (U, 6, 0, 0),
+                                           (I, 7, 0, 0), (U, 8, 0, 0), (F, 4, 2, 1), (F, 6, 3, 2), (F, 8, 4, 3)])
+def test_tiled_path_weight_types(kind, bits, e, m, act):
+    case = WL.Case(f"tiled_t{kind}_{bits}_{act}", 130, 640, 192, kind, bits, e, m, group=128, act=act,
+                   scale_dtype="f16", zero=(1 << (bits - 1)) if kind == U else None, seed=8800 + bits)
+    P = Prepared(case)
+    assert_c_close(P.gpu_c(), P.oracle_c(), case.name)
+
+
+def test_both_paths_agree_with_the_oracle_on_the_same_small_problem():
+    from paper_2504_12984_amd import binding as B
+    case = WL.Case("both_paths", 48, 768, 256, U, 6, group=128, act="bf16", scale_dtype="bf16", zero=32, seed=8900)
+    P = Prepared(case)
+    ref = P.oracle_c()
+    for path in (1, 2):
+        B.qg_set_knob(0, path)
+        assert_c_close(P.gpu_c(), ref, f"path {path}")
+
+
+def test_tiled_path_one_hot_rows_bit_exact():
+    from paper_2504_12984_amd import binding as B
+    case = WL.Case("tiled_onehot", 256, 256, 128, I, 6, group=128, act="bf16", scale_dtype="f16", zero=None, seed=8950)
+    inp = WL.make_inputs(case)
+    A = torch.zeros((256, 256), dtype=torch.bfloat16)
+    A[torch.arange(256), torch.arange(256)] = 1.0
+    inp["A"] = A
+    P = Prepared(case, inp)
+    _, wbits = P.oracle_w()
+    B.qg_set_knob(0, 2)
+    assert np.array_equal(bits_of(P.gpu_c()), wbits)
