@@ -195,6 +195,7 @@ int qgemm(const void* A, const void* packed_W, const void* scales, const uint8_t
   p.zbias = (t.kind == QG_INT) ? (1 << (t.bits - 1)) : 0;
   p.scale_bf16 = (scale_dtype == QG_BF16);
   p.splitk = 1; p.chunks_per_split = (int)(K / TILE_K);
+  if (!set_group_index(p)) return QG_EUNSUPPORTED;
 
   int path = g_knob[0];
   if (path == 0) path = (M <= 64) ? 1 : 2;

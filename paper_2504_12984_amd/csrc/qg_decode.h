@@ -152,6 +152,20 @@ struct Decoder<WT, ROUTE_F16> {
     }
   }
 
+  // one register (two values) of the MFMA operand: pair T, which belongs to sub-tile nt
+  template <int T>
+  static __device__ __forceinline__ uint32_t pair(const uint32_t (&r)[RAW], const Consts& gc, const Uniform& u, int nt) {
+    if constexpr (!IS_FLOAT) {
+      uint32_t x = int_pair_magic<BITS, T>(r, u.magic);
+      return u32((as_h2(x) - gc.c[Pos<BITS, T>::widx][nt]) * gc.s[nt]);
+    } else {
+      constexpr int ADJ = 15 - ((1 << (EB - 1)) - 1);
+      const _Float16 a = (_Float16)(float)(1 << ADJ);
+      const h2_t adj = {a, a};
+      return u32((as_h2(float_pair_raw<BITS, EB, MB, T>(r)) * adj) * gc.s[nt]);
+    }
+  }
+
   // the four registers (8 values) lane feeds to the MFMA for k-step J, sub-tile NT
   template <int J, int NT>
   static __device__ __forceinline__ void frag(const uint32_t (&r)[RAW], const Consts& gc, const Uniform& u, uint32_t (&out)[4]) {
@@ -205,8 +219,11 @@ struct Decoder<WT, ROUTE_BF16> {
 #pragma unroll
     for (int nt = 0; nt < 4; ++nt) {
       uint32_t s16 = (nt & 1) ? (sw[nt >> 1] >> 16) : (sw[nt >> 1] & 0xffffu);
-      float s = scale_bf16 ? __builtin_bit_cast(float, s16 << 16)
-                           : (float)__builtin_bit_cast(_Float16, (uint16_t)s16);
+      // widen the 16-bit scale exactly; both forms are computed and one is
+      // selected with a mask so that no branch lands in the pipelined loops
+      const uint32_t from_h = __builtin_bit_cast(uint32_t, (float)__builtin_bit_cast(_Float16, (uint16_t)s16));
+      const uint32_t sel = scale_bf16 ? 0xffffffffu : 0u;
+      float s = __builtin_bit_cast(float, ((s16 << 16) & sel) | (from_h & ~sel));
       if constexpr (!IS_FLOAT) {
         gc.s[nt] = s;
         float z = (float)(int)(((zraw >> (8 * nt)) & 0xffu) + (uint32_t)zbias);
@@ -222,6 +239,20 @@ struct Decoder<WT, ROUTE_BF16> {
   static __device__ __forceinline__ uint32_t pk_bf16(float lo, float hi) {
     f2_t f = {lo, hi};
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, b2_t));
+  }
+
+  // one register (two values) of the MFMA operand: pair T, which belongs to sub-tile nt
+  template <int T>
+  static __device__ __forceinline__ uint32_t pair(const uint32_t (&r)[RAW], const Consts& gc, const Uniform& u, int nt) {
+    if constexpr (!IS_FLOAT) {
+      h2_t x = as_h2(int_pair_magic<BITS, T>(r, u.magic));
+      constexpr int w = Pos<BITS, T>::widx;
+      return pk_bf16(__builtin_fmaf((float)x.x, gc.s[nt], gc.ncs[w][nt]),
+                     __builtin_fmaf((float)x.y, gc.s[nt], gc.ncs[w][nt]));
+    } else {
+      h2_t x = as_h2(float_pair_raw<BITS, EB, MB, T>(r));
+      return pk_bf16((float)x.x * gc.s[nt], (float)x.y * gc.s[nt]);
+    }
   }
 
   template <int J, int NT>

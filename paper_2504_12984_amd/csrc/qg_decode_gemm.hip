@@ -91,7 +91,7 @@ __global__ __launch_bounds__(NW * 64) void decode_kernel(GemmParams p) {
       uint4 q = src[i * 64];
       s.r[4 * i + 0] = q.x; s.r[4 * i + 1] = q.y; s.r[4 * i + 2] = q.z; s.r[4 * i + 3] = q.w;
     }
-    const int g0 = (c * TILE_K) / p.group;
+    const int g0 = (p.group == 64) ? 2 * c : ((c >> p.gshift) & p.gmask);
     s.s0 = *reinterpret_cast<const uint2*>(p.S + (int64_t)g0 * p.N + n0);
     if constexpr (TWO_GROUPS) {
       s.s1 = *reinterpret_cast<const uint2*>(p.S + (int64_t)(g0 + 1) * p.N + n0);

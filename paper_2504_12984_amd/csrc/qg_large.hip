@@ -36,6 +36,15 @@ __device__ __forceinline__ f4_t mfma16(u4_t w, u4_t a, f4_t c) {
     return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(b8_t, w), __builtin_bit_cast(b8_t, a), c, 0, 0, 0);
 }
 
+// acc += w . a with the accumulator pinned to accumulation registers
+template <int ROUTE>
+__device__ __forceinline__ void mfma16_acc(f4_t& acc, const u4_t& w, const u4_t& a) {
+  if constexpr (ROUTE == ROUTE_F16)
+    asm volatile("v_mfma_f32_16x16x32_f16 %0, %1, %2, %0" : "+a"(acc) : "v"(w), "v"(a));
+  else
+    asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(w), "v"(a));
+}
+
 template <int ROUTE>
 __device__ __forceinline__ uint32_t pack_out(float lo, float hi) {
   f2_t f = {lo, hi};
@@ -55,7 +64,7 @@ struct LargeLds {
   static constexpr int BUF = 4 * SLICE;
 };
 
-template <int WT, int ROUTE, int BM>
+template <int WT, int ROUTE, bool TWO_GROUPS, int BM>
 __global__ __launch_bounds__(256) void large_kernel(GemmParams p, int tiles_m, int tiles_n, int per_xcd) {
   typedef Decoder<WT, ROUTE> D;
   constexpr int BITS = D::BITS, RAW = D::RAW;
@@ -83,7 +92,9 @@ __global__ __launch_bounds__(256) void large_kernel(GemmParams p, int tiles_m, i
   const bool active = ncw < NCH;
   const int nc = active ? ncw : NCH - 1;                 // idle wavefronts shadow a valid strip
   const int n0 = TILE_N * nc + 4 * i16;
-  const bool two_groups = (p.group == 64);
+  // no zero-points: read (valid) scale bytes instead and mask them away
+  const uint8_t* zbase = p.Z ? p.Z : reinterpret_cast<const uint8_t*>(p.S);
+  const uint32_t zmask = p.Z ? 0xffffffffu : 0u;
 
   // ---- A staging: thread t moves pieces q = t + 256*i, row = q/4, piece = q%4 ---------
   const uint16_t* a_src[PIECES];
@@ -91,11 +102,11 @@ __global__ __launch_bounds__(256) void large_kernel(GemmParams p, int tiles_m, i
 #pragma unroll
   for (int i = 0; i < PIECES; ++i) {
     const int q = tid + 256 * i, row = q >> 2, pc = q & 3;
-    a_src[i] = p.A + (int64_t)min(m0 + row, p.M - 1) * p.K + 8 * pc;
+    a_src[i] = p.A + (int64_t)min(m0 + row, p.M - 1) * p.K + 8 * pc;   // rows past M shadow row M-1
     a_dst[i] = row * 64 + 16 * (pc ^ ((row >> 2) & 3));
   }
   u4_t stage[2][PIECES];
-  auto a_issue = [&](int set, int kstep) __attribute__((always_inline)) {   // kstep = 4*chunk + slice, clamped to the last one
+  auto a_issue = [&](int set, int kstep) __attribute__((always_inline)) {   // kstep = 4*chunk + slice
     const int ks = min(kstep, 4 * KC - 1);
 #pragma unroll
     for (int i = 0; i < PIECES; ++i) stage[set][i] = *reinterpret_cast<const u4_t*>(a_src[i] + ks * 32);
@@ -112,27 +123,27 @@ __global__ __launch_bounds__(256) void large_kernel(GemmParams p, int tiles_m, i
     uint2 s0, s1;
     uint32_t z0, z1;
   };
-  WStage wcur, wnxt;
-  const uint4* wstrip = reinterpret_cast<const uint4*>(p.W + (int64_t)nc * KC * (1024 * BITS));
+  const uint4* wstrip = reinterpret_cast<const uint4*>(p.W + (int64_t)nc * KC * (1024 * BITS)) + l;
   auto w_issue = [&](WStage& s, int c) __attribute__((always_inline)) {
     c = min(c, KC - 1);
-    const uint4* src = wstrip + (int64_t)c * (64 * BITS) + l;
+    const uint4* src = wstrip + (int64_t)c * (64 * BITS);
 #pragma unroll
     for (int i = 0; i < BITS; ++i) {
       uint4 q = src[i * 64];
       s.r[4 * i + 0] = q.x; s.r[4 * i + 1] = q.y; s.r[4 * i + 2] = q.z; s.r[4 * i + 3] = q.w;
     }
-    const int g0 = (c * TILE_K) / p.group;
+    const int g0 = TWO_GROUPS ? 2 * c : ((c >> p.gshift) & p.gmask);
     s.s0 = *reinterpret_cast<const uint2*>(p.S + (int64_t)g0 * p.N + n0);
-    s.z0 = p.Z ? *reinterpret_cast<const uint32_t*>(p.Z + (int64_t)g0 * p.N + n0) : 0u;
-    if (two_groups) {
+    s.z0 = *reinterpret_cast<const uint32_t*>(zbase + (int64_t)g0 * p.N + n0);
+    if constexpr (TWO_GROUPS) {
       s.s1 = *reinterpret_cast<const uint2*>(p.S + (int64_t)(g0 + 1) * p.N + n0);
-      s.z1 = p.Z ? *reinterpret_cast<const uint32_t*>(p.Z + (int64_t)(g0 + 1) * p.N + n0) : 0u;
-    } else {
-      s.s1 = s.s0; s.z1 = s.z0;
+      s.z1 = *reinterpret_cast<const uint32_t*>(zbase + (int64_t)(g0 + 1) * p.N + n0);
     }
   };
 
+  // Accumulators live in the accumulation registers (AGPRs) for the whole
+  // kernel; the matrix instruction is issued through asm so that the register
+  // allocator cannot shuttle them through vector registers.
   f4_t acc[MTS][4];
 #pragma unroll
   for (int mt = 0; mt < MTS; ++mt)
@@ -143,48 +154,91 @@ __global__ __launch_bounds__(256) void large_kernel(GemmParams p, int tiles_m, i
   u.init();
 
   // ---- prologue: chunk 0's A slab into buffer 0, ring primed for chunk 1 --------------
-  w_issue(wcur, 0);
+  WStage wA, wB;
+  w_issue(wA, 0);
   a_issue(0, 0); a_issue(1, 1);
   a_commit(0, 0, 0); a_issue(0, 2);
   a_commit(1, 0, 1); a_issue(1, 3);
   a_commit(0, 0, 2); a_issue(0, 4);     // slice 0 of chunk 1
   a_commit(1, 0, 3); a_issue(1, 5);     // slice 1 of chunk 1
-  __syncthreads();
 
   // my A fragment of row-tile mt, k-step slice j: piece b of row mt*16 + i16
   const int a_rd = i16 * 64 + 16 * (b ^ ((i16 >> 2) & 3));
 
-  for (int kc = 0; kc < KC; ++kc) {
-    const int cur = kc & 1, nxt = cur ^ 1;
-    w_issue(wnxt, kc + 1);
-    typename D::Consts gc0, gc1;
-    D::make_consts(gc0, wcur.s0, wcur.z0, p.zbias, p.scale_bf16);
-    if (two_groups) D::make_consts(gc1, wcur.s1, wcur.z1, p.zbias, p.scale_bf16);
-    else gc1 = gc0;
+  // Weight fragments are unpacked one k-step ahead of their use, and the unpack
+  // of step J+1 is spread over the MFMAs of step J (one pair per 16-row tile),
+  // so the vector ALU works in the shadow of the matrix pipeline.  Fragments
+  // ping-pong between two register sets by k-step parity, weight stages and
+  // their constants by chunk parity (the chunk loop is unrolled by two).
+  typename D::Consts gA0, gA1, gB0, gB1;
+  D::make_consts(gA0, wA.s0, wA.z0 & zmask, p.zbias, p.scale_bf16);
+  if constexpr (TWO_GROUPS) D::make_consts(gA1, wA.s1, wA.z1 & zmask, p.zbias, p.scale_bf16);
+  u4_t wf[2][4];
+  static_for<4>([&](auto NTc) __attribute__((always_inline)) {
+    constexpr int NT = decltype(NTc)::value;
+    uint32_t o[4];
+    D::template frag<0, NT>(wA.r, gA0, u, o);
+    wf[0][NT] = (u4_t){o[0], o[1], o[2], o[3]};
+  });
+  __syncthreads();
+
+  // one chunk: weights wc (constants gc0/gc1) are consumed, wn is loaded and its
+  // constants gn0/gn1 built; CUR is the LDS buffer holding this chunk's A slab
+  auto chunk = [&](auto CURc, WStage& wc, WStage& wn, typename D::Consts& gc0, typename D::Consts& gc1,
+                   typename D::Consts& gn0, typename D::Consts& gn1, int kc) __attribute__((always_inline)) {
+    constexpr int CUR = decltype(CURc)::value, NXT = CUR ^ 1;
+    w_issue(wn, kc + 1);
     static_for<4>([&](auto Jc) __attribute__((always_inline)) {
       constexpr int J = decltype(Jc)::value;
+      constexpr int JN = (J + 1) & 3;
       // A slab of the next chunk: commit the slice loaded two k-steps ago, then
       // start the load that will be committed two k-steps from now
-      a_commit(J & 1, nxt, J);
+      a_commit(J & 1, NXT, J);
       a_issue(J & 1, 4 * (kc + 1) + J + 2);
-      u4_t wf[4];
-      static_for<4>([&](auto NTc) __attribute__((always_inline)) {
-        constexpr int NT = decltype(NTc)::value;
-        uint32_t o[4];
-        D::template frag<J, NT>(wcur.r, (J < 2) ? gc0 : gc1, u, o);
-        wf[NT] = (u4_t){o[0], o[1], o[2], o[3]};
-      });
-      const uint8_t* abase = lds + cur * L::BUF + J * L::SLICE + a_rd;
-#pragma unroll
-      for (int mt = 0; mt < MTS; ++mt) {
-        u4_t a = *reinterpret_cast<const u4_t*>(abase + mt * (16 * 64));
-#pragma unroll
-        for (int nt = 0; nt < 4; ++nt) acc[mt][nt] = mfma16<ROUTE>(wf[nt], a, acc[mt][nt]);
+      if constexpr (J == 3) {
+        D::make_consts(gn0, wn.s0, wn.z0 & zmask, p.zbias, p.scale_bf16);
+        if constexpr (TWO_GROUPS) D::make_consts(gn1, wn.s1, wn.z1 & zmask, p.zbias, p.scale_bf16);
       }
+      const uint8_t* abase = lds + CUR * L::BUF + J * L::SLICE + a_rd;
+      u4_t a_cur = *reinterpret_cast<const u4_t*>(abase);
+      uint32_t nf[4][4];                 // fragment of k-step J+1 under construction
+      auto unpack_one = [&](auto Rc) __attribute__((always_inline)) {
+        constexpr int R = decltype(Rc)::value, PNT = R / 4, PV = R % 4;
+        constexpr int T = (JN * 4 + PNT) * 4 + PV;
+        if constexpr (J < 3) nf[PNT][PV] = D::template pair<T>(wc.r, (TWO_GROUPS && JN >= 2) ? gc1 : gc0, u, PNT);
+        else                 nf[PNT][PV] = D::template pair<T>(wn.r, gn0, u, PNT);
+      };
+      static_for<MTS>([&](auto MTc) __attribute__((always_inline)) {
+        constexpr int MT = decltype(MTc)::value;
+        u4_t a_nxt = a_cur;
+        if constexpr (MT + 1 < MTS) a_nxt = *reinterpret_cast<const u4_t*>(abase + (MT + 1) * (16 * 64));
+        // 16 pairs over MTS row tiles
+        static_for<16 / MTS>([&](auto Qc) __attribute__((always_inline)) {
+          unpack_one(std::integral_constant<int, MT * (16 / MTS) + decltype(Qc)::value>{});
+        });
+#pragma unroll
+        for (int nt = 0; nt < 4; ++nt) mfma16_acc<ROUTE>(acc[MT][nt], wf[J & 1][nt], a_cur);
+        a_cur = a_nxt;
+        // keep the schedule of one row tile inside that row tile: the LDS read
+        // runs one tile ahead, and register live ranges stay short
+        __builtin_amdgcn_sched_barrier(0);
+      });
+#pragma unroll
+      for (int nt = 0; nt < 4; ++nt) wf[JN & 1][nt] = (u4_t){nf[nt][0], nf[nt][1], nf[nt][2], nf[nt][3]};
     });
-    wcur = wnxt;
     __syncthreads();
+  };
+
+  int kc = 0;
+  for (; kc + 2 <= KC; kc += 2) {
+    chunk(std::integral_constant<int, 0>{}, wA, wB, gA0, gA1, gB0, gB1, kc);
+    chunk(std::integral_constant<int, 1>{}, wB, wA, gB0, gB1, gA0, gA1, kc + 1);
   }
+  if (kc < KC) chunk(std::integral_constant<int, 0>{}, wA, wB, gA0, gA1, gB0, gB1, kc);
+
+  // the matrix pipeline may still be writing the accumulators (the compiler
+  // does not see the asm MFMAs, so it inserts no wait states of its own)
+  asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
 
   // ---- epilogue: a lane holds 16 consecutive columns of row mt*16 + i16 ---------------
   if (!active) return;
@@ -209,14 +263,14 @@ __global__ __launch_bounds__(256) void large_kernel(GemmParams p, int tiles_m, i
 #define QG_CAT2(a, b) a##b
 #define QG_CAT(a, b) QG_CAT2(a, b)
 
-template <int ROUTE, int BM>
+template <int ROUTE, bool TG, int BM>
 static int launch_bm(const GemmParams& p, hipStream_t st) {
   const int tiles_m = (p.M + BM - 1) / BM;
   const int tiles_n = (p.N + LARGE_BN - 1) / LARGE_BN;
   const int total = tiles_m * tiles_n;
   const int per_xcd = (total + 7) / 8;
   const size_t lds_bytes = 2 * LargeLds<BM>::BUF;
-  auto kern = large_kernel<QG_WT, ROUTE, BM>;
+  auto kern = large_kernel<QG_WT, ROUTE, TG, BM>;
   static bool attr_done = false;   // raise the dynamic LDS limit once per instantiation
   if (!attr_done) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -231,8 +285,9 @@ static int launch_bm(const GemmParams& p, hipStream_t st) {
 template <int ROUTE>
 static int launch_route(const GemmParams& p, int bm, hipStream_t st) {
   if (bm == 0) bm = (p.M > 128) ? 256 : 128;
-  if (bm == 128) return launch_bm<ROUTE, 128>(p, st);
-  if (bm == 256) return launch_bm<ROUTE, 256>(p, st);
+  const bool tg = (p.group == 64);
+  if (bm == 128) return tg ? launch_bm<ROUTE, true, 128>(p, st) : launch_bm<ROUTE, false, 128>(p, st);
+  if (bm == 256) return tg ? launch_bm<ROUTE, true, 256>(p, st) : launch_bm<ROUTE, false, 256>(p, st);
   return QG_EINVAL;
 }
 

@@ -93,7 +93,7 @@ __global__ __launch_bounds__(SMALL_WAVES * 64) void small_kernel(GemmParams p) {
 #pragma unroll
       for (int j = 0; j < 4; ++j)
         s.a[mt][j] = *reinterpret_cast<const u4_t*>(arow[mt] + c * TILE_K + 32 * j);
-    const int g0 = (c * TILE_K) / p.group;
+    const int g0 = (p.group == 64) ? 2 * c : ((c >> p.gshift) & p.gmask);
     s.s0 = *reinterpret_cast<const uint2*>(p.S + (int64_t)g0 * p.N + n0);
     s.z0 = p.Z ? *reinterpret_cast<const uint32_t*>(p.Z + (int64_t)g0 * p.N + n0) : 0u;
     if (two_groups) {
