@@ -152,6 +152,26 @@ struct Decoder<WT, ROUTE_F16> {
     }
   }
 
+  // The same pair in three separately schedulable phases (extract / centre or
+  // re-bias / scale-and-round), so that a caller can slot them between matrix
+  // instructions.
+  typedef h2_t Mid;
+  template <int T>
+  static __device__ __forceinline__ uint32_t pair_e(const uint32_t (&r)[RAW], const Uniform& u) {
+    if constexpr (!IS_FLOAT) return int_pair_magic<BITS, T>(r, u.magic);
+    else return float_pair_raw<BITS, EB, MB, T>(r);
+  }
+  template <int T>
+  static __device__ __forceinline__ Mid pair_s(uint32_t x, const Consts& gc, int nt) {
+    if constexpr (!IS_FLOAT) return as_h2(x) - gc.c[Pos<BITS, T>::widx][nt];
+    else {
+      constexpr int ADJ = 15 - ((1 << (EB - 1)) - 1);
+      const _Float16 a = (_Float16)(float)(1 << ADJ);
+      return as_h2(x) * (h2_t){a, a};
+    }
+  }
+  static __device__ __forceinline__ uint32_t pair_p(Mid m, const Consts& gc, int nt) { return u32(m * gc.s[nt]); }
+
   // one register (two values) of the MFMA operand: pair T, which belongs to sub-tile nt
   template <int T>
   static __device__ __forceinline__ uint32_t pair(const uint32_t (&r)[RAW], const Consts& gc, const Uniform& u, int nt) {
@@ -240,6 +260,24 @@ struct Decoder<WT, ROUTE_BF16> {
     f2_t f = {lo, hi};
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, b2_t));
   }
+
+  typedef f2_t Mid;
+  template <int T>
+  static __device__ __forceinline__ uint32_t pair_e(const uint32_t (&r)[RAW], const Uniform& u) {
+    if constexpr (!IS_FLOAT) return int_pair_magic<BITS, T>(r, u.magic);
+    else return float_pair_raw<BITS, EB, MB, T>(r);
+  }
+  template <int T>
+  static __device__ __forceinline__ Mid pair_s(uint32_t xb, const Consts& gc, int nt) {
+    h2_t x = as_h2(xb);
+    if constexpr (!IS_FLOAT) {
+      constexpr int w = Pos<BITS, T>::widx;
+      return (f2_t){__builtin_fmaf((float)x.x, gc.s[nt], gc.ncs[w][nt]), __builtin_fmaf((float)x.y, gc.s[nt], gc.ncs[w][nt])};
+    } else {
+      return (f2_t){(float)x.x * gc.s[nt], (float)x.y * gc.s[nt]};
+    }
+  }
+  static __device__ __forceinline__ uint32_t pair_p(Mid m, const Consts&, int) { return pk_bf16(m.x, m.y); }
 
   // one register (two values) of the MFMA operand: pair T, which belongs to sub-tile nt
   template <int T>

@@ -187,40 +187,64 @@ __global__ __launch_bounds__(256) void large_kernel(GemmParams p, int tiles_m, i
   auto chunk = [&](auto CURc, WStage& wc, WStage& wn, typename D::Consts& gc0, typename D::Consts& gc1,
                    typename D::Consts& gn0, typename D::Consts& gn1, int kc) __attribute__((always_inline)) {
     constexpr int CUR = decltype(CURc)::value, NXT = CUR ^ 1;
+    constexpr int PB = 16 / MTS;                       // pairs unpacked per row tile
     w_issue(wn, kc + 1);
+    // A fragments: flat index f = J*MTS + MT over the chunk, read two tiles ahead
+    const uint8_t* abase = lds + CUR * L::BUF + a_rd;
+    auto a_read = [&](int f) __attribute__((always_inline)) {
+      return *reinterpret_cast<const u4_t*>(abase + (f / MTS) * L::SLICE + (f % MTS) * (16 * 64));
+    };
+    u4_t ar[3];
+    ar[0] = a_read(0);
+    ar[1] = a_read(1);
     static_for<4>([&](auto Jc) __attribute__((always_inline)) {
       constexpr int J = decltype(Jc)::value;
       constexpr int JN = (J + 1) & 3;
-      // A slab of the next chunk: commit the slice loaded two k-steps ago, then
-      // start the load that will be committed two k-steps from now
-      a_commit(J & 1, NXT, J);
-      a_issue(J & 1, 4 * (kc + 1) + J + 2);
       if constexpr (J == 3) {
         D::make_consts(gn0, wn.s0, wn.z0 & zmask, p.zbias, p.scale_bf16);
         if constexpr (TWO_GROUPS) D::make_consts(gn1, wn.s1, wn.z1 & zmask, p.zbias, p.scale_bf16);
       }
-      const uint8_t* abase = lds + CUR * L::BUF + J * L::SLICE + a_rd;
-      u4_t a_cur = *reinterpret_cast<const u4_t*>(abase);
       uint32_t nf[4][4];                 // fragment of k-step J+1 under construction
-      auto unpack_one = [&](auto Rc) __attribute__((always_inline)) {
-        constexpr int R = decltype(Rc)::value, PNT = R / 4, PV = R % 4;
-        constexpr int T = (JN * 4 + PNT) * 4 + PV;
-        if constexpr (J < 3) nf[PNT][PV] = D::template pair<T>(wc.r, (TWO_GROUPS && JN >= 2) ? gc1 : gc0, u, PNT);
-        else                 nf[PNT][PV] = D::template pair<T>(wn.r, gn0, u, PNT);
-      };
       static_for<MTS>([&](auto MTc) __attribute__((always_inline)) {
         constexpr int MT = decltype(MTc)::value;
-        u4_t a_nxt = a_cur;
-        if constexpr (MT + 1 < MTS) a_nxt = *reinterpret_cast<const u4_t*>(abase + (MT + 1) * (16 * 64));
-        // 16 pairs over MTS row tiles
-        static_for<16 / MTS>([&](auto Qc) __attribute__((always_inline)) {
-          unpack_one(std::integral_constant<int, MT * (16 / MTS) + decltype(Qc)::value>{});
+        constexpr int F = J * MTS + MT;
+        if constexpr (F + 2 < 4 * MTS) ar[(F + 2) % 3] = a_read(F + 2);
+        // A slab of the next chunk, one 16-byte piece per thread every 4th row
+        // tile: commit the piece loaded two k-steps ago, then start the load
+        // that will be committed two k-steps from now
+        if constexpr (MT % 4 == 0 && MT / 4 < PIECES) {
+          constexpr int I = MT / 4;
+          *reinterpret_cast<u4_t*>(lds + NXT * L::BUF + J * L::SLICE + a_dst[I]) = stage[J & 1][I];
+          stage[J & 1][I] = *reinterpret_cast<const u4_t*>(a_src[I] + min(4 * (kc + 1) + J + 2, 4 * KC - 1) * 32);
+        }
+        const typename D::Consts& g = (J < 3) ? ((TWO_GROUPS && JN >= 2) ? gc1 : gc0) : gn0;
+        const uint32_t (&rw)[RAW] = (J < 3) ? wc.r : wn.r;
+        uint32_t xe[PB];
+        typename D::Mid mid[PB];
+        // MFMA / unpack phases alternate; the barriers pin that order so that
+        // each VALU group issues in the shadow of the preceding matrix instruction
+        mfma16_acc<ROUTE>(acc[MT][0], wf[J & 1][0], ar[F % 3]);
+        __builtin_amdgcn_sched_barrier(0);
+        static_for<PB>([&](auto Qc) __attribute__((always_inline)) {
+          constexpr int Q = decltype(Qc)::value, R = MT * PB + Q;
+          xe[Q] = D::template pair_e<(JN * 4 + R / 4) * 4 + R % 4>(rw, u);
         });
-#pragma unroll
-        for (int nt = 0; nt < 4; ++nt) mfma16_acc<ROUTE>(acc[MT][nt], wf[J & 1][nt], a_cur);
-        a_cur = a_nxt;
-        // keep the schedule of one row tile inside that row tile: the LDS read
-        // runs one tile ahead, and register live ranges stay short
+        __builtin_amdgcn_sched_barrier(0);
+        mfma16_acc<ROUTE>(acc[MT][1], wf[J & 1][1], ar[F % 3]);
+        __builtin_amdgcn_sched_barrier(0);
+        static_for<PB>([&](auto Qc) __attribute__((always_inline)) {
+          constexpr int Q = decltype(Qc)::value, R = MT * PB + Q;
+          mid[Q] = D::template pair_s<(JN * 4 + R / 4) * 4 + R % 4>(xe[Q], g, R / 4);
+        });
+        __builtin_amdgcn_sched_barrier(0);
+        mfma16_acc<ROUTE>(acc[MT][2], wf[J & 1][2], ar[F % 3]);
+        __builtin_amdgcn_sched_barrier(0);
+        static_for<PB>([&](auto Qc) __attribute__((always_inline)) {
+          constexpr int Q = decltype(Qc)::value, R = MT * PB + Q;
+          nf[R / 4][R % 4] = D::pair_p(mid[Q], g, R / 4);
+        });
+        __builtin_amdgcn_sched_barrier(0);
+        mfma16_acc<ROUTE>(acc[MT][3], wf[J & 1][3], ar[F % 3]);
         __builtin_amdgcn_sched_barrier(0);
       });
 #pragma unroll
