@@ -164,7 +164,7 @@ def main():
         ach = alg_bytes / (launch_ms * 1e-3) / 1e9
         roof = {"bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": None,
-                "kernel": "qg::small_kernel", "avg_launch_us": round(launch_ms * 1e3, 3),
+                "kernel": "qg::decode_kernel" if all(c.M <= 16 for c in cases) else "qg::small_kernel", "avg_launch_us": round(launch_ms * 1e3, 3),
                 "algorithmic_bytes_per_launch": int(alg_bytes)}
     else:
         metric, unit, value = "effective_tflops", "TFLOP/s", tflops
