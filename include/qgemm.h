@@ -110,8 +110,8 @@ QG_API int qdequant(const void* packed_W, const void* scales, const uint8_t* zer
 /* C[M,N] (row-major, `act`) = A[M,K] (row-major, `act`) . dequant(W).
  * Arguments as for qdequant; M >= 1 is arbitrary, C is overwritten.
  * Path choice (by M) is internal: M <= 64 streams the weights once through
- * a split-K wavefront-per-tile kernel; larger M uses the LDS-staged tiled
- * kernel. */
+ * a split-K kernel (1, 2 or 4 tiles of 16 rows per wavefront); larger M uses
+ * the LDS-staged tiled kernel. */
 QG_API int qgemm(const void* A, const void* packed_W, const void* scales, const uint8_t* zeros,
           qg_wtype t, int layout, int act, int scale_dtype, int64_t group,
           int64_t M, int64_t N, int64_t K, void* C, void* stream);
@@ -119,8 +119,8 @@ QG_API int qgemm(const void* A, const void* packed_W, const void* scales, const 
 /* Optional: path/tuning override for experiments (0 = automatic).  Returns the
  * previous value.  knob 0: forced path (1 = small-M kernel, 2 = tiled kernel);
  * knob 1: forced split-K factor of the small-M kernels; knob 2: forced row-tile
- * (128 / 256) of the tiled kernel; knob 3: pipeline variant + 1 of the M <= 16
- * kernel. */
+ * (128 / 256) of the tiled kernel; knob 3: pipeline variant of the M <= 64
+ * kernel (10*row tiles + 0/1 for 8/4 wavefronts per strip). */
 QG_API int qg_set_knob(int knob, int value);
 
 #ifdef __cplusplus

@@ -14,7 +14,6 @@ int launch_repack(const uint8_t*, int, int, int, uint32_t, uint8_t*, hipStream_t
 
 #define QG_DECL(i)                                                            \
   int dequant_launch_wt##i(const DequantParams&, int, hipStream_t);           \
-  int small_launch_wt##i(const GemmParams&, int, int, hipStream_t);           \
   int decode_launch_wt##i(const GemmParams&, int, int, hipStream_t);          \
   int decode_waves_wt##i(int);                                                \
   int large_launch_wt##i(const GemmParams&, int, int, hipStream_t);
@@ -25,9 +24,6 @@ typedef int (*dq_fn)(const DequantParams&, int, hipStream_t);
 typedef int (*gm_fn)(const GemmParams&, int, int, hipStream_t);
 #define QG_ENT(i) dequant_launch_wt##i,
 static const dq_fn kDequant[NUM_WT] = {QG_FOR_ALL_WT(QG_ENT)};
-#undef QG_ENT
-#define QG_ENT(i) small_launch_wt##i,
-static const gm_fn kSmall[NUM_WT] = {QG_FOR_ALL_WT(QG_ENT)};
 #undef QG_ENT
 #define QG_ENT(i) large_launch_wt##i,
 static const gm_fn kLarge[NUM_WT] = {QG_FOR_ALL_WT(QG_ENT)};
@@ -202,13 +198,13 @@ int qgemm(const void* A, const void* packed_W, const void* scales, const uint8_t
   if (path == 1 && M > 64) return QG_EINVAL;
 
   if (path == 1) {
-    const bool decode = (M <= 16);            // M <= 16: streaming kernel; 17..64: register-blocked kernel
-    const int mt = M <= 16 ? 1 : (M <= 32 ? 2 : 4);
     const int KC = (int)(K / TILE_K), NCH = (int)(N / TILE_N);
-    // M <= 16 pipeline variants: 8 wavefronts per strip for short K (few chunks per
-    // wavefront, more loads in flight at once), 4 wavefronts otherwise
-    const int variant = g_knob[3] > 0 ? g_knob[3] - 1 : (KC <= 32 ? 1 : 3);
-    const int waves = decode ? kDecodeWaves[wt](variant) : 8;
+    const int mt = M <= 16 ? 1 : (M <= 32 ? 2 : 4);
+    // 8 wavefronts per strip for one row tile and short K (few chunks per wavefront,
+    // more loads in flight at once), 4 wavefronts otherwise
+    int variant = 10 * mt + ((mt == 1 && KC <= 32) ? 0 : 1);
+    if (g_knob[3] > 0) variant = g_knob[3];
+    const int waves = kDecodeWaves[wt](variant);
     // Split K over workgroups only when the column strips alone cannot fill the
     // 256 CUs, and never below 4 chunks per wavefront.
     int splitk = g_knob[1];
@@ -227,7 +223,7 @@ int qgemm(const void* A, const void* packed_W, const void* scales, const uint8_t
       if (rc != QG_OK) return rc;
       p.ws = w->partial; p.tickets = w->tickets;
     }
-    return decode ? kDecode[wt](p, route, variant, st) : kSmall[wt](p, route, mt, st);
+    return kDecode[wt](p, route, variant, st);
   }
   return kLarge[wt](p, route, g_knob[2], st);
 }

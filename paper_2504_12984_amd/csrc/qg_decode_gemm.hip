@@ -1,4 +1,4 @@
-// Decode-sized matmul, M <= 16: the weights are streamed from HBM exactly once
+// Decode-sized matmul, M <= 64 (one, two or four tiles of 16 rows): the weights are streamed from HBM exactly once
 // and the kernel is built to keep that stream saturated.
 //
 // One workgroup of NW wavefronts owns one 64-column strip of W and one slab of
@@ -33,6 +33,14 @@ typedef _Float16 h8_t __attribute__((ext_vector_type(8)));
 typedef __bf16 b8_t __attribute__((ext_vector_type(8)));
 typedef float f4_t __attribute__((ext_vector_type(4)));
 
+// Weights are used once: load them with the streaming (non-temporal) policy so that
+// they do not push the re-used A rows out of the vector cache and L2 (measured:
+// 5-10 % shorter kernels at 4..8 bits, M = 16).
+__device__ __forceinline__ uint4 stream_load(const uint4* p) {
+  u4_t v = __builtin_nontemporal_load(reinterpret_cast<const u4_t*>(p));
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+
 template <int ROUTE>
 __device__ __forceinline__ f4_t mfma16(u4_t w, u4_t a, f4_t c) {
   if constexpr (ROUTE == ROUTE_F16)
@@ -48,7 +56,7 @@ __device__ __forceinline__ uint32_t pack_out(float lo, float hi) {
   else return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, b2_t));
 }
 
-template <int WT, int ROUTE, bool TWO_GROUPS, int NW, int DEPTH>
+template <int WT, int ROUTE, bool TWO_GROUPS, int NW, int DEPTH, int MT>
 __global__ __launch_bounds__(NW * 64) void decode_kernel(GemmParams p) {
   typedef Decoder<WT, ROUTE> D;
   constexpr int BITS = D::BITS, RAW = D::RAW;
@@ -64,15 +72,17 @@ __global__ __launch_bounds__(NW * 64) void decode_kernel(GemmParams p) {
   const int n0 = TILE_N * nc + 4 * i16;
 
   const uint4* wstrip = reinterpret_cast<const uint4*>(p.W + (int64_t)nc * KC * (1024 * BITS)) + l;
-  // rows past M re-read row M-1; their results are never stored
-  const uint16_t* arow = p.A + (int64_t)min(i16, p.M - 1) * p.K + 8 * b;
+  // MT tiles of 16 rows; rows past M re-read row M-1, their results are never stored
+  const uint16_t* arow[MT];
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt) arow[mt] = p.A + (int64_t)min(mt * 16 + i16, p.M - 1) * p.K + 8 * b;
   // no zero-points: read (valid) scale bytes instead and mask them away
   const uint8_t* zbase = p.Z ? p.Z : reinterpret_cast<const uint8_t*>(p.S);
   const uint32_t zmask = p.Z ? 0xffffffffu : 0u;
 
   struct Stage {
     uint32_t r[RAW];
-    u4_t a[4];
+    u4_t a[MT][4];
     uint2 s0, s1;
     uint32_t z0, z1;
   };
@@ -84,11 +94,13 @@ __global__ __launch_bounds__(NW * 64) void decode_kernel(GemmParams p) {
     __builtin_amdgcn_sched_barrier(0);         // stay below the last use of the entry being refilled,
                                                // so that the refill reuses the same registers
 #pragma unroll
-    for (int j = 0; j < 4; ++j) s.a[j] = *reinterpret_cast<const u4_t*>(arow + c * TILE_K + 32 * j);
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) s.a[mt][j] = *reinterpret_cast<const u4_t*>(arow[mt] + c * TILE_K + 32 * j);
     const uint4* src = wstrip + (int64_t)c * (64 * BITS);
 #pragma unroll
     for (int i = 0; i < BITS; ++i) {
-      uint4 q = src[i * 64];
+      uint4 q = stream_load(src + i * 64);
       s.r[4 * i + 0] = q.x; s.r[4 * i + 1] = q.y; s.r[4 * i + 2] = q.z; s.r[4 * i + 3] = q.w;
     }
     const int g0 = (p.group == 64) ? 2 * c : ((c >> p.gshift) & p.gmask);
@@ -101,9 +113,11 @@ __global__ __launch_bounds__(NW * 64) void decode_kernel(GemmParams p) {
     __builtin_amdgcn_sched_barrier(0);
   };
 
-  f4_t acc[4];
+  f4_t acc[MT][4];
 #pragma unroll
-  for (int nt = 0; nt < 4; ++nt) acc[nt] = (f4_t){0.f, 0.f, 0.f, 0.f};
+  for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+    for (int nt = 0; nt < 4; ++nt) acc[mt][nt] = (f4_t){0.f, 0.f, 0.f, 0.f};
 
   typename D::Uniform u;
   u.init();
@@ -120,7 +134,9 @@ __global__ __launch_bounds__(NW * 64) void decode_kernel(GemmParams p) {
         constexpr int NT = decltype(NTc)::value;
         uint32_t o[4];
         D::template frag<J, NT>(s.r, (TWO_GROUPS && J >= 2) ? gc1 : gc0, u, o);
-        acc[NT] = mfma16<ROUTE>((u4_t){o[0], o[1], o[2], o[3]}, s.a[J], acc[NT]);
+        const u4_t wf = {o[0], o[1], o[2], o[3]};      // unpacked once, used by every row tile
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) acc[mt][NT] = mfma16<ROUTE>(wf, s.a[mt][J], acc[mt][NT]);
       });
     });
   };
@@ -151,23 +167,27 @@ __global__ __launch_bounds__(NW * 64) void decode_kernel(GemmParams p) {
     });
   }
 
-  // ---- reduce over the NW wavefronts through LDS ---------------------------------------
+  // ---- reduce over the NW wavefronts through LDS, one 16-row tile at a time -----------------
   __shared__ float red[NW * 16 * 64];                      // [NW][16 column offsets][64 lanes]
   __shared__ int s_last;
   constexpr int PER = 16 / NW;                             // column offsets per thread
   const int idx0 = PER * w;
+  float sum[MT][PER];
 #pragma unroll
-  for (int nt = 0; nt < 4; ++nt)
+  for (int mt = 0; mt < MT; ++mt) {
+    if (mt) __syncthreads();
 #pragma unroll
-    for (int r = 0; r < 4; ++r) red[(w * 16 + 4 * r + nt) * 64 + l] = acc[nt][r];   // column offset 4r + nt
-  __syncthreads();
-  float sum[PER];
+    for (int nt = 0; nt < 4; ++nt)
 #pragma unroll
-  for (int e = 0; e < PER; ++e) {
-    float t = 0.f;
+      for (int r = 0; r < 4; ++r) red[(w * 16 + 4 * r + nt) * 64 + l] = acc[mt][nt][r];   // column offset 4r + nt
+    __syncthreads();
 #pragma unroll
-    for (int ww = 0; ww < NW; ++ww) t += red[(ww * 16 + idx0 + e) * 64 + l];
-    sum[e] = t;
+    for (int e = 0; e < PER; ++e) {
+      float t = 0.f;
+#pragma unroll
+      for (int ww = 0; ww < NW; ++ww) t += red[(ww * 16 + idx0 + e) * 64 + l];
+      sum[mt][e] = t;
+    }
   }
 
   if (p.splitk > 1) {
@@ -178,57 +198,74 @@ __global__ __launch_bounds__(NW * 64) void decode_kernel(GemmParams p) {
     // one arrival count per workgroup; the workgroup that counts splitk-1
     // earlier arrivals sums all tiles in split order, so the result does not
     // depend on arrival order.
-    float* tile = p.ws + ((int64_t)split * NCH + nc) * 1024;
+    float* tile = p.ws + ((int64_t)split * NCH + nc) * (MT * 1024);
 #pragma unroll
-    for (int e = 0; e < PER; ++e)
-      __hip_atomic_store(tile + (idx0 + e) * 64 + l, sum[e], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int e = 0; e < PER; ++e)
+        __hip_atomic_store(tile + mt * 1024 + (idx0 + e) * 64 + l, sum[mt][e], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // a workgroup barrier alone does not wait for global stores
     __syncthreads();
     if (tid == 0)
       s_last = (__hip_atomic_fetch_add(&p.tickets[nc], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (unsigned)(p.splitk - 1));
     __syncthreads();
     if (!s_last) return;
+    // all loads of a split are issued before the first add (independent accumulators)
 #pragma unroll
-    for (int e = 0; e < PER; ++e) {
-      float t = 0.f;
-      for (int sp = 0; sp < p.splitk; ++sp)
-        t += __hip_atomic_load(p.ws + ((int64_t)sp * NCH + nc) * 1024 + (idx0 + e) * 64 + l, __ATOMIC_RELAXED,
-                               __HIP_MEMORY_SCOPE_AGENT);
-      sum[e] = t;
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int e = 0; e < PER; ++e) sum[mt][e] = 0.f;
+    for (int sp = 0; sp < p.splitk; ++sp) {
+      const float* src = p.ws + ((int64_t)sp * NCH + nc) * (MT * 1024);
+      float v[MT][PER];
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int e = 0; e < PER; ++e)
+          v[mt][e] = __hip_atomic_load(src + mt * 1024 + (idx0 + e) * 64 + l, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int e = 0; e < PER; ++e) sum[mt][e] += v[mt][e];
     }
     if (tid == 0) __hip_atomic_store(&p.tickets[nc], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next call
   }
-  if (i16 < p.M) {
-    uint16_t* dst = p.C + (int64_t)i16 * p.N + TILE_N * nc + 16 * b + idx0;
 #pragma unroll
-    for (int e = 0; e < PER; e += 2) *reinterpret_cast<uint32_t*>(dst + e) = pack_out<ROUTE>(sum[e], sum[e + 1]);
+  for (int mt = 0; mt < MT; ++mt) {
+    const int m = mt * 16 + i16;
+    if (m < p.M) {
+      uint16_t* dst = p.C + (int64_t)m * p.N + TILE_N * nc + 16 * b + idx0;
+#pragma unroll
+      for (int e = 0; e < PER; e += 2) *reinterpret_cast<uint32_t*>(dst + e) = pack_out<ROUTE>(sum[mt][e], sum[mt][e + 1]);
+    }
   }
 }
 
 #define QG_CAT2(a, b) a##b
 #define QG_CAT(a, b) QG_CAT2(a, b)
 
-template <int ROUTE, bool TG, int NW, int DEPTH>
+template <int ROUTE, bool TG, int NW, int DEPTH, int MT>
 static int launch_cfg(const GemmParams& p, hipStream_t st) {
-  auto kern = decode_kernel<QG_WT, ROUTE, TG, NW, DEPTH>;
+  auto kern = decode_kernel<QG_WT, ROUTE, TG, NW, DEPTH, MT>;
   dim3 grid((unsigned)(p.N / TILE_N), (unsigned)p.splitk), block(NW * 64);
   hipLaunchKernelGGL(kern, grid, block, 0, st, p);
   return hipGetLastError() == hipSuccess ? QG_OK : QG_EHIP;
 }
 
+// variant = 10 * (row tiles: 1, 2, 4) + (0: 8 wavefronts per strip, 1: 4 wavefronts)
 template <int ROUTE, bool TG>
 static int launch_variant(const GemmParams& p, int variant, hipStream_t st) {
   switch (variant) {
-    case 0: return launch_cfg<ROUTE, TG, 4, (wt_bits(QG_WT) <= 5 ? 4 : 3)>(p, st);
-    case 1: return launch_cfg<ROUTE, TG, 8, 2>(p, st);
-    case 2: return launch_cfg<ROUTE, TG, 8, 3>(p, st);
-    case 3: return launch_cfg<ROUTE, TG, 4, 2>(p, st);
+    case 10: return launch_cfg<ROUTE, TG, 8, 2, 1>(p, st);
+    case 11: return launch_cfg<ROUTE, TG, 4, 2, 1>(p, st);
+    case 21: return launch_cfg<ROUTE, TG, 4, 2, 2>(p, st);
+    case 41: return launch_cfg<ROUTE, TG, 4, 2, 4>(p, st);
     default: return QG_EINVAL;
   }
 }
 
 // number of wavefronts per workgroup of a variant (the host sizes split-K with it)
-int QG_CAT(decode_waves_wt, QG_WT)(int variant) { return (variant == 1 || variant == 2) ? 8 : 4; }
+int QG_CAT(decode_waves_wt, QG_WT)(int variant) { return (variant % 10 == 0) ? 8 : 4; }
 
 int QG_CAT(decode_launch_wt, QG_WT)(const GemmParams& p, int route, int variant, hipStream_t st) {
   const bool tg = (p.group == 64);
