@@ -8,7 +8,7 @@
 namespace qg {
 
 int launch_pack_codes(const uint8_t*, int, int64_t, uint8_t*, hipStream_t);
-int launch_repack(const uint8_t*, int, int, int, uint32_t, uint8_t*, hipStream_t);
+int launch_repack(const uint8_t*, int, int, int, uint32_t, int, uint8_t*, hipStream_t);
 
 #define QG_FOR_ALL_WT(X) X(0) X(1) X(2) X(3) X(4) X(5) X(6) X(7) X(8) X(9) X(10) X(11) X(12) X(13)
 
@@ -147,7 +147,8 @@ int repack(const void* canonical, qg_wtype t, int layout, int64_t K, int64_t N, 
   if (K <= 0 || N <= 0 || K % TILE_K || N % TILE_N || K > (1 << 24) || N > (1 << 24)) return QG_EINVAL;
   if (!aligned16(packed_out)) return QG_EINVAL;
   uint32_t flip = (t.kind == QG_INT) ? (1u << (t.bits - 1)) : 0u;
-  return launch_repack(static_cast<const uint8_t*>(canonical), t.bits, (int)K, (int)N, flip,
+  const int natural = (wt >= 0 && wt_natural(wt)) ? 1 : 0;   // types decoded by the hardware converts
+  return launch_repack(static_cast<const uint8_t*>(canonical), t.bits, (int)K, (int)N, flip, natural,
                        static_cast<uint8_t*>(packed_out), static_cast<hipStream_t>(stream));
 }
 

@@ -47,6 +47,12 @@ __host__ __device__ constexpr int wt_ebits(int wt) {
 }
 __host__ __device__ constexpr int wt_mbits(int wt) { return wt < 8 ? 0 : wt_bits(wt) - 1 - wt_ebits(wt); }
 
+// Float types the hardware converts by itself (OCP FP4 e2m1, FP6 e3m2, FP8 e4m3 on
+// gfx950).  Their codes sit in the lane's bytes in plain order -- code c of the lane at
+// bits [c*bits, (c+1)*bits), pair t = codes (2t, 2t+1) -- which is the order the
+// packed convert instructions read; every other type uses the two 16-bit streams.
+__host__ __device__ constexpr bool wt_natural(int wt) { return wt == 9 || wt == 11 || wt == 13; }
+
 inline int wt_index(const qg_wtype& t) {
   if (t.bits < 1 || t.bits > 8) return -1;
   if (t.kind == QG_UINT || t.kind == QG_INT) return (t.ebits == 0 && t.mbits == 0) ? t.bits - 1 : -1;

@@ -106,6 +106,27 @@ __device__ __forceinline__ uint32_t float_pair_raw(const uint32_t (&r)[4 * BITS]
   }
 }
 
+// ===================== float codes with a hardware convert ======================
+// Pair T as two exact half-precision values (every e2m1 / e3m2 / e4m3 value is
+// representable in fp16).  e3m2 converts a whole k-step (32 codes in 6 registers)
+// at once; the compiler merges the identical calls made for the 16 pairs of a step.
+typedef _Float16 h32_t __attribute__((ext_vector_type(32)));
+typedef uint32_t u6_t __attribute__((ext_vector_type(6)));
+template <int WT, int T>
+__device__ __forceinline__ h2_t natural_pair(const uint32_t (&r)[4 * wt_bits(WT)]) {
+  if constexpr (WT == 13) {
+    return __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(r[T / 2], 1.0f, (T % 2) == 1);
+  } else if constexpr (WT == 9) {
+    return __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(r[T / 4], 1.0f, T % 4);
+  } else {
+    static_assert(WT == 11, "no hardware convert for this type");
+    constexpr int G = T / 16;
+    const u6_t six = {r[6 * G + 0], r[6 * G + 1], r[6 * G + 2], r[6 * G + 3], r[6 * G + 4], r[6 * G + 5]};
+    const h32_t all = __builtin_amdgcn_cvt_scalef32_pk32_f16_bf6(six, 1.0f);   // "bf6" is e3m2 ("fp6" is e2m3)
+    return (h2_t){all[2 * (T % 16)], all[2 * (T % 16) + 1]};
+  }
+}
+
 // ============================ per-group constants ================================
 // sraw: the lane's four 16-bit scales (columns 4*i + 0..3), zraw: its four
 // zero-point bytes.  Built once per (chunk, group), used by 8 or 16 pairs each.
@@ -117,6 +138,7 @@ template <int WT>
 struct Decoder<WT, ROUTE_F16> {
   static constexpr int BITS = wt_bits(WT);
   static constexpr bool IS_FLOAT = wt_is_float(WT);
+  static constexpr bool NATURAL = wt_natural(WT);
   static constexpr int EB = wt_ebits(WT), MB = wt_mbits(WT);
   static constexpr int WN = Lay<BITS>::WN;
   static constexpr int RAW = 4 * BITS;
@@ -158,12 +180,14 @@ struct Decoder<WT, ROUTE_F16> {
   typedef h2_t Mid;
   template <int T>
   static __device__ __forceinline__ uint32_t pair_e(const uint32_t (&r)[RAW], const Uniform& u) {
-    if constexpr (!IS_FLOAT) return int_pair_magic<BITS, T>(r, u.magic);
+    if constexpr (NATURAL) return u32(natural_pair<WT, T>(r));
+    else if constexpr (!IS_FLOAT) return int_pair_magic<BITS, T>(r, u.magic);
     else return float_pair_raw<BITS, EB, MB, T>(r);
   }
   template <int T>
   static __device__ __forceinline__ Mid pair_s(uint32_t x, const Consts& gc, int nt) {
-    if constexpr (!IS_FLOAT) return as_h2(x) - gc.c[Pos<BITS, T>::widx][nt];
+    if constexpr (NATURAL) return as_h2(x);
+    else if constexpr (!IS_FLOAT) return as_h2(x) - gc.c[Pos<BITS, T>::widx][nt];
     else {
       constexpr int ADJ = 15 - ((1 << (EB - 1)) - 1);
       const _Float16 a = (_Float16)(float)(1 << ADJ);
@@ -175,7 +199,9 @@ struct Decoder<WT, ROUTE_F16> {
   // one register (two values) of the MFMA operand: pair T, which belongs to sub-tile nt
   template <int T>
   static __device__ __forceinline__ uint32_t pair(const uint32_t (&r)[RAW], const Consts& gc, const Uniform& u, int nt) {
-    if constexpr (!IS_FLOAT) {
+    if constexpr (NATURAL) {
+      return u32(natural_pair<WT, T>(r) * gc.s[nt]);          // exact value, one rounding multiply
+    } else if constexpr (!IS_FLOAT) {
       uint32_t x = int_pair_magic<BITS, T>(r, u.magic);
       return u32((as_h2(x) - gc.c[Pos<BITS, T>::widx][nt]) * gc.s[nt]);
     } else {
@@ -190,7 +216,12 @@ struct Decoder<WT, ROUTE_F16> {
   template <int J, int NT>
   static __device__ __forceinline__ void frag(const uint32_t (&r)[RAW], const Consts& gc, const Uniform& u, uint32_t (&out)[4]) {
     constexpr int T0 = (J * 4 + NT) * 4;
-    if constexpr (!IS_FLOAT) {
+    if constexpr (NATURAL) {
+      out[0] = pair<T0 + 0>(r, gc, u, NT);
+      out[1] = pair<T0 + 1>(r, gc, u, NT);
+      out[2] = pair<T0 + 2>(r, gc, u, NT);
+      out[3] = pair<T0 + 3>(r, gc, u, NT);
+    } else if constexpr (!IS_FLOAT) {
       uint32_t x0 = int_pair_magic<BITS, T0 + 0>(r, u.magic);
       uint32_t x1 = int_pair_magic<BITS, T0 + 1>(r, u.magic);
       uint32_t x2 = int_pair_magic<BITS, T0 + 2>(r, u.magic);
@@ -218,6 +249,7 @@ template <int WT>
 struct Decoder<WT, ROUTE_BF16> {
   static constexpr int BITS = wt_bits(WT);
   static constexpr bool IS_FLOAT = wt_is_float(WT);
+  static constexpr bool NATURAL = wt_natural(WT);
   static constexpr int EB = wt_ebits(WT), MB = wt_mbits(WT);
   static constexpr int WN = Lay<BITS>::WN;
   static constexpr int RAW = 4 * BITS;
@@ -249,6 +281,8 @@ struct Decoder<WT, ROUTE_BF16> {
         float z = (float)(int)(((zraw >> (8 * nt)) & 0xffu) + (uint32_t)zbias);
 #pragma unroll
         for (int w = 0; w < WN; ++w) gc.ncs[w][nt] = -((float)(1 << (10 - w * BITS)) + z) * s;
+      } else if constexpr (NATURAL) {
+        gc.s[nt] = s;
       } else {
         constexpr int ADJ = 15 - ((1 << (EB - 1)) - 1);
         gc.s[nt] = s * (float)(1 << ADJ);
@@ -264,7 +298,8 @@ struct Decoder<WT, ROUTE_BF16> {
   typedef f2_t Mid;
   template <int T>
   static __device__ __forceinline__ uint32_t pair_e(const uint32_t (&r)[RAW], const Uniform& u) {
-    if constexpr (!IS_FLOAT) return int_pair_magic<BITS, T>(r, u.magic);
+    if constexpr (NATURAL) return u32(natural_pair<WT, T>(r));
+    else if constexpr (!IS_FLOAT) return int_pair_magic<BITS, T>(r, u.magic);
     else return float_pair_raw<BITS, EB, MB, T>(r);
   }
   template <int T>
@@ -274,7 +309,8 @@ struct Decoder<WT, ROUTE_BF16> {
       constexpr int w = Pos<BITS, T>::widx;
       return (f2_t){__builtin_fmaf((float)x.x, gc.s[nt], gc.ncs[w][nt]), __builtin_fmaf((float)x.y, gc.s[nt], gc.ncs[w][nt])};
     } else {
-      return (f2_t){(float)x.x * gc.s[nt], (float)x.y * gc.s[nt]};
+      // x * s as fma(x, s, -0): one mixed-precision op; adding -0 keeps the sign of a zero product
+      return (f2_t){__builtin_fmaf((float)x.x, gc.s[nt], -0.0f), __builtin_fmaf((float)x.y, gc.s[nt], -0.0f)};
     }
   }
   static __device__ __forceinline__ uint32_t pair_p(Mid m, const Consts&, int) { return pk_bf16(m.x, m.y); }
@@ -288,8 +324,10 @@ struct Decoder<WT, ROUTE_BF16> {
       return pk_bf16(__builtin_fmaf((float)x.x, gc.s[nt], gc.ncs[w][nt]),
                      __builtin_fmaf((float)x.y, gc.s[nt], gc.ncs[w][nt]));
     } else {
-      h2_t x = as_h2(float_pair_raw<BITS, EB, MB, T>(r));
-      return pk_bf16((float)x.x * gc.s[nt], (float)x.y * gc.s[nt]);
+      h2_t x;
+      if constexpr (NATURAL) x = natural_pair<WT, T>(r);
+      else x = as_h2(float_pair_raw<BITS, EB, MB, T>(r));
+      return pk_bf16(__builtin_fmaf((float)x.x, gc.s[nt], -0.0f), __builtin_fmaf((float)x.y, gc.s[nt], -0.0f));
     }
   }
 
@@ -307,13 +345,10 @@ struct Decoder<WT, ROUTE_BF16> {
       QG_ONE(0) QG_ONE(1) QG_ONE(2) QG_ONE(3)
 #undef QG_ONE
     } else {
-#define QG_ONE(V)                                                                         \
-  {                                                                                       \
-    h2_t x = as_h2(float_pair_raw<BITS, EB, MB, T0 + V>(r));                             \
-    out[V] = pk_bf16((float)x.x * gc.s[NT], (float)x.y * gc.s[NT]);                       \
-  }
-      QG_ONE(0) QG_ONE(1) QG_ONE(2) QG_ONE(3)
-#undef QG_ONE
+      out[0] = pair<T0 + 0>(r, gc, u, NT);
+      out[1] = pair<T0 + 1>(r, gc, u, NT);
+      out[2] = pair<T0 + 2>(r, gc, u, NT);
+      out[3] = pair<T0 + 3>(r, gc, u, NT);
     }
   }
 };

@@ -41,7 +41,7 @@ __device__ __forceinline__ uint32_t fetch_code(const uint8_t* __restrict__ canon
 // lane will find them.
 __global__ __launch_bounds__(256) void repack_kernel(const uint8_t* __restrict__ canon, int64_t canon_bytes,
                                                      uint32_t* __restrict__ out, int bits, int K, int N,
-                                                     uint32_t flip) {
+                                                     uint32_t flip, int natural) {
   const int KC = K / TILE_K;
   const int64_t nchunks = (int64_t)KC * (N / TILE_N);
   int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -50,6 +50,24 @@ __global__ __launch_bounds__(256) void repack_kernel(const uint8_t* __restrict__
   const int l = (int)(gid & 63), b = l >> 4, i16 = l & 15;
   const int nc = (int)(chunk / KC), kc = (int)(chunk % KC);
   uint32_t* dst = out + chunk * (256 * bits);
+  if (natural) {
+    // plain order: code c = 2t + {0 lo, 1 hi} of the lane at bits [c*bits, (c+1)*bits)
+    for (int d = 0; d < 4 * bits; ++d) {
+      uint32_t word = 0;
+      int c0 = (32 * d) / bits, c1 = (32 * d + 31) / bits;
+      if (c1 > 2 * PAIRS - 1) c1 = 2 * PAIRS - 1;
+      for (int c = c0; c <= c1; ++c) {
+        int t = c >> 1, j = t >> 4, nt = (t >> 2) & 3, v = t & 3;
+        int k = TILE_K * kc + 32 * j + 8 * b + 2 * v + (c & 1);
+        int n = TILE_N * nc + 4 * i16 + nt;
+        uint32_t code = fetch_code(canon, canon_bytes, (int64_t)k * N + n, bits);
+        int sh = c * bits - 32 * d;
+        word |= (sh >= 0) ? (code << sh) : (code >> (-sh));
+      }
+      dst[(d >> 2) * 256 + l * 4 + (d & 3)] = word;
+    }
+    return;
+  }
   for (int d = 0; d < 4 * bits; ++d) {
     uint32_t lo = 0, hi = 0;
     int t0 = (16 * d) / bits, t1 = (16 * d + 15) / bits;
@@ -77,12 +95,12 @@ int launch_pack_codes(const uint8_t* codes, int bits, int64_t count, uint8_t* ou
   return hipGetLastError() == hipSuccess ? QG_OK : QG_EHIP;
 }
 
-int launch_repack(const uint8_t* canon, int bits, int K, int N, uint32_t flip, uint8_t* out, hipStream_t st) {
+int launch_repack(const uint8_t* canon, int bits, int K, int N, uint32_t flip, int natural, uint8_t* out, hipStream_t st) {
   int64_t nchunks = (int64_t)(K / TILE_K) * (N / TILE_N);
   int64_t canon_bytes = ((int64_t)K * N * bits + 7) / 8;
   int64_t blocks = (nchunks * 64 + 255) / 256;
   hipLaunchKernelGGL(repack_kernel, dim3((unsigned)blocks), dim3(256), 0, st, canon, canon_bytes,
-                     reinterpret_cast<uint32_t*>(out), bits, K, N, flip);
+                     reinterpret_cast<uint32_t*>(out), bits, K, N, flip, natural);
   return hipGetLastError() == hipSuccess ? QG_OK : QG_EHIP;
 }
 
