@@ -56,8 +56,12 @@ constexpr int LARGE_BN = 256;
 constexpr int LARGE_GROUP_M = 4;   // m-tiles per L2 panel
 
 // LDS: A slab of one chunk = 4 k-step slices, each [BM rows][4 pieces of 16 B];
-// piece p of row r is stored at slot p ^ ((r >> 2) & 3): the 16 lanes that read
-// one piece column of 16 consecutive rows then hit 16 different 4-bank groups.
+// piece p of row r is stored at slot p ^ lds_swizzle(r).  A fragment read takes
+// one piece column of 16 consecutive rows (64-byte row stride = 4 four-bank
+// groups): the swizzle makes the groups distinct both within every aligned run of
+// 8 rows modulo 8 groups (32 banks) and within the 16 rows modulo 16 groups (64
+// banks), whichever way the hardware splits a 16-byte-per-lane read.
+__device__ __forceinline__ int lds_swizzle(int r) { return (((r >> 2) & 1) << 1) | (((r >> 1) ^ (r >> 3)) & 1); }
 template <int BM>
 struct LargeLds {
   static constexpr int SLICE = BM * 64;        // bytes
@@ -103,7 +107,7 @@ __global__ __launch_bounds__(256) void large_kernel(GemmParams p, int tiles_m, i
   for (int i = 0; i < PIECES; ++i) {
     const int q = tid + 256 * i, row = q >> 2, pc = q & 3;
     a_src[i] = p.A + (int64_t)min(m0 + row, p.M - 1) * p.K + 8 * pc;   // rows past M shadow row M-1
-    a_dst[i] = row * 64 + 16 * (pc ^ ((row >> 2) & 3));
+    a_dst[i] = row * 64 + 16 * (pc ^ lds_swizzle(row));
   }
   u4_t stage[2][PIECES];
   auto a_issue = [&](int set, int kstep) __attribute__((always_inline)) {   // kstep = 4*chunk + slice
@@ -163,7 +167,7 @@ __global__ __launch_bounds__(256) void large_kernel(GemmParams p, int tiles_m, i
   a_commit(1, 0, 3); a_issue(1, 5);     // slice 1 of chunk 1
 
   // my A fragment of row-tile mt, k-step slice j: piece b of row mt*16 + i16
-  const int a_rd = i16 * 64 + 16 * (b ^ ((i16 >> 2) & 3));
+  const int a_rd = i16 * 64 + 16 * (b ^ lds_swizzle(i16));
 
   // Weight fragments are unpacked one k-step ahead of their use, and the unpack
   // of step J+1 is spread over the MFMAs of step J (one pair per 16-row tile),
@@ -205,10 +209,44 @@ __global__ __launch_bounds__(256) void large_kernel(GemmParams p, int tiles_m, i
         if constexpr (TWO_GROUPS) D::make_consts(gn1, wn.s1, wn.z1 & zmask, p.zbias, p.scale_bf16);
       }
       uint32_t nf[4][4];                 // fragment of k-step J+1 under construction
+      uint32_t xe[PB];
+      typename D::Mid mid[PB], mid_prev[PB];
+      const typename D::Consts& g = (J < 3) ? ((TWO_GROUPS && JN >= 2) ? gc1 : gc0) : gn0;
+      const uint32_t (&rw)[RAW] = (J < 3) ? wc.r : wn.r;
       static_for<MTS>([&](auto MTc) __attribute__((always_inline)) {
         constexpr int MT = decltype(MTc)::value;
         constexpr int F = J * MTS + MT;
-        if constexpr (F + 2 < 4 * MTS) ar[(F + 2) % 3] = a_read(F + 2);
+        // The matrix pipeline hides two vector instructions per MFMA, no more, so
+        // the unpack of the PB pairs of this row tile is cut into three phases
+        // that sit in different gaps, and the last phase of tile MT runs in tile
+        // MT+1: a consumer never directly follows its producer (the compiler
+        // cannot see through the asm MFMA and would pad such pairs with s_nop).
+        mfma16_acc<ROUTE>(acc[MT][0], wf[J & 1][0], ar[F % 3]);
+        __builtin_amdgcn_sched_barrier(0);
+        static_for<PB>([&](auto Qc) __attribute__((always_inline)) {          // extract
+          constexpr int Q = decltype(Qc)::value, R = MT * PB + Q;
+          xe[Q] = D::template pair_e<(JN * 4 + R / 4) * 4 + R % 4>(rw, u);
+        });
+        __builtin_amdgcn_sched_barrier(0);
+        mfma16_acc<ROUTE>(acc[MT][1], wf[J & 1][1], ar[F % 3]);
+        __builtin_amdgcn_sched_barrier(0);
+        if constexpr (F + 2 < 4 * MTS) ar[(F + 2) % 3] = a_read(F + 2);       // A fragment two tiles ahead
+        if constexpr (MT > 0) {                                               // scale-and-round of the previous tile
+          static_for<PB>([&](auto Qc) __attribute__((always_inline)) {
+            constexpr int Q = decltype(Qc)::value, R = (MT - 1) * PB + Q;
+            nf[R / 4][R % 4] = D::pair_p(mid_prev[Q], g, R / 4);
+          });
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        mfma16_acc<ROUTE>(acc[MT][2], wf[J & 1][2], ar[F % 3]);
+        __builtin_amdgcn_sched_barrier(0);
+        static_for<PB>([&](auto Qc) __attribute__((always_inline)) {          // centre / widen
+          constexpr int Q = decltype(Qc)::value, R = MT * PB + Q;
+          mid[Q] = D::template pair_s<(JN * 4 + R / 4) * 4 + R % 4>(xe[Q], g, R / 4);
+        });
+        __builtin_amdgcn_sched_barrier(0);
+        mfma16_acc<ROUTE>(acc[MT][3], wf[J & 1][3], ar[F % 3]);
+        __builtin_amdgcn_sched_barrier(0);
         // A slab of the next chunk, one 16-byte piece per thread every 4th row
         // tile: commit the piece loaded two k-steps ago, then start the load
         // that will be committed two k-steps from now
@@ -217,35 +255,13 @@ __global__ __launch_bounds__(256) void large_kernel(GemmParams p, int tiles_m, i
           *reinterpret_cast<u4_t*>(lds + NXT * L::BUF + J * L::SLICE + a_dst[I]) = stage[J & 1][I];
           stage[J & 1][I] = *reinterpret_cast<const u4_t*>(a_src[I] + min(4 * (kc + 1) + J + 2, 4 * KC - 1) * 32);
         }
-        const typename D::Consts& g = (J < 3) ? ((TWO_GROUPS && JN >= 2) ? gc1 : gc0) : gn0;
-        const uint32_t (&rw)[RAW] = (J < 3) ? wc.r : wn.r;
-        uint32_t xe[PB];
-        typename D::Mid mid[PB];
-        // MFMA / unpack phases alternate; the barriers pin that order so that
-        // each VALU group issues in the shadow of the preceding matrix instruction
-        mfma16_acc<ROUTE>(acc[MT][0], wf[J & 1][0], ar[F % 3]);
+#pragma unroll
+        for (int q = 0; q < PB; ++q) mid_prev[q] = mid[q];
         __builtin_amdgcn_sched_barrier(0);
-        static_for<PB>([&](auto Qc) __attribute__((always_inline)) {
-          constexpr int Q = decltype(Qc)::value, R = MT * PB + Q;
-          xe[Q] = D::template pair_e<(JN * 4 + R / 4) * 4 + R % 4>(rw, u);
-        });
-        __builtin_amdgcn_sched_barrier(0);
-        mfma16_acc<ROUTE>(acc[MT][1], wf[J & 1][1], ar[F % 3]);
-        __builtin_amdgcn_sched_barrier(0);
-        static_for<PB>([&](auto Qc) __attribute__((always_inline)) {
-          constexpr int Q = decltype(Qc)::value, R = MT * PB + Q;
-          mid[Q] = D::template pair_s<(JN * 4 + R / 4) * 4 + R % 4>(xe[Q], g, R / 4);
-        });
-        __builtin_amdgcn_sched_barrier(0);
-        mfma16_acc<ROUTE>(acc[MT][2], wf[J & 1][2], ar[F % 3]);
-        __builtin_amdgcn_sched_barrier(0);
-        static_for<PB>([&](auto Qc) __attribute__((always_inline)) {
-          constexpr int Q = decltype(Qc)::value, R = MT * PB + Q;
-          nf[R / 4][R % 4] = D::pair_p(mid[Q], g, R / 4);
-        });
-        __builtin_amdgcn_sched_barrier(0);
-        mfma16_acc<ROUTE>(acc[MT][3], wf[J & 1][3], ar[F % 3]);
-        __builtin_amdgcn_sched_barrier(0);
+      });
+      static_for<PB>([&](auto Qc) __attribute__((always_inline)) {            // last tile's scale-and-round
+        constexpr int Q = decltype(Qc)::value, R = (MTS - 1) * PB + Q;
+        nf[R / 4][R % 4] = D::pair_p(mid_prev[Q], g, R / 4);
       });
 #pragma unroll
       for (int nt = 0; nt < 4; ++nt) wf[JN & 1][nt] = (u4_t){nf[nt][0], nf[nt][1], nf[nt][2], nf[nt][3]};
