@@ -63,13 +63,22 @@ typedef enum { QG_F16 = 0, QG_BF16 = 1 } qg_dtype;      /* activation / scale dt
  * e1m1, e2m1, e2m2, e3m2, e3m3, e4m3 (Section "Arbitrary Data Type Support"). */
 typedef struct { int32_t kind, bits, ebits, mbits; } qg_wtype;
 
-/* The one device layout implemented.  W is cut into tiles of 128 (K) x 64 (N)
- * codes; a tile is 1024*bits bytes, read by one 64-lane wavefront as `bits`
- * 16-byte loads per lane, and the lane's 16*bits bytes hold exactly the 128
- * codes that lane feeds to the 16x16x32 matrix instruction (no exchange between
- * lanes, no staging through LDS).  Tiles of one 64-column strip are contiguous
- * along K.  intk codes are stored offset-binary (sign bit flipped). */
+/* Device layouts.  In both, W is cut into tiles of 128 (K) x 64 (N) codes; a tile
+ * is 1024*bits bytes, read by one 64-lane wavefront as `bits` 16-byte loads per
+ * lane, and the lane's 16*bits bytes hold exactly the 128 codes that lane feeds to
+ * the matrix instruction (no exchange between lanes, no staging through LDS).
+ * Tiles of one 64-column strip are contiguous along K.  intk codes are stored
+ * offset-binary (sign bit flipped).  The layouts differ in which 128 codes a lane
+ * owns, i.e. in the matrix instruction the kernels built for them use (the paper
+ * transforms the weight for the program that will read it, Section "Efficient
+ * Low-Precision Weight Loading"):
+ *   QG_LAYOUT_TILE128x64      lane owns 4 columns; 16x16x32 instruction.  Kernels
+ *                             for every M; the choice for decode (small M).
+ *   QG_LAYOUT_TILE128x64_R32  lane owns 2 columns; 32x32x16 instruction.  One
+ *                             tiled kernel for every M, fastest for M >= 128;
+ *                             qgemm needs M*K < 2^31 with it. */
 #define QG_LAYOUT_TILE128x64 0
+#define QG_LAYOUT_TILE128x64_R32 1
 #define QG_TILE_K 128
 #define QG_TILE_N 64
 

@@ -20,6 +20,7 @@ QG_OK, QG_EINVAL, QG_EUNSUPPORTED, QG_EHIP = 0, -1, -2, -3
 QG_UINT, QG_INT, QG_FLOAT = 0, 1, 2
 QG_F16, QG_BF16 = 0, 1
 QG_LAYOUT_TILE128x64 = 0
+QG_LAYOUT_TILE128x64_R32 = 1
 TILE_K, TILE_N = 128, 64
 
 EXPORTS = ("qg_status_string", "qg_last_error", "qg_canonical_bytes", "qgemm_packed_bytes",

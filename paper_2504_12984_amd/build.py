@@ -9,6 +9,7 @@ next to this file.  Objects go to _build/ (not tracked).
 from __future__ import annotations
 
 import os
+import re
 import subprocess
 import sys
 from concurrent.futures import ThreadPoolExecutor
@@ -26,9 +27,34 @@ FLAGS = ["--offload-arch=gfx950", "-std=c++20", "-O3", "-fPIC", "-fvisibility=hi
 
 def _jobs():
     jobs = [("qg_pack.hip", None), ("qg_api.hip", None)]
-    for src in ("qg_dequant.hip", "qg_decode_gemm.hip", "qg_large.hip"):
+    for src in ("qg_dequant.hip", "qg_decode_gemm.hip", "qg_large.hip", "qg_large32.hip"):
         jobs += [(src, wt) for wt in range(NUM_WT)]
     return jobs
+
+
+# The tiled kernels issue their matrix instructions through inline asm, so the
+# compiler does not know when an accumulator is final and would spill or reload one
+# without waiting for the matrix pipeline.  Their register budget is therefore
+# checked at build time: beyond the few dwords of loop-invariant values that are parked
+# across the main loop, nothing may go to scratch memory.
+SPILL_CHECKED = {"qg_large.hip": 32, "qg_large32.hip": 32}    # bytes per lane allowed
+
+
+def _check_scratch(stem, src, remarks):
+    limit = SPILL_CHECKED[src]
+    name = None
+    for ln in remarks.splitlines():
+        m = re.search(r"remark: (.*?) \[-Rpass-analysis", ln)
+        if not m:
+            continue
+        text = m.group(1).strip()
+        if text.startswith("Function Name:"):
+            name = text.split(":", 1)[1].strip()
+        elif text.startswith("ScratchSize") and name:
+            used = int(text.split(":")[1])
+            if used > limit:
+                raise RuntimeError(f"{stem}: kernel {name} spills {used} bytes per lane to scratch "
+                                   f"(limit {limit}); its accumulators are not safe to spill")
 
 
 def _compile(job):
@@ -38,10 +64,18 @@ def _compile(job):
     cmd = [HIPCC, *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
     if wt is not None:
         cmd.insert(-4, f"-DQG_WT={wt}")
+    if src in SPILL_CHECKED:
+        cmd.insert(-4, "-Rpass-analysis=kernel-resource-usage")
     r = subprocess.run(cmd, capture_output=True, text=True)
-    err = "\n".join(ln for ln in r.stderr.splitlines() if "packed-fp32-ops" not in ln)
     if r.returncode != 0:
+        err = "\n".join(ln for ln in r.stderr.splitlines() if "packed-fp32-ops" not in ln)
         raise RuntimeError(f"hipcc failed for {stem}:\n{err}")
+    if src in SPILL_CHECKED:
+        _check_scratch(stem, src, r.stderr)
+    lines = [ln for ln in r.stderr.splitlines() if "packed-fp32-ops" not in ln]
+    if src in SPILL_CHECKED:      # drop the resource remarks and the source excerpts printed with them
+        lines = [ln for ln in lines if "warning:" in ln or "error:" in ln]
+    err = "\n".join(lines)
     return obj, err
 
 

@@ -8,7 +8,7 @@
 namespace qg {
 
 int launch_pack_codes(const uint8_t*, int, int64_t, uint8_t*, hipStream_t);
-int launch_repack(const uint8_t*, int, int, int, uint32_t, int, uint8_t*, hipStream_t);
+int launch_repack(const uint8_t*, int, int, int, uint32_t, int, int, uint8_t*, hipStream_t);
 
 #define QG_FOR_ALL_WT(X) X(0) X(1) X(2) X(3) X(4) X(5) X(6) X(7) X(8) X(9) X(10) X(11) X(12) X(13)
 
@@ -16,7 +16,8 @@ int launch_repack(const uint8_t*, int, int, int, uint32_t, int, uint8_t*, hipStr
   int dequant_launch_wt##i(const DequantParams&, int, hipStream_t);           \
   int decode_launch_wt##i(const GemmParams&, int, int, hipStream_t);          \
   int decode_waves_wt##i(int);                                                \
-  int large_launch_wt##i(const GemmParams&, int, int, hipStream_t);
+  int large_launch_wt##i(const GemmParams&, int, int, hipStream_t);          \
+  int large32_launch_wt##i(const GemmParams&, int, int, hipStream_t);
 QG_FOR_ALL_WT(QG_DECL)
 #undef QG_DECL
 
@@ -27,6 +28,9 @@ static const dq_fn kDequant[NUM_WT] = {QG_FOR_ALL_WT(QG_ENT)};
 #undef QG_ENT
 #define QG_ENT(i) large_launch_wt##i,
 static const gm_fn kLarge[NUM_WT] = {QG_FOR_ALL_WT(QG_ENT)};
+#undef QG_ENT
+#define QG_ENT(i) large32_launch_wt##i,
+static const gm_fn kLarge32[NUM_WT] = {QG_FOR_ALL_WT(QG_ENT)};
 #undef QG_ENT
 #define QG_ENT(i) decode_launch_wt##i,
 static const gm_fn kDecode[NUM_WT] = {QG_FOR_ALL_WT(QG_ENT)};
@@ -85,11 +89,12 @@ static int get_workspace(size_t partial_bytes, size_t ticket_count, hipStream_t 
   return QG_OK;
 }
 
+static bool layout_ok(int layout) { return layout == QG_LAYOUT_TILE128x64 || layout == QG_LAYOUT_TILE128x64_R32; }
 static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 static int check_common(qg_wtype t, int layout, int act, int scale_dtype, int64_t group, int64_t K, int64_t N,
                         int* wt_out, int* route_out) {
-  if (layout != QG_LAYOUT_TILE128x64) return QG_EINVAL;
+  if (!layout_ok(layout)) return QG_EINVAL;
   int wt = wt_index(t);
   if (wt == -2) return QG_EUNSUPPORTED;
   if (wt < 0) return QG_EINVAL;
@@ -127,7 +132,7 @@ size_t qg_canonical_bytes(int bits, int64_t count) {
 }
 
 size_t qgemm_packed_bytes(qg_wtype t, int layout, int64_t K, int64_t N) {
-  if (layout != QG_LAYOUT_TILE128x64 || wt_index(t) == -1) return 0;
+  if (!layout_ok(layout) || wt_index(t) == -1) return 0;
   if (K <= 0 || N <= 0 || K % TILE_K || N % TILE_N) return 0;
   return (size_t)(K * N * t.bits / 8);
 }
@@ -140,7 +145,7 @@ int qg_pack_codes(const uint8_t* codes, int bits, int64_t count, uint8_t* stream
 }
 
 int repack(const void* canonical, qg_wtype t, int layout, int64_t K, int64_t N, void* packed_out, void* stream) {
-  if (layout != QG_LAYOUT_TILE128x64) return QG_EINVAL;
+  if (!layout_ok(layout)) return QG_EINVAL;
   int wt = wt_index(t);
   if (wt == -1) return QG_EINVAL;   // any float split can be re-laid out; only the type must be well formed
   if (!canonical || !packed_out || canonical == packed_out) return QG_EINVAL;
@@ -148,7 +153,7 @@ int repack(const void* canonical, qg_wtype t, int layout, int64_t K, int64_t N, 
   if (!aligned16(packed_out)) return QG_EINVAL;
   uint32_t flip = (t.kind == QG_INT) ? (1u << (t.bits - 1)) : 0u;
   const int natural = (wt >= 0 && wt_natural(wt)) ? 1 : 0;   // types decoded by the hardware converts
-  return launch_repack(static_cast<const uint8_t*>(canonical), t.bits, (int)K, (int)N, flip, natural,
+  return launch_repack(static_cast<const uint8_t*>(canonical), t.bits, (int)K, (int)N, flip, natural, layout,
                        static_cast<uint8_t*>(packed_out), static_cast<hipStream_t>(stream));
 }
 
@@ -164,6 +169,7 @@ int qdequant(const void* packed_W, const void* scales, const uint8_t* zeros, qg_
   p.S = static_cast<const uint16_t*>(scales);
   p.Z = zeros;
   p.out = static_cast<uint16_t*>(W_out);
+  p.layout = layout;
   p.K = (int)K; p.N = (int)N; p.group = (int)group;
   p.zbias = (t.kind == QG_INT) ? (1 << (t.bits - 1)) : 0;
   p.scale_bf16 = (scale_dtype == QG_BF16);
@@ -193,6 +199,12 @@ int qgemm(const void* A, const void* packed_W, const void* scales, const uint8_t
   p.scale_bf16 = (scale_dtype == QG_BF16);
   p.splitk = 1; p.chunks_per_split = (int)(K / TILE_K);
   if (!set_group_index(p)) return QG_EUNSUPPORTED;
+
+  if (layout == QG_LAYOUT_TILE128x64_R32) {
+    // one kernel for every M; its A staging addresses rows with 32-bit byte offsets
+    if ((uint64_t)M * (uint64_t)K * 2u >= (1ull << 32)) return QG_EUNSUPPORTED;
+    return kLarge32[wt](p, route, g_knob[2], st);
+  }
 
   int path = g_knob[0];
   if (path == 0) path = (M <= 64) ? 1 : 2;

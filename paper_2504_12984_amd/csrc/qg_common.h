@@ -27,12 +27,35 @@ namespace qg {
 //     n = 64*nc + 4*i + nt
 // Chunks of one 64-column strip are contiguous along K:
 //     byte offset of chunk (kc, nc) = (nc * (K/128) + kc) * 1024 * BITS
+// A second layout (QG_LAYOUT_TILE128x64_R32) has the same chunks, streams and
+// byte offsets and differs only in which element a pair is: it follows the
+// operand shape of the 32x32x16 matrix instruction, whose lane l feeds row
+// l % 32 with the eight k values 8*(l/32) .. +7:
+//     t = (j*2 + nt)*4 + v,   j in 0..7 (k-step of 16), nt in 0..1, v in 0..3
+//     lane l = 32*h + i:   k = 128*kc + 16*j + 8*h + 2*v + {0, 1},   n = 64*nc + 2*i + nt
 // This is the paper's "reinterpret each tile as the bytes each thread loads and
 // store the tile contiguously" (Section "Efficient Low-Precision Weight
 // Loading"), with T = 64 lanes and n = 16*BITS bytes per lane, so n1 = 16.
 constexpr int TILE_K = QG_TILE_K;
 constexpr int TILE_N = QG_TILE_N;
 constexpr int PAIRS = 64;
+constexpr int NUM_LAYOUT = 2;
+
+// Per-layout shape: columns per lane (NT), k extent of one matrix instruction
+// (K_STEP), steps per chunk, and the element (k of the lo code, n) offsets inside
+// the chunk of pair t of lane l.
+template <int LY>
+struct LayoutOf {
+  static constexpr int NT = LY == 0 ? 4 : 2;
+  static constexpr int K_STEP = LY == 0 ? 32 : 16;
+  static constexpr int STEPS = TILE_K / K_STEP;
+  static constexpr int ROWS = LY == 0 ? 16 : 32;        // lanes per k-block
+  __host__ __device__ static constexpr int t0(int j, int nt) { return (j * NT + nt) * 4; }
+  __host__ __device__ static constexpr int pair_k(int l, int t) { return K_STEP * (t / (4 * NT)) + 8 * (l / ROWS) + 2 * (t & 3); }
+  __host__ __device__ static constexpr int pair_n(int l, int t) { return NT * (l % ROWS) + ((t >> 2) % NT); }
+};
+__host__ __device__ constexpr int pair_k(int layout, int l, int t) { return layout == 0 ? LayoutOf<0>::pair_k(l, t) : LayoutOf<1>::pair_k(l, t); }
+__host__ __device__ constexpr int pair_n(int layout, int l, int t) { return layout == 0 ? LayoutOf<0>::pair_n(l, t) : LayoutOf<1>::pair_n(l, t); }
 
 // ---- weight-type index used to pick a kernel instantiation ---------------------
 // 0..7   integer codes of 1..8 bits (uintk; intk is stored offset-binary and
@@ -78,6 +101,7 @@ struct DequantParams {
   const uint16_t* S;
   const uint8_t* Z;
   uint16_t* out;
+  int layout;
   int K, N, group;
   int zbias;        // added to every zero-point (2^(bits-1) for intk, else 0)
   int scale_bf16;   // scales are bf16 (only with ROUTE_BF16)

@@ -128,14 +128,15 @@ __device__ __forceinline__ h2_t natural_pair(const uint32_t (&r)[4 * wt_bits(WT)
 }
 
 // ============================ per-group constants ================================
-// sraw: the lane's four 16-bit scales (columns 4*i + 0..3), zraw: its four
-// zero-point bytes.  Built once per (chunk, group), used by 8 or 16 pairs each.
-template <int WT, int ROUTE>
+// sraw: the lane's 16-bit scales (its NTL adjacent columns, low bits first), zraw:
+// its zero-point bytes.  Built once per (chunk, group), used by 8 or 16 pairs each.
+template <int WT, int ROUTE, int LY = 0>
 struct Decoder;
 
 // ---- integers, fp16 route:  w = ((2^e + q) - (2^e + z')) * s ------------------
-template <int WT>
-struct Decoder<WT, ROUTE_F16> {
+template <int WT, int LY>
+struct Decoder<WT, ROUTE_F16, LY> {
+  static constexpr int NTL = LayoutOf<LY>::NT;     // columns per lane
   static constexpr int BITS = wt_bits(WT);
   static constexpr bool IS_FLOAT = wt_is_float(WT);
   static constexpr bool NATURAL = wt_natural(WT);
@@ -144,8 +145,8 @@ struct Decoder<WT, ROUTE_F16> {
   static constexpr int RAW = 4 * BITS;
 
   struct Consts {
-    h2_t s[4];
-    h2_t c[WN][4];   // integers: 2^(10-pp) + z'   (floats: unused)
+    h2_t s[NTL];
+    h2_t c[WN][NTL];   // integers: 2^(10-pp) + z'   (floats: unused)
   };
   struct Uniform {
     uint32_t magic[WN];
@@ -158,7 +159,7 @@ struct Decoder<WT, ROUTE_F16> {
   static __device__ __forceinline__ void make_consts(Consts& gc, uint2 sraw, uint32_t zraw, int zbias, int /*scale_bf16*/) {
     uint32_t sw[2] = {sraw.x, sraw.y};
 #pragma unroll
-    for (int nt = 0; nt < 4; ++nt) {
+    for (int nt = 0; nt < NTL; ++nt) {
       uint32_t s16 = (nt & 1) ? (sw[nt >> 1] >> 16) : (sw[nt >> 1] & 0xffffu);
       gc.s[nt] = as_h2(s16 | (s16 << 16));
       if constexpr (!IS_FLOAT) {
@@ -215,7 +216,7 @@ struct Decoder<WT, ROUTE_F16> {
   // the four registers (8 values) lane feeds to the MFMA for k-step J, sub-tile NT
   template <int J, int NT>
   static __device__ __forceinline__ void frag(const uint32_t (&r)[RAW], const Consts& gc, const Uniform& u, uint32_t (&out)[4]) {
-    constexpr int T0 = (J * 4 + NT) * 4;
+    constexpr int T0 = LayoutOf<LY>::t0(J, NT);
     if constexpr (NATURAL) {
       out[0] = pair<T0 + 0>(r, gc, u, NT);
       out[1] = pair<T0 + 1>(r, gc, u, NT);
@@ -245,8 +246,9 @@ struct Decoder<WT, ROUTE_F16> {
 };
 
 // ---- bf16 route:  w = bf16_rne( fma(x, s, -(2^e + z') * s) ), all exact in fp32 --
-template <int WT>
-struct Decoder<WT, ROUTE_BF16> {
+template <int WT, int LY>
+struct Decoder<WT, ROUTE_BF16, LY> {
+  static constexpr int NTL = LayoutOf<LY>::NT;     // columns per lane
   static constexpr int BITS = wt_bits(WT);
   static constexpr bool IS_FLOAT = wt_is_float(WT);
   static constexpr bool NATURAL = wt_natural(WT);
@@ -255,8 +257,8 @@ struct Decoder<WT, ROUTE_BF16> {
   static constexpr int RAW = 4 * BITS;
 
   struct Consts {
-    float s[4];       // integers: scale; floats: scale * 2^(15-bias)
-    float ncs[WN][4];  // integers: -(2^(10-pp) + z') * s, exact (<= 22 bits)
+    float s[NTL];     // integers: scale; floats: scale * 2^(15-bias)
+    float ncs[WN][NTL];  // integers: -(2^(10-pp) + z') * s, exact (<= 22 bits)
   };
   struct Uniform {
     uint32_t magic[WN];
@@ -269,7 +271,7 @@ struct Decoder<WT, ROUTE_BF16> {
   static __device__ __forceinline__ void make_consts(Consts& gc, uint2 sraw, uint32_t zraw, int zbias, int scale_bf16) {
     uint32_t sw[2] = {sraw.x, sraw.y};
 #pragma unroll
-    for (int nt = 0; nt < 4; ++nt) {
+    for (int nt = 0; nt < NTL; ++nt) {
       uint32_t s16 = (nt & 1) ? (sw[nt >> 1] >> 16) : (sw[nt >> 1] & 0xffffu);
       // widen the 16-bit scale exactly; both forms are computed and one is
       // selected with a mask so that no branch lands in the pipelined loops
@@ -333,7 +335,7 @@ struct Decoder<WT, ROUTE_BF16> {
 
   template <int J, int NT>
   static __device__ __forceinline__ void frag(const uint32_t (&r)[RAW], const Consts& gc, const Uniform& u, uint32_t (&out)[4]) {
-    constexpr int T0 = (J * 4 + NT) * 4;
+    constexpr int T0 = LayoutOf<LY>::t0(J, NT);
     if constexpr (!IS_FLOAT) {
 #define QG_ONE(V)                                                                         \
   {                                                                                       \

@@ -11,9 +11,10 @@
 
 namespace qg {
 
-template <int WT, int ROUTE>
+template <int WT, int ROUTE, int LY>
 __global__ __launch_bounds__(256) void dequant_kernel(DequantParams p) {
-  typedef Decoder<WT, ROUTE> D;
+  typedef Decoder<WT, ROUTE, LY> D;
+  typedef LayoutOf<LY> L;
   constexpr int BITS = D::BITS, RAW = D::RAW;
   const int l = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -21,7 +22,6 @@ __global__ __launch_bounds__(256) void dequant_kernel(DequantParams p) {
   const int64_t chunk = (int64_t)blockIdx.x * 4 + wave;
   if (chunk >= (int64_t)KC * (p.N / TILE_N)) return;
   const int nc = (int)(chunk / KC), kc = (int)(chunk % KC);
-  const int b = l >> 4, i16 = l & 15;
 
   uint32_t r[RAW];
   const uint4* src = reinterpret_cast<const uint4*>(p.W + chunk * (1024 * BITS));
@@ -32,21 +32,28 @@ __global__ __launch_bounds__(256) void dequant_kernel(DequantParams p) {
   }
   typename D::Uniform u;
   u.init();
-  const int n0 = TILE_N * nc + 4 * i16;
-  static_for<4>([&](auto Jc) __attribute__((always_inline)) {
+  const int n0 = TILE_N * nc + L::pair_n(l, 0);
+  static_for<L::STEPS>([&](auto Jc) __attribute__((always_inline)) {
     constexpr int J = decltype(Jc)::value;
-    const int g = (TILE_K * kc + 32 * J) / p.group;
-    uint2 sraw = *reinterpret_cast<const uint2*>(p.S + (int64_t)g * p.N + n0);
-    uint32_t zraw = p.Z ? *reinterpret_cast<const uint32_t*>(p.Z + (int64_t)g * p.N + n0) : 0u;
+    const int g = (TILE_K * kc + L::K_STEP * J) / p.group;
+    uint2 sraw;
+    uint32_t zraw = 0u;
+    if constexpr (L::NT == 4) {
+      sraw = *reinterpret_cast<const uint2*>(p.S + (int64_t)g * p.N + n0);
+      if (p.Z) zraw = *reinterpret_cast<const uint32_t*>(p.Z + (int64_t)g * p.N + n0);
+    } else {
+      sraw = make_uint2(*reinterpret_cast<const uint32_t*>(p.S + (int64_t)g * p.N + n0), 0u);
+      if (p.Z) zraw = *reinterpret_cast<const uint16_t*>(p.Z + (int64_t)g * p.N + n0);
+    }
     typename D::Consts gc;
     D::make_consts(gc, sraw, zraw, p.zbias, p.scale_bf16);
-    static_for<4>([&](auto NTc) __attribute__((always_inline)) {
+    static_for<L::NT>([&](auto NTc) __attribute__((always_inline)) {
       constexpr int NT = decltype(NTc)::value;
       uint32_t o[4];
       D::template frag<J, NT>(r, gc, u, o);
 #pragma unroll
       for (int v = 0; v < 4; ++v) {
-        int k = TILE_K * kc + 32 * J + 8 * b + 2 * v;
+        const int k = TILE_K * kc + L::pair_k(l, L::t0(J, NT) + v);
         p.out[(int64_t)k * p.N + n0 + NT] = (uint16_t)(o[v] & 0xffffu);
         p.out[(int64_t)(k + 1) * p.N + n0 + NT] = (uint16_t)(o[v] >> 16);
       }
@@ -57,11 +64,17 @@ __global__ __launch_bounds__(256) void dequant_kernel(DequantParams p) {
 #define QG_CAT2(a, b) a##b
 #define QG_CAT(a, b) QG_CAT2(a, b)
 
+template <int LY>
+static void launch_ly(const DequantParams& p, int route, dim3 grid, dim3 block, hipStream_t st) {
+  if (route == ROUTE_F16) hipLaunchKernelGGL((dequant_kernel<QG_WT, ROUTE_F16, LY>), grid, block, 0, st, p);
+  else                    hipLaunchKernelGGL((dequant_kernel<QG_WT, ROUTE_BF16, LY>), grid, block, 0, st, p);
+}
+
 int QG_CAT(dequant_launch_wt, QG_WT)(const DequantParams& p, int route, hipStream_t st) {
   int64_t nchunks = (int64_t)(p.K / TILE_K) * (p.N / TILE_N);
   dim3 grid((unsigned)((nchunks + 3) / 4)), block(256);
-  if (route == ROUTE_F16) hipLaunchKernelGGL((dequant_kernel<QG_WT, ROUTE_F16>), grid, block, 0, st, p);
-  else                    hipLaunchKernelGGL((dequant_kernel<QG_WT, ROUTE_BF16>), grid, block, 0, st, p);
+  if (p.layout == 0) launch_ly<0>(p, route, grid, block, st);
+  else               launch_ly<1>(p, route, grid, block, st);
   return hipGetLastError() == hipSuccess ? QG_OK : QG_EHIP;
 }
 

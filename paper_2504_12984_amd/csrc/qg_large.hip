@@ -172,24 +172,25 @@ __global__ __launch_bounds__(256) void large_kernel(GemmParams p, int tiles_m, i
   // Weight fragments are unpacked one k-step ahead of their use, and the unpack
   // of step J+1 is spread over the MFMAs of step J (one pair per 16-row tile),
   // so the vector ALU works in the shadow of the matrix pipeline.  Fragments
-  // ping-pong between two register sets by k-step parity, weight stages and
-  // their constants by chunk parity (the chunk loop is unrolled by two).
-  typename D::Consts gA0, gA1, gB0, gB1;
-  D::make_consts(gA0, wA.s0, wA.z0 & zmask, p.zbias, p.scale_bf16);
-  if constexpr (TWO_GROUPS) D::make_consts(gA1, wA.s1, wA.z1 & zmask, p.zbias, p.scale_bf16);
+  // ping-pong between two register sets by k-step parity, weight stages by chunk
+  // parity (the chunk loop is unrolled by two).  Group constants are rebuilt in
+  // place just before their first use: g0 (first half of a chunk, or all of it)
+  // during the last k-step of the chunk before, g1 (second half, group size 64)
+  // during the k-step before the half -- each is dead by then.
+  typename D::Consts g0, g1;
+  D::make_consts(g0, wA.s0, wA.z0 & zmask, p.zbias, p.scale_bf16);
   u4_t wf[2][4];
   static_for<4>([&](auto NTc) __attribute__((always_inline)) {
     constexpr int NT = decltype(NTc)::value;
     uint32_t o[4];
-    D::template frag<0, NT>(wA.r, gA0, u, o);
+    D::template frag<0, NT>(wA.r, g0, u, o);
     wf[0][NT] = (u4_t){o[0], o[1], o[2], o[3]};
   });
   __syncthreads();
 
-  // one chunk: weights wc (constants gc0/gc1) are consumed, wn is loaded and its
-  // constants gn0/gn1 built; CUR is the LDS buffer holding this chunk's A slab
-  auto chunk = [&](auto CURc, WStage& wc, WStage& wn, typename D::Consts& gc0, typename D::Consts& gc1,
-                   typename D::Consts& gn0, typename D::Consts& gn1, int kc) __attribute__((always_inline)) {
+  // one chunk: weights wc are consumed, wn is loaded; CUR is the LDS buffer holding
+  // this chunk's A slab
+  auto chunk = [&](auto CURc, WStage& wc, WStage& wn, int kc) __attribute__((always_inline)) {
     constexpr int CUR = decltype(CURc)::value, NXT = CUR ^ 1;
     constexpr int PB = 16 / MTS;                       // pairs unpacked per row tile
     w_issue(wn, kc + 1);
@@ -204,14 +205,12 @@ __global__ __launch_bounds__(256) void large_kernel(GemmParams p, int tiles_m, i
     static_for<4>([&](auto Jc) __attribute__((always_inline)) {
       constexpr int J = decltype(Jc)::value;
       constexpr int JN = (J + 1) & 3;
-      if constexpr (J == 3) {
-        D::make_consts(gn0, wn.s0, wn.z0 & zmask, p.zbias, p.scale_bf16);
-        if constexpr (TWO_GROUPS) D::make_consts(gn1, wn.s1, wn.z1 & zmask, p.zbias, p.scale_bf16);
-      }
+      if constexpr (J == 3) D::make_consts(g0, wn.s0, wn.z0 & zmask, p.zbias, p.scale_bf16);
+      if constexpr (TWO_GROUPS && J == 1) D::make_consts(g1, wc.s1, wc.z1 & zmask, p.zbias, p.scale_bf16);
       uint32_t nf[4][4];                 // fragment of k-step J+1 under construction
       uint32_t xe[PB];
       typename D::Mid mid[PB], mid_prev[PB];
-      const typename D::Consts& g = (J < 3) ? ((TWO_GROUPS && JN >= 2) ? gc1 : gc0) : gn0;
+      const typename D::Consts& g = (TWO_GROUPS && JN >= 2) ? g1 : g0;
       const uint32_t (&rw)[RAW] = (J < 3) ? wc.r : wn.r;
       static_for<MTS>([&](auto MTc) __attribute__((always_inline)) {
         constexpr int MT = decltype(MTc)::value;
@@ -271,10 +270,10 @@ __global__ __launch_bounds__(256) void large_kernel(GemmParams p, int tiles_m, i
 
   int kc = 0;
   for (; kc + 2 <= KC; kc += 2) {
-    chunk(std::integral_constant<int, 0>{}, wA, wB, gA0, gA1, gB0, gB1, kc);
-    chunk(std::integral_constant<int, 1>{}, wB, wA, gB0, gB1, gA0, gA1, kc + 1);
+    chunk(std::integral_constant<int, 0>{}, wA, wB, kc);
+    chunk(std::integral_constant<int, 1>{}, wB, wA, kc + 1);
   }
-  if (kc < KC) chunk(std::integral_constant<int, 0>{}, wA, wB, gA0, gA1, gB0, gB1, kc);
+  if (kc < KC) chunk(std::integral_constant<int, 0>{}, wA, wB, kc);
 
   // the matrix pipeline may still be writing the accumulators (the compiler
   // does not see the asm MFMAs, so it inserts no wait states of its own)

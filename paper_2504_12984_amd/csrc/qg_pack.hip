@@ -41,13 +41,13 @@ __device__ __forceinline__ uint32_t fetch_code(const uint8_t* __restrict__ canon
 // lane will find them.
 __global__ __launch_bounds__(256) void repack_kernel(const uint8_t* __restrict__ canon, int64_t canon_bytes,
                                                      uint32_t* __restrict__ out, int bits, int K, int N,
-                                                     uint32_t flip, int natural) {
+                                                     uint32_t flip, int natural, int layout) {
   const int KC = K / TILE_K;
   const int64_t nchunks = (int64_t)KC * (N / TILE_N);
   int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   int64_t chunk = gid >> 6;
   if (chunk >= nchunks) return;
-  const int l = (int)(gid & 63), b = l >> 4, i16 = l & 15;
+  const int l = (int)(gid & 63);
   const int nc = (int)(chunk / KC), kc = (int)(chunk % KC);
   uint32_t* dst = out + chunk * (256 * bits);
   if (natural) {
@@ -57,9 +57,9 @@ __global__ __launch_bounds__(256) void repack_kernel(const uint8_t* __restrict__
       int c0 = (32 * d) / bits, c1 = (32 * d + 31) / bits;
       if (c1 > 2 * PAIRS - 1) c1 = 2 * PAIRS - 1;
       for (int c = c0; c <= c1; ++c) {
-        int t = c >> 1, j = t >> 4, nt = (t >> 2) & 3, v = t & 3;
-        int k = TILE_K * kc + 32 * j + 8 * b + 2 * v + (c & 1);
-        int n = TILE_N * nc + 4 * i16 + nt;
+        int t = c >> 1;
+        int k = TILE_K * kc + pair_k(layout, l, t) + (c & 1);
+        int n = TILE_N * nc + pair_n(layout, l, t);
         uint32_t code = fetch_code(canon, canon_bytes, (int64_t)k * N + n, bits);
         int sh = c * bits - 32 * d;
         word |= (sh >= 0) ? (code << sh) : (code >> (-sh));
@@ -73,9 +73,8 @@ __global__ __launch_bounds__(256) void repack_kernel(const uint8_t* __restrict__
     int t0 = (16 * d) / bits, t1 = (16 * d + 15) / bits;
     if (t1 > PAIRS - 1) t1 = PAIRS - 1;
     for (int t = t0; t <= t1; ++t) {
-      int j = t >> 4, nt = (t >> 2) & 3, v = t & 3;
-      int k = TILE_K * kc + 32 * j + 8 * b + 2 * v;
-      int n = TILE_N * nc + 4 * i16 + nt;
+      int k = TILE_K * kc + pair_k(layout, l, t);
+      int n = TILE_N * nc + pair_n(layout, l, t);
       uint32_t clo = fetch_code(canon, canon_bytes, (int64_t)k * N + n, bits) ^ flip;
       uint32_t chi = fetch_code(canon, canon_bytes, (int64_t)(k + 1) * N + n, bits) ^ flip;
       int sh = t * bits - 16 * d;
@@ -95,12 +94,12 @@ int launch_pack_codes(const uint8_t* codes, int bits, int64_t count, uint8_t* ou
   return hipGetLastError() == hipSuccess ? QG_OK : QG_EHIP;
 }
 
-int launch_repack(const uint8_t* canon, int bits, int K, int N, uint32_t flip, int natural, uint8_t* out, hipStream_t st) {
+int launch_repack(const uint8_t* canon, int bits, int K, int N, uint32_t flip, int natural, int layout, uint8_t* out, hipStream_t st) {
   int64_t nchunks = (int64_t)(K / TILE_K) * (N / TILE_N);
   int64_t canon_bytes = ((int64_t)K * N * bits + 7) / 8;
   int64_t blocks = (nchunks * 64 + 255) / 256;
   hipLaunchKernelGGL(repack_kernel, dim3((unsigned)blocks), dim3(256), 0, st, canon, canon_bytes,
-                     reinterpret_cast<uint32_t*>(out), bits, K, N, flip, natural);
+                     reinterpret_cast<uint32_t*>(out), bits, K, N, flip, natural, layout);
   return hipGetLastError() == hipSuccess ? QG_OK : QG_EHIP;
 }
 

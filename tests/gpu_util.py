@@ -36,6 +36,14 @@ class Prepared:
         self.d_zeros = None if self.inp["zeros"] is None else torch.from_numpy(self.inp["zeros"]).to(dev)
         self.d_A = self.inp["A"].to(dev)
         self.d_packed = B.repack(self.d_stream, self.wtype, c.K, c.N)
+        self._packed = {0: self.d_packed}
+
+    def packed(self, layout=0):
+        from paper_2504_12984_amd import binding as B
+        if layout not in self._packed:
+            c = self.case
+            self._packed[layout] = B.repack(self.d_stream, self.wtype, c.K, c.N, layout=layout)
+        return self._packed[layout]
 
     def oracle_w(self):
         c = self.case
@@ -48,16 +56,17 @@ class Prepared:
         return O.qgemm_from_stream(A, self.stream, c.kind, c.bits, c.ebits, c.mbits, self.scales64,
                                    self.inp["zeros"], c.group, c.K, c.N, c.act, cols=cols)
 
-    def gpu_w(self):
+    def gpu_w(self, layout=0):
         from paper_2504_12984_amd import binding as B
         c = self.case
-        return B.qdequant(self.d_packed, self.d_scales, self.d_zeros, self.wtype, ACT[c.act], c.group, c.K, c.N)
+        return B.qdequant(self.packed(layout), self.d_scales, self.d_zeros, self.wtype, ACT[c.act], c.group,
+                          c.K, c.N, layout=layout)
 
-    def gpu_c(self, A=None):
+    def gpu_c(self, A=None, layout=0):
         from paper_2504_12984_amd import binding as B
         c = self.case
-        return B.qgemm(self.d_A if A is None else A, self.d_packed, self.d_scales, self.d_zeros, self.wtype,
-                       c.group, c.N)
+        return B.qgemm(self.d_A if A is None else A, self.packed(layout), self.d_scales, self.d_zeros, self.wtype,
+                       c.group, c.N, layout=layout)
 
 
 def assert_c_close(C_gpu: torch.Tensor, C_ref: np.ndarray, what=""):

@@ -28,12 +28,14 @@ def test_pack_codes_equals_oracle_stream(bits):
 def _check_w(case, inputs=None):
     P = Prepared(case, inputs)
     _, want = P.oracle_w()
-    got = bits_of(P.gpu_w())
-    if not np.array_equal(got, want):
-        bad = np.argwhere(got != want)
-        k, n = bad[0]
-        raise AssertionError(f"{case.name}: {len(bad)} of {want.size} weights differ; first at k={k} n={n}: "
-                             f"gpu={got[k, n]:#06x} oracle={want[k, n]:#06x} code={P.inp['codes'][k, n]}")
+    for layout in (0, 1):                       # both device layouts decode to the same matrix
+        got = bits_of(P.gpu_w(layout))
+        if not np.array_equal(got, want):
+            bad = np.argwhere(got != want)
+            k, n = bad[0]
+            raise AssertionError(f"{case.name} layout {layout}: {len(bad)} of {want.size} weights differ; first at "
+                                 f"k={k} n={n}: gpu={got[k, n]:#06x} oracle={want[k, n]:#06x} "
+                                 f"code={P.inp['codes'][k, n]}")
 
 
 @pytest.mark.parametrize("act", ["f16", "bf16"])

@@ -133,6 +133,19 @@ def test_tiled_path_weight_types(kind, bits, e, m, act):
     assert_c_close(P.gpu_c(), P.oracle_c(), case.name)
 
 
+@pytest.mark.parametrize("bm", [128, 256])
+@pytest.mark.parametrize("bits", [1, 3, 4, 7, 8])
+def test_tiled_path_fp16_two_groups_per_chunk(bits, bm):
+    # group 64 puts two sets of scales / zero-points in every 128-row chunk
+    from paper_2504_12984_amd import binding as B
+    case = WL.Case(f"tiled_g64_{bits}_{bm}", 130, 640, 192, U, bits, group=64, act="f16", scale_dtype="f16",
+                   zero=1 << (bits - 1), seed=8850 + bits)
+    P = Prepared(case)
+    B.qg_set_knob(0, 2)
+    B.qg_set_knob(2, bm)
+    assert_c_close(P.gpu_c(), P.oracle_c(), case.name)
+
+
 def test_both_paths_agree_with_the_oracle_on_the_same_small_problem():
     from paper_2504_12984_amd import binding as B
     case = WL.Case("both_paths", 48, 768, 256, U, 6, group=128, act="bf16", scale_dtype="bf16", zero=32, seed=8900)
