@@ -159,5 +159,42 @@ def qgemm(A: torch.Tensor, packed: torch.Tensor, scales: torch.Tensor, zeros, t:
     return out
 
 
+class BoundQgemm:
+    """One qgemm call with its arguments checked and marshalled once.
+
+    For callers that issue the same matmul many times (a decode loop, the
+    benchmark): `__call__` is a single foreign call on pre-built C arguments, a
+    few microseconds cheaper than `qgemm`, which matters when the kernel itself
+    takes under ten.  The tensors are held by reference and must stay alive and
+    in place; the stream is the one current when the object was made unless one
+    is passed.
+    """
+
+    def __init__(self, A: torch.Tensor, packed: torch.Tensor, scales: torch.Tensor, zeros, t: WType, group: int,
+                 N: int, out: torch.Tensor, layout: int = QG_LAYOUT_TILE128x64, stream: int | None = None):
+        if A.dim() != 2 or A.dtype not in _DT:
+            raise ValueError("A must be [M,K] fp16 or bf16")
+        M, K = A.shape
+        if scales.dtype not in _DT or tuple(scales.shape) != (K // group, N):
+            raise ValueError("scales must be [K/group, N] fp16 or bf16")
+        if zeros is not None and (zeros.dtype != torch.uint8 or tuple(zeros.shape) != (K // group, N)):
+            raise ValueError("zeros must be uint8 [K/group, N]")
+        if tuple(out.shape) != (M, N) or out.dtype != A.dtype:
+            raise ValueError("out must be [M,N] of A's dtype")
+        vp, i32, i64 = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64
+        self._keep = (A, packed, scales, zeros, out)
+        self.out = out
+        self._args = (vp(_ptr(A, "A")), vp(_ptr(packed, "packed")), vp(_ptr(scales, "scales")),
+                      vp(_ptr(zeros, "zeros")), t.c(), i32(layout), i32(_DT[A.dtype]), i32(_DT[scales.dtype]),
+                      i64(group), i64(M), i64(N), i64(K), vp(_ptr(out, "C")),
+                      vp(_stream() if stream is None else stream))
+
+    def __call__(self) -> torch.Tensor:
+        rc = _lib.qgemm(*self._args)
+        if rc != QG_OK:
+            raise QgError("qgemm", rc)
+        return self.out
+
+
 def qg_set_knob(knob: int, value: int) -> int:
     return _lib.qg_set_knob(knob, value)

@@ -213,9 +213,9 @@ int qgemm(const void* A, const void* packed_W, const void* scales, const uint8_t
   if (path == 1) {
     const int KC = (int)(K / TILE_K), NCH = (int)(N / TILE_N);
     const int mt = M <= 16 ? 1 : (M <= 32 ? 2 : 4);
-    // 8 wavefronts per strip for one row tile and short K (few chunks per wavefront,
-    // more loads in flight at once), 4 wavefronts otherwise
-    int variant = 10 * mt + ((mt == 1 && KC <= 32) ? 0 : 1);
+    // 16 wavefronts per strip for one row tile and short K (two chunks per wavefront,
+    // every load of the strip in flight at once), 4 wavefronts otherwise
+    int variant = 10 * mt + ((mt == 1 && KC <= 32) ? 2 : 1);
     if (g_knob[3] > 0) variant = g_knob[3];
     const int waves = kDecodeWaves[wt](variant);
     // Split K over workgroups only when the column strips alone cannot fill the

@@ -103,13 +103,24 @@ __global__ __launch_bounds__(NW * 64) void decode_kernel(GemmParams p) {
       uint4 q = stream_load(src + i * 64);
       s.r[4 * i + 0] = q.x; s.r[4 * i + 1] = q.y; s.r[4 * i + 2] = q.z; s.r[4 * i + 3] = q.w;
     }
+#ifdef QG_DBG_NOSZ
+    s.s0 = make_uint2(0x3c003c00u, 0x3c003c00u); s.s1 = s.s0; s.z0 = 0x04040404u; s.z1 = s.z0;
+    __builtin_amdgcn_sched_barrier(0);
+    return;
+#endif
     const int g0 = (p.group == 64) ? 2 * c : ((c >> p.gshift) & p.gmask);
+#ifdef QG_SZ_BCAST
+    if (b == 0) {
+#endif
     s.s0 = *reinterpret_cast<const uint2*>(p.S + (int64_t)g0 * p.N + n0);
     if constexpr (TWO_GROUPS) {
       s.s1 = *reinterpret_cast<const uint2*>(p.S + (int64_t)(g0 + 1) * p.N + n0);
       s.z1 = *reinterpret_cast<const uint32_t*>(zbase + (int64_t)(g0 + 1) * p.N + n0);
     }
     s.z0 = *reinterpret_cast<const uint32_t*>(zbase + (int64_t)g0 * p.N + n0);
+#ifdef QG_SZ_BCAST
+    }
+#endif
     __builtin_amdgcn_sched_barrier(0);
   };
 
@@ -126,6 +137,17 @@ __global__ __launch_bounds__(NW * 64) void decode_kernel(GemmParams p) {
     constexpr int S = decltype(Sc)::value;
     Stage& s = st[S];
     typename D::Consts gc0, gc1;
+#ifdef QG_SZ_BCAST
+    {
+      const int ba = 4 * i16;
+      s.s0.x = __builtin_amdgcn_ds_bpermute(ba, s.s0.x); s.s0.y = __builtin_amdgcn_ds_bpermute(ba, s.s0.y);
+      s.z0 = __builtin_amdgcn_ds_bpermute(ba, s.z0);
+      if constexpr (TWO_GROUPS) {
+        s.s1.x = __builtin_amdgcn_ds_bpermute(ba, s.s1.x); s.s1.y = __builtin_amdgcn_ds_bpermute(ba, s.s1.y);
+        s.z1 = __builtin_amdgcn_ds_bpermute(ba, s.z1);
+      }
+    }
+#endif
     D::make_consts(gc0, s.s0, s.z0 & zmask, p.zbias, p.scale_bf16);
     if constexpr (TWO_GROUPS) D::make_consts(gc1, s.s1, s.z1 & zmask, p.zbias, p.scale_bf16);
     static_for<4>([&](auto Jc) __attribute__((always_inline)) {
@@ -133,10 +155,19 @@ __global__ __launch_bounds__(NW * 64) void decode_kernel(GemmParams p) {
       static_for<4>([&](auto NTc) __attribute__((always_inline)) {
         constexpr int NT = decltype(NTc)::value;
         uint32_t o[4];
+#ifdef QG_DBG_NODECODE
+        o[0] = s.r[(J * 4 + NT) % RAW]; o[1] = s.r[(J * 4 + NT + 1) % RAW]; o[2] = s.r[(J * 4 + NT + 2) % RAW]; o[3] = s.r[(J * 4 + NT + 3) % RAW] ^ s.s0.x ^ s.z0;
+#else
         D::template frag<J, NT>(s.r, (TWO_GROUPS && J >= 2) ? gc1 : gc0, u, o);
+#endif
         const u4_t wf = {o[0], o[1], o[2], o[3]};      // unpacked once, used by every row tile
+#ifdef QG_DBG_NOMFMA
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) acc[mt][NT][0] += __builtin_bit_cast(float, wf.x ^ wf.y ^ wf.z ^ wf.w ^ s.a[mt][J].x ^ s.a[mt][J].w);
+#else
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) acc[mt][NT] = mfma16<ROUTE>(wf, s.a[mt][J], acc[mt][NT]);
+#endif
       });
     });
   };
@@ -169,24 +200,40 @@ __global__ __launch_bounds__(NW * 64) void decode_kernel(GemmParams p) {
 
   // ---- reduce over the NW wavefronts through LDS, one 16-row tile at a time -----------------
   __shared__ float red[NW * 16 * 64];                      // [NW][16 column offsets][64 lanes]
-  __shared__ int s_last;
+  int* s_last = reinterpret_cast<int*>(red);               // reused once the sums are in registers
   constexpr int PER = 16 / NW;                             // column offsets per thread
   const int idx0 = PER * w;
   float sum[MT][PER];
+#ifdef QG_DBG_NOREDUCE
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+    for (int e = 0; e < PER; ++e) sum[mt][e] = acc[mt][e & 3][(e >> 2) & 3];
+  if (false)
+#endif
+  // lanes whose row is past M carry nothing: they stay out of the LDS traffic, of the
+  // split-K exchange and of the final store
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) {
+    const bool row_ok = mt * 16 + i16 < p.M;
     if (mt) __syncthreads();
+    if (row_ok) {
 #pragma unroll
-    for (int nt = 0; nt < 4; ++nt)
+      for (int nt = 0; nt < 4; ++nt)
 #pragma unroll
-      for (int r = 0; r < 4; ++r) red[(w * 16 + 4 * r + nt) * 64 + l] = acc[mt][nt][r];   // column offset 4r + nt
+        for (int r = 0; r < 4; ++r) red[(w * 16 + 4 * r + nt) * 64 + l] = acc[mt][nt][r];   // column offset 4r + nt
+    }
     __syncthreads();
 #pragma unroll
-    for (int e = 0; e < PER; ++e) {
-      float t = 0.f;
+    for (int e = 0; e < PER; ++e) sum[mt][e] = 0.f;
+    if (row_ok) {
 #pragma unroll
-      for (int ww = 0; ww < NW; ++ww) t += red[(ww * 16 + idx0 + e) * 64 + l];
-      sum[mt][e] = t;
+      for (int e = 0; e < PER; ++e) {
+        float t = 0.f;
+#pragma unroll
+        for (int ww = 0; ww < NW; ++ww) t += red[(ww * 16 + idx0 + e) * 64 + l];
+        sum[mt][e] = t;
+      }
     }
   }
 
@@ -201,15 +248,17 @@ __global__ __launch_bounds__(NW * 64) void decode_kernel(GemmParams p) {
     float* tile = p.ws + ((int64_t)split * NCH + nc) * (MT * 1024);
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
+      if (mt * 16 + i16 < p.M) {
 #pragma unroll
-      for (int e = 0; e < PER; ++e)
-        __hip_atomic_store(tile + mt * 1024 + (idx0 + e) * 64 + l, sum[mt][e], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        for (int e = 0; e < PER; ++e)
+          __hip_atomic_store(tile + mt * 1024 + (idx0 + e) * 64 + l, sum[mt][e], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // a workgroup barrier alone does not wait for global stores
     __syncthreads();
     if (tid == 0)
-      s_last = (__hip_atomic_fetch_add(&p.tickets[nc], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (unsigned)(p.splitk - 1));
+      *s_last = (__hip_atomic_fetch_add(&p.tickets[nc], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (unsigned)(p.splitk - 1));
     __syncthreads();
-    if (!s_last) return;
+    if (!*s_last) return;
     // all loads of a split are issued before the first add (independent accumulators)
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
@@ -221,8 +270,11 @@ __global__ __launch_bounds__(NW * 64) void decode_kernel(GemmParams p) {
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-        for (int e = 0; e < PER; ++e)
-          v[mt][e] = __hip_atomic_load(src + mt * 1024 + (idx0 + e) * 64 + l, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        for (int e = 0; e < PER; ++e) {
+          v[mt][e] = 0.f;
+          if (mt * 16 + i16 < p.M)
+            v[mt][e] = __hip_atomic_load(src + mt * 1024 + (idx0 + e) * 64 + l, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
@@ -235,8 +287,12 @@ __global__ __launch_bounds__(NW * 64) void decode_kernel(GemmParams p) {
     const int m = mt * 16 + i16;
     if (m < p.M) {
       uint16_t* dst = p.C + (int64_t)m * p.N + TILE_N * nc + 16 * b + idx0;
+      if constexpr (PER == 1) {
+        dst[0] = (uint16_t)(pack_out<ROUTE>(sum[mt][0], 0.f) & 0xffffu);
+      } else {
 #pragma unroll
-      for (int e = 0; e < PER; e += 2) *reinterpret_cast<uint32_t*>(dst + e) = pack_out<ROUTE>(sum[mt][e], sum[mt][e + 1]);
+        for (int e = 0; e + 1 < PER; e += 2) *reinterpret_cast<uint32_t*>(dst + e) = pack_out<ROUTE>(sum[mt][e], sum[mt][e + 1]);
+      }
     }
   }
 }
@@ -252,12 +308,13 @@ static int launch_cfg(const GemmParams& p, hipStream_t st) {
   return hipGetLastError() == hipSuccess ? QG_OK : QG_EHIP;
 }
 
-// variant = 10 * (row tiles: 1, 2, 4) + (0: 8 wavefronts per strip, 1: 4 wavefronts)
+// variant = 10 * (row tiles: 1, 2, 4) + (0: 8 wavefronts per strip, 1: 4 wavefronts, 2: 16 wavefronts)
 template <int ROUTE, bool TG>
 static int launch_variant(const GemmParams& p, int variant, hipStream_t st) {
   switch (variant) {
     case 10: return launch_cfg<ROUTE, TG, 8, 2, 1>(p, st);
     case 11: return launch_cfg<ROUTE, TG, 4, 2, 1>(p, st);
+    case 12: return launch_cfg<ROUTE, TG, 16, 2, 1>(p, st);
     case 21: return launch_cfg<ROUTE, TG, 4, 2, 2>(p, st);
     case 41: return launch_cfg<ROUTE, TG, 4, 2, 4>(p, st);
     default: return QG_EINVAL;
@@ -265,7 +322,7 @@ static int launch_variant(const GemmParams& p, int variant, hipStream_t st) {
 }
 
 // number of wavefronts per workgroup of a variant (the host sizes split-K with it)
-int QG_CAT(decode_waves_wt, QG_WT)(int variant) { return (variant % 10 == 0) ? 8 : 4; }
+int QG_CAT(decode_waves_wt, QG_WT)(int variant) { return (variant % 10 == 0) ? 8 : (variant % 10 == 2) ? 16 : 4; }
 
 int QG_CAT(decode_launch_wt, QG_WT)(const GemmParams& p, int route, int variant, hipStream_t st) {
   const bool tg = (p.group == 64);
