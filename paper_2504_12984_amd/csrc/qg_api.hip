@@ -216,6 +216,10 @@ int qgemm(const void* A, const void* packed_W, const void* scales, const uint8_t
     // 16 wavefronts per strip for one row tile and short K (two chunks per wavefront,
     // every load of the strip in flight at once), 4 wavefronts otherwise
     int variant = 10 * mt + ((mt == 1 && KC <= 32) ? 2 : 1);
+    // long K and enough strips to fill the chip with pairs of them: 8 wavefronts on 2
+    // adjacent strips, 4 along K each -- wavefronts at the same K position share
+    // their A rows in the vector cache (measured 5-13 % shorter at K = 8192, N = 28672)
+    if (mt == 1 && KC > 32 && NCH % 2 == 0 && NCH / 2 >= 192) variant = 14;
     if (g_knob[3] > 0) variant = g_knob[3];
     const int waves = kDecodeWaves[wt](variant);
     // Split K over workgroups only when the column strips alone cannot fill the

@@ -56,19 +56,26 @@ __device__ __forceinline__ uint32_t pack_out(float lo, float hi) {
   else return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, b2_t));
 }
 
-template <int WT, int ROUTE, bool TWO_GROUPS, int NW, int DEPTH, int MT>
+template <int WT, int ROUTE, bool TWO_GROUPS, int NW, int DEPTH, int MT, int NS = 1>
 __global__ __launch_bounds__(NW * 64) void decode_kernel(GemmParams p) {
+  // NS adjacent strips per workgroup, NK wavefronts along K for each: wavefront w
+  // works on strip w % NS and takes every NK-th chunk of the slab starting at
+  // w / NS, so the NS wavefronts with the same w / NS walk the same K range at the
+  // same pace and find each other's A rows in the vector cache.
+  constexpr int NK = NW / NS;
+  static_assert(NW % NS == 0 && 16 % NK == 0, "wavefront grid");
   typedef Decoder<WT, ROUTE> D;
   constexpr int BITS = D::BITS, RAW = D::RAW;
 
   const int tid = threadIdx.x, l = tid & 63;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, kept in a scalar register
   const int b = l >> 4, i16 = l & 15;
-  const int nc = blockIdx.x, split = blockIdx.y;
+  const int ws = w % NS, wk = w / NS;                       // my strip and K position inside the workgroup
+  const int nc = blockIdx.x * NS + ws, split = blockIdx.y;
   const int KC = p.K / TILE_K, NCH = p.N / TILE_N;
   const int c0 = split * p.chunks_per_split;
   const int c1 = min(KC, c0 + p.chunks_per_split);
-  const int mine = (c1 - c0 > w) ? (c1 - c0 - w + NW - 1) / NW : 0;
+  const int mine = (c1 - c0 > wk) ? (c1 - c0 - wk + NK - 1) / NK : 0;
   const int n0 = TILE_N * nc + 4 * i16;
 
   const uint4* wstrip = reinterpret_cast<const uint4*>(p.W + (int64_t)nc * KC * (1024 * BITS)) + l;
@@ -172,7 +179,7 @@ __global__ __launch_bounds__(NW * 64) void decode_kernel(GemmParams p) {
     });
   };
 
-  auto chunk_of = [&](int i) __attribute__((always_inline)) { return c0 + w + min(i, mine - 1) * NW; };
+  auto chunk_of = [&](int i) __attribute__((always_inline)) { return c0 + wk + min(i, mine - 1) * NK; };
 
   if (mine > 0) {
     // prologue: DEPTH chunks in flight (past-the-end stages re-load my last chunk)
@@ -201,8 +208,8 @@ __global__ __launch_bounds__(NW * 64) void decode_kernel(GemmParams p) {
   // ---- reduce over the NW wavefronts through LDS, one 16-row tile at a time -----------------
   __shared__ float red[NW * 16 * 64];                      // [NW][16 column offsets][64 lanes]
   int* s_last = reinterpret_cast<int*>(red);               // reused once the sums are in registers
-  constexpr int PER = 16 / NW;                             // column offsets per thread
-  const int idx0 = PER * w;
+  constexpr int PER = 16 / NK;                             // column offsets per thread
+  const int idx0 = PER * wk;
   float sum[MT][PER];
 #ifdef QG_DBG_NOREDUCE
 #pragma unroll
@@ -231,7 +238,7 @@ __global__ __launch_bounds__(NW * 64) void decode_kernel(GemmParams p) {
       for (int e = 0; e < PER; ++e) {
         float t = 0.f;
 #pragma unroll
-        for (int ww = 0; ww < NW; ++ww) t += red[(ww * 16 + idx0 + e) * 64 + l];
+        for (int kk = 0; kk < NK; ++kk) t += red[((kk * NS + ws) * 16 + idx0 + e) * 64 + l];
         sum[mt][e] = t;
       }
     }
@@ -256,7 +263,7 @@ __global__ __launch_bounds__(NW * 64) void decode_kernel(GemmParams p) {
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // a workgroup barrier alone does not wait for global stores
     __syncthreads();
     if (tid == 0)
-      *s_last = (__hip_atomic_fetch_add(&p.tickets[nc], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (unsigned)(p.splitk - 1));
+      *s_last = (__hip_atomic_fetch_add(&p.tickets[blockIdx.x], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (unsigned)(p.splitk - 1));
     __syncthreads();
     if (!*s_last) return;
     // all loads of a split are issued before the first add (independent accumulators)
@@ -280,7 +287,7 @@ __global__ __launch_bounds__(NW * 64) void decode_kernel(GemmParams p) {
 #pragma unroll
         for (int e = 0; e < PER; ++e) sum[mt][e] += v[mt][e];
     }
-    if (tid == 0) __hip_atomic_store(&p.tickets[nc], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next call
+    if (tid == 0) __hip_atomic_store(&p.tickets[blockIdx.x], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next call
   }
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) {
@@ -300,10 +307,11 @@ __global__ __launch_bounds__(NW * 64) void decode_kernel(GemmParams p) {
 #define QG_CAT2(a, b) a##b
 #define QG_CAT(a, b) QG_CAT2(a, b)
 
-template <int ROUTE, bool TG, int NW, int DEPTH, int MT>
+template <int ROUTE, bool TG, int NW, int DEPTH, int MT, int NS = 1>
 static int launch_cfg(const GemmParams& p, hipStream_t st) {
-  auto kern = decode_kernel<QG_WT, ROUTE, TG, NW, DEPTH, MT>;
-  dim3 grid((unsigned)(p.N / TILE_N), (unsigned)p.splitk), block(NW * 64);
+  if ((p.N / TILE_N) % NS) return QG_EINVAL;
+  auto kern = decode_kernel<QG_WT, ROUTE, TG, NW, DEPTH, MT, NS>;
+  dim3 grid((unsigned)(p.N / TILE_N / NS), (unsigned)p.splitk), block(NW * 64);
   hipLaunchKernelGGL(kern, grid, block, 0, st, p);
   return hipGetLastError() == hipSuccess ? QG_OK : QG_EHIP;
 }
@@ -315,14 +323,27 @@ static int launch_variant(const GemmParams& p, int variant, hipStream_t st) {
     case 10: return launch_cfg<ROUTE, TG, 8, 2, 1>(p, st);
     case 11: return launch_cfg<ROUTE, TG, 4, 2, 1>(p, st);
     case 12: return launch_cfg<ROUTE, TG, 16, 2, 1>(p, st);
+    case 13: return launch_cfg<ROUTE, TG, 16, 2, 1, 4>(p, st);    // 4 strips x 4 wavefronts along K
+    case 14: return launch_cfg<ROUTE, TG, 8, 2, 1, 2>(p, st);     // 2 strips x 4
+    case 15: return launch_cfg<ROUTE, TG, 16, 2, 1, 2>(p, st);    // 2 strips x 8
+    case 16: return launch_cfg<ROUTE, TG, 8, 2, 1, 4>(p, st);     // 4 strips x 2
     case 21: return launch_cfg<ROUTE, TG, 4, 2, 2>(p, st);
     case 41: return launch_cfg<ROUTE, TG, 4, 2, 4>(p, st);
     default: return QG_EINVAL;
   }
 }
 
-// number of wavefronts per workgroup of a variant (the host sizes split-K with it)
-int QG_CAT(decode_waves_wt, QG_WT)(int variant) { return (variant % 10 == 0) ? 8 : (variant % 10 == 2) ? 16 : 4; }
+// number of wavefronts along K per strip of a variant (the host sizes split-K with it)
+int QG_CAT(decode_waves_wt, QG_WT)(int variant) {
+  switch (variant) {
+    case 10: return 8;
+    case 12: return 16;
+    case 13: case 14: return 4;
+    case 15: return 8;
+    case 16: return 2;
+    default: return 4;
+  }
+}
 
 int QG_CAT(decode_launch_wt, QG_WT)(const GemmParams& p, int route, int variant, hipStream_t st) {
   const bool tg = (p.group == 64);

@@ -71,6 +71,19 @@ def test_split_k_factors_agree_with_oracle_and_leave_counters_clean(splitk):
     assert np.array_equal(bits_of(first), bits_of(second))
 
 
+@pytest.mark.parametrize("splitk", [1, 3])
+@pytest.mark.parametrize("variant", [10, 11, 12, 13, 14, 15, 16])
+@pytest.mark.parametrize("M", [1, 16])
+def test_every_wavefront_arrangement_of_the_streaming_kernel(M, variant, splitk):
+    # 8, 4 or 16 wavefronts on one strip, or 2 / 4 strips per workgroup
+    from paper_2504_12984_amd import binding as B
+    case = WL.Case(f"arr_{M}_{variant}_{splitk}", M, 1408, 512, I, 3, group=128, zero=None, seed=8350 + M)
+    P = Prepared(case)
+    B.qg_set_knob(3, variant)
+    B.qg_set_knob(1, splitk)
+    assert_c_close(P.gpu_c(), P.oracle_c(), case.name)
+
+
 def test_one_hot_rows_return_weight_rows_bit_exactly():
     # ties the matmul to the bit-exact de-quantisation: fp32 accumulation of a
     # single non-zero product and one rounding reproduce the weight itself
