@@ -218,8 +218,9 @@ int qgemm(const void* A, const void* packed_W, const void* scales, const uint8_t
     int variant = 10 * mt + ((mt == 1 && KC <= 32) ? 2 : 1);
     // long K and enough strips to fill the chip with pairs of them: 8 wavefronts on 2
     // adjacent strips, 4 along K each -- wavefronts at the same K position share
-    // their A rows in the vector cache (measured 5-13 % shorter at K = 8192, N = 28672)
-    if (mt == 1 && KC > 32 && NCH % 2 == 0 && NCH / 2 >= 192) variant = 14;
+    // their A rows in the vector cache (measured 5-13 % shorter at K = 8192, N = 28672;
+    // with 2 or 4 row tiles: 2 strips x 2 wavefronts along K)
+    if (KC > 32 && NCH % 2 == 0 && NCH / 2 >= 192) variant = (mt == 1) ? 14 : (mt == 2) ? 26 : 46;
     if (g_knob[3] > 0) variant = g_knob[3];
     const int waves = kDecodeWaves[wt](variant);
     // Split K over workgroups only when the column strips alone cannot fill the

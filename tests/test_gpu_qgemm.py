@@ -84,6 +84,18 @@ def test_every_wavefront_arrangement_of_the_streaming_kernel(M, variant, splitk)
     assert_c_close(P.gpu_c(), P.oracle_c(), case.name)
 
 
+@pytest.mark.parametrize("M,variant", [(17, 21), (32, 24), (30, 26), (33, 41), (64, 46), (50, 46)])
+def test_two_strip_arrangements_with_several_row_tiles(M, variant):
+    from paper_2504_12984_amd import binding as B
+    case = WL.Case(f"arr2_{M}_{variant}", M, 1152, 256, U, 6, group=128, act="bf16", scale_dtype="bf16",
+                   zero=31, seed=8360 + M)
+    P = Prepared(case)
+    B.qg_set_knob(3, variant)
+    for splitk in (1, 2):
+        B.qg_set_knob(1, splitk)
+        assert_c_close(P.gpu_c(), P.oracle_c(), f"{case.name} splitk={splitk}")
+
+
 def test_one_hot_rows_return_weight_rows_bit_exactly():
     # ties the matmul to the bit-exact de-quantisation: fp32 accumulation of a
     # single non-zero product and one rounding reproduce the weight itself
