@@ -11,8 +11,8 @@ more copies than the last-level cache holds has the same effect without a
 second kernel inside the timed region).  Inputs are seeded and synthetic and
 already in HBM when the timed region starts.  Prints one JSON line.
 
-Other workloads (for the tables in the design doc): cfg1, cfg3_i<k>, cfg4_f<bits>_M<m>,
-cfg5_u<k>_M<m>.
+Other workloads (for the tables in the design doc): cfg1, cfg2_M<m>, cfg3_i<k>[_M<m>],
+cfg4_f<bits>_M<m>, cfg5_u<k>_M<m> [--layout 1], sweep_{u,i,f}<bits>.
 """
 from __future__ import annotations
 
@@ -65,6 +65,9 @@ def cases_for(name):
     if name.startswith("cfg5_u"):
         bits, m = name[6:].split("_M")
         return [WL.cfg5(int(bits), int(m))]
+    if name.startswith("sweep_"):                        # sweep_u4, sweep_i7, sweep_f6 (M = 16)
+        kind = {"u": WL.KIND_UINT, "i": WL.KIND_INT, "f": WL.KIND_FLOAT}[name[6]]
+        return [WL.sweep(kind, int(name[7:]))]
     raise SystemExit(f"unknown workload {name}")
 
 
@@ -164,7 +167,40 @@ def main():
     launches = len(cases)
     launch_ms = ms_per_step / launches
 
+    def gpu_time_ms(fn, reps):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(reps):
+            fn(i)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
     small = all(c.M <= 64 for c in cases)
+    sink = torch.zeros(4096, dtype=torch.float32, device=dev)
+    # Empirical ceilings on this machine, same protocol (back-to-back launches, events):
+    # a kernel that only reads the same packed weights, and a register-resident matrix loop.
+    if small:
+        probes = [B.qg_probe_stream_read(packed[i], sink) for i in range(copies)]
+        for i in range(min(copies, 5)):
+            probes[i]()
+        torch.cuda.synchronize()
+        t_probe = gpu_time_ms(lambda i: probes[i % copies](), 200)
+        empirical = {"what": "kernel that only reads the packed weight of one launch, rotating the same copies",
+                     "us": round(t_probe * 1e3, 3), "gbps": round(P / (t_probe * 1e-3) / 1e9, 1)}
+    else:
+        is_bf16 = c0.act == "bf16"
+        empirical = {"what": "register-resident 32x32x16 matrix-instruction loop, 1 wavefront per SIMD"}
+        for label, rnd in (("constant_operands", False), ("random_operands", True)):
+            B.qg_probe_mfma(is_bf16, rnd, 2000, 1, sink)
+            torch.cuda.synchronize()
+            fl = [0.0]
+
+            def run(i, rnd=rnd):
+                fl[0] = B.qg_probe_mfma(is_bf16, rnd, 20000, 1, sink)
+            t_probe = gpu_time_ms(run, 5)
+            empirical[label + "_tflops"] = round(fl[0] / (t_probe * 1e-3) / 1e12, 1)
+
     flops_step = sum(2.0 * c.M * c.N * c.K for c in cases)
     alg_bytes = sum(algorithmic_bytes(c)[1] for c in cases) / launches
     gbs_packed = launches * P / (ms_per_step * 1e-3) / 1e9
@@ -175,14 +211,17 @@ def main():
         roof = {"bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload),
                 "kernel": "qg::decode_kernel", "avg_launch_us": round(launch_ms * 1e3, 3),
-                "algorithmic_bytes_per_launch": int(alg_bytes)}
+                "algorithmic_bytes_per_launch": int(alg_bytes),
+                "empirical_ceiling": empirical, "frac_of_empirical": round(gbs_packed / empirical["gbps"], 4)}
     else:
         metric, unit, value = "effective_tflops", "TFLOP/s", tflops
         roof = {"bound": "mfma", "achieved": round(tflops, 1), "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
                 "frac": round(tflops / MFMA_PEAK_TFLOPS, 4), "traffic": None,
                 "kernel": "qg::large32_kernel" if layout == 1 else "qg::large_kernel",
                 "avg_launch_us": round(launch_ms * 1e3, 3),
-                "algorithmic_flops_per_launch": flops_step / launches}
+                "algorithmic_flops_per_launch": flops_step / launches,
+                "empirical_ceiling": empirical,
+                "frac_of_empirical": round(tflops / empirical["random_operands_tflops"], 4)}
 
     out = {
         "metric": metric, "value": round(value, 2), "unit": unit, "n_gpus": 1,

@@ -133,6 +133,21 @@ QG_API int qgemm(const void* A, const void* packed_W, const void* scales, const 
  * 21, 41; 13..16, 24, 26, 46: 16, 8 or 4 wavefronts on 4 or 2 adjacent strips).  Knobs 0, 1 and 3 apply to QG_LAYOUT_TILE128x64 only. */
 QG_API int qg_set_knob(int knob, int value);
 
+/* Measurement aids -- not part of the method (no passage of the paper defines
+ * them): the two empirical ceilings bench.py quotes beside the published peaks.
+ * Both enqueue one kernel on `stream` and return; the caller times them.
+ * qg_probe_stream_read: reads `bytes` (>= 16; whole 16-byte units are read) from
+ *   device buffer `buf` (16-byte aligned) once with 16-byte loads and discards
+ *   them.  `sink`: >= 1 KiB of device memory, practically never written.
+ * qg_probe_mfma: 256 * waves_per_simd workgroups of 4 wavefronts each run `iters`
+ *   x 8 register-resident 32x32x16 matrix instructions (bf16 != 0: bf16 operands,
+ *   else fp16) on constant (all ones) or pseudo-random operand data;
+ *   *flops_out (host, may be NULL) receives the flop count of the launch.
+ * QG_EINVAL on null / misaligned pointers or counts out of range. */
+QG_API int qg_probe_stream_read(const void* buf, size_t bytes, void* sink, void* stream);
+QG_API int qg_probe_mfma(int bf16, int random_data, int iters, int waves_per_simd, void* sink,
+                         double* flops_out, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -24,7 +24,8 @@ QG_LAYOUT_TILE128x64_R32 = 1
 TILE_K, TILE_N = 128, 64
 
 EXPORTS = ("qg_status_string", "qg_last_error", "qg_canonical_bytes", "qgemm_packed_bytes",
-           "qg_pack_codes", "repack", "qdequant", "qgemm", "qg_set_knob")
+           "qg_pack_codes", "repack", "qdequant", "qgemm", "qg_set_knob", "qg_probe_stream_read",
+           "qg_probe_mfma")
 
 
 class QgWType(ctypes.Structure):
@@ -77,6 +78,10 @@ def _load() -> ctypes.CDLL:
     lib.qgemm.argtypes = [vp, vp, vp, vp, QgWType, i32, i32, i32, i64, i64, i64, i64, vp, vp]
     lib.qg_set_knob.restype = i32
     lib.qg_set_knob.argtypes = [i32, i32]
+    lib.qg_probe_stream_read.restype = i32
+    lib.qg_probe_stream_read.argtypes = [vp, sz, vp, vp]
+    lib.qg_probe_mfma.restype = i32
+    lib.qg_probe_mfma.argtypes = [i32, i32, i32, i32, vp, ctypes.POINTER(ctypes.c_double), vp]
     return lib
 
 
@@ -194,6 +199,29 @@ class BoundQgemm:
         if rc != QG_OK:
             raise QgError("qgemm", rc)
         return self.out
+
+
+def qg_probe_stream_read(buf: torch.Tensor, sink: torch.Tensor):
+    """The read-only streaming probe over all of `buf` (measurement aid).  Returns a
+    callable that enqueues it on the stream current now; like BoundQgemm, the
+    arguments are marshalled once so that the call costs the host as little as a
+    bound matmul call."""
+    vp = ctypes.c_void_p
+    args = (vp(_ptr(buf, "buf")), ctypes.c_size_t(buf.numel() * buf.element_size()), vp(_ptr(sink, "sink")),
+            vp(_stream()))
+
+    def call():
+        _check("qg_probe_stream_read", _lib.qg_probe_stream_read(*args))
+    call.keep = (buf, sink)
+    return call
+
+
+def qg_probe_mfma(bf16: bool, random_data: bool, iters: int, waves_per_simd: int, sink: torch.Tensor) -> float:
+    """Enqueue the register-resident matrix-instruction probe; returns its flop count."""
+    flops = ctypes.c_double(0.0)
+    _check("qg_probe_mfma", _lib.qg_probe_mfma(int(bf16), int(random_data), iters, waves_per_simd,
+                                               _ptr(sink, "sink"), ctypes.byref(flops), _stream()))
+    return flops.value
 
 
 def qg_set_knob(knob: int, value: int) -> int:

@@ -26,7 +26,7 @@ FLAGS = ["--offload-arch=gfx950", "-std=c++20", "-O3", "-fPIC", "-fvisibility=hi
 
 
 def _jobs():
-    jobs = [("qg_pack.hip", None), ("qg_api.hip", None)]
+    jobs = [("qg_pack.hip", None), ("qg_probe.hip", None), ("qg_api.hip", None)]
     for src in ("qg_dequant.hip", "qg_decode_gemm.hip", "qg_large.hip", "qg_large32.hip"):
         jobs += [(src, wt) for wt in range(NUM_WT)]
     return jobs

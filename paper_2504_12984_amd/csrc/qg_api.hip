@@ -8,6 +8,8 @@
 namespace qg {
 
 int launch_pack_codes(const uint8_t*, int, int64_t, uint8_t*, hipStream_t);
+int launch_probe_stream(const void*, size_t, void*, hipStream_t);
+int launch_probe_mfma(int, int, int, int, void*, hipStream_t);
 int launch_repack(const uint8_t*, int, int, int, uint32_t, int, int, uint8_t*, hipStream_t);
 
 #define QG_FOR_ALL_WT(X) X(0) X(1) X(2) X(3) X(4) X(5) X(6) X(7) X(8) X(9) X(10) X(11) X(12) X(13)
@@ -244,6 +246,18 @@ int qgemm(const void* A, const void* packed_W, const void* scales, const uint8_t
     return kDecode[wt](p, route, variant, st);
   }
   return kLarge[wt](p, route, g_knob[2], st);
+}
+
+int qg_probe_stream_read(const void* buf, size_t bytes, void* sink, void* stream) {
+  if (!buf || !sink || bytes < 16 || !aligned16(buf)) return QG_EINVAL;
+  return launch_probe_stream(buf, bytes, sink, static_cast<hipStream_t>(stream));
+}
+
+int qg_probe_mfma(int bf16, int random_data, int iters, int waves_per_simd, void* sink, double* flops_out, void* stream) {
+  if (!sink || iters < 1 || waves_per_simd < 1 || waves_per_simd > 8) return QG_EINVAL;
+  // 8 instructions of 32*32*16*2 flop per iteration and wavefront, 4 wavefronts per block
+  if (flops_out) *flops_out = 8.0 * 32768.0 * (double)iters * 4.0 * 256.0 * waves_per_simd;
+  return launch_probe_mfma(bf16 != 0, random_data != 0, iters, waves_per_simd, sink, static_cast<hipStream_t>(stream));
 }
 
 int qg_set_knob(int knob, int value) {

@@ -100,10 +100,12 @@ __global__ __launch_bounds__(NW * 64) void decode_kernel(GemmParams p) {
     Stage& s = st[S];
     __builtin_amdgcn_sched_barrier(0);         // stay below the last use of the entry being refilled,
                                                // so that the refill reuses the same registers
+#ifndef QG_W_FIRST
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
       for (int j = 0; j < 4; ++j) s.a[mt][j] = *reinterpret_cast<const u4_t*>(arow[mt] + c * TILE_K + 32 * j);
+#endif
     const uint4* src = wstrip + (int64_t)c * (64 * BITS);
 #pragma unroll
     for (int i = 0; i < BITS; ++i) {
@@ -127,6 +129,12 @@ __global__ __launch_bounds__(NW * 64) void decode_kernel(GemmParams p) {
     s.z0 = *reinterpret_cast<const uint32_t*>(zbase + (int64_t)g0 * p.N + n0);
 #ifdef QG_SZ_BCAST
     }
+#endif
+#ifdef QG_W_FIRST
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) s.a[mt][j] = *reinterpret_cast<const u4_t*>(arow[mt] + c * TILE_K + 32 * j);
 #endif
     __builtin_amdgcn_sched_barrier(0);
   };

@@ -1,0 +1,79 @@
+// Measurement aids, not part of the method: the two empirical ceilings the matmul
+// kernels are compared against on the machine they run on.
+//   stream probe  reads a buffer once with 16-byte loads and does nothing else --
+//                 the time any kernel needs just to pull those bytes out of HBM
+//   mfma probe    a register-resident loop of 32x32x16 matrix instructions on
+//                 constant or pseudo-random operands -- the matrix rate the chip
+//                 sustains at the clock it holds under that load (the clock, and
+//                 with it the rate, depends on how much the operand bits toggle)
+#include "qg_common.h"
+
+namespace qg {
+
+typedef uint32_t u4_t __attribute__((ext_vector_type(4)));
+typedef float f16_t __attribute__((ext_vector_type(16)));
+
+__global__ __launch_bounds__(256) void probe_stream_kernel(const uint4* __restrict__ src, size_t n16, uint32_t* sink) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  uint32_t acc = 0;
+  for (; i + 3 * stride < n16; i += 4 * stride) {
+    uint4 a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
+    acc ^= a.x + b.y + c.z + d.w;
+  }
+  for (; i < n16; i += stride) acc ^= src[i].x;
+  if (acc == 0x9e3779b9u) sink[threadIdx.x] = acc;     // keeps the loads alive; practically never taken
+}
+
+__device__ __forceinline__ uint32_t probe_rand_pair(uint32_t& s, int bf16) {
+  s = s * 1664525u + 1013904223u;
+  // two values in (-2, 2) with random signs and mantissas
+  const uint32_t base = bf16 ? 0x3f00u : 0x3800u, mask = bf16 ? 0x80ffu : 0x87ffu;
+  return (base | ((s >> 3) & mask)) | ((base | ((s >> 17) & mask)) << 16);
+}
+
+template <int BF16>
+__global__ __launch_bounds__(256) void probe_mfma_kernel(int iters, int random_data, float* sink) {
+  f16_t acc[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+#pragma unroll
+    for (int j = 0; j < 16; ++j) acc[i][j] = 0.f;
+  uint32_t s = threadIdx.x * 2654435761u + blockIdx.x * 97u + 12345u;
+  const uint32_t one = BF16 ? 0x3f803f80u : 0x3c003c00u;
+  u4_t a[4], b[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      a[i][j] = random_data ? probe_rand_pair(s, BF16) : one;
+      b[i][j] = random_data ? probe_rand_pair(s, BF16) : one;
+    }
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      if constexpr (BF16) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc[i]) : "v"(a[i & 3]), "v"(b[(i >> 1) & 3]));
+      else                asm volatile("v_mfma_f32_32x32x16_f16 %0, %1, %2, %0" : "+a"(acc[i]) : "v"(a[i & 3]), "v"(b[(i >> 1) & 3]));
+    }
+  }
+  asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15" ::: "memory");
+  float t = 0.f;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) t += acc[i][0];
+  if (t == 123.456f) sink[threadIdx.x] = t;
+}
+
+int launch_probe_stream(const void* buf, size_t bytes, void* sink, hipStream_t st) {
+  hipLaunchKernelGGL(probe_stream_kernel, dim3(2048), dim3(256), 0, st, static_cast<const uint4*>(buf), bytes / 16,
+                     static_cast<uint32_t*>(sink));
+  return hipGetLastError() == hipSuccess ? QG_OK : QG_EHIP;
+}
+
+int launch_probe_mfma(int bf16, int random_data, int iters, int waves_per_simd, void* sink, hipStream_t st) {
+  dim3 grid(256 * waves_per_simd), block(256);
+  if (bf16) hipLaunchKernelGGL(probe_mfma_kernel<1>, grid, block, 0, st, iters, random_data, static_cast<float*>(sink));
+  else      hipLaunchKernelGGL(probe_mfma_kernel<0>, grid, block, 0, st, iters, random_data, static_cast<float*>(sink));
+  return hipGetLastError() == hipSuccess ? QG_OK : QG_EHIP;
+}
+
+}  // namespace qg

@@ -113,6 +113,25 @@ def cfg5(bits: int, M: int) -> Case:
                 seed=500 + 10 * bits + (1024, 4096).index(M))
 
 
+_SWEEP_FLOATS = {3: (1, 1), 4: (2, 1), 5: (2, 2), 6: (3, 2), 7: (3, 3), 8: (4, 3)}
+
+
+def sweep(kind: int, bits: int, M: int = 16) -> Case:
+    """The paper's full weight-type sweep (Figure "speedup over cuBLAS for every type"):
+    M = 16, K = 8192, N = 57344, one scale per column group of 128; uint1..8 with a
+    mid-range zero-point, int2..8, and the representative float of 3..8 bits."""
+    if kind == KIND_FLOAT:
+        e, m = _SWEEP_FLOATS[bits]
+        return Case(f"sweep_f{bits}e{e}m{m}_M{M}", M, 8192, 57344, KIND_FLOAT, bits, e, m, group=128,
+                    zero=None, scale_lo=0.01, scale_hi=0.1, seed=600 + bits)
+    assert 1 <= bits <= 8
+    if kind == KIND_UINT:
+        return Case(f"sweep_u{bits}_M{M}", M, 8192, 57344, KIND_UINT, bits, group=128, zero=1 << (bits - 1),
+                    seed=620 + bits)
+    return Case(f"sweep_i{bits}_M{M}", M, 8192, 57344, KIND_INT, bits, group=128, zero=None,
+                scale_lo=0.002, scale_hi=0.02, seed=640 + bits)
+
+
 def shrink(case: Case, **kw) -> Case:
     """Same recipe at another size (used by the element-by-element parity tests)."""
     return replace(case, **kw)

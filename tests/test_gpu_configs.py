@@ -23,9 +23,10 @@ NSAMPLE = 96
 
 
 class FullCase:
-    def __init__(self, case: WL.Case):
+    def __init__(self, case: WL.Case, layout: int = 0):
         from paper_2504_12984_amd import binding as B
         self.B = B
+        self.layout = layout
         self.case = c = case
         self.inp = WL.make_inputs(c)
         self.wtype = B.WType(c.kind, c.bits, c.ebits, c.mbits)
@@ -38,7 +39,7 @@ class FullCase:
         self.d_scales = self.inp["scales"].cuda()
         self.d_zeros = None if self.inp["zeros"] is None else torch.from_numpy(self.inp["zeros"]).cuda()
         d_stream = torch.from_numpy(self.stream).cuda()
-        self.d_packed = B.repack(d_stream, self.wtype, c.K, c.N)
+        self.d_packed = B.repack(d_stream, self.wtype, c.K, c.N, layout=layout)
         del d_stream
         self.d_cols = torch.from_numpy(self.cols).cuda()
 
@@ -52,7 +53,8 @@ class FullCase:
 
     def check_weights(self):
         c = self.case
-        W = self.B.qdequant(self.d_packed, self.d_scales, self.d_zeros, self.wtype, ACT[c.act], c.group, c.K, c.N)
+        W = self.B.qdequant(self.d_packed, self.d_scales, self.d_zeros, self.wtype, ACT[c.act], c.group, c.K, c.N,
+                            layout=self.layout)
         got = bits_of(W[:, self.d_cols])
         del W
         wr, want = self.oracle_w_cols()
@@ -61,7 +63,8 @@ class FullCase:
 
     def check_gemm(self, A: torch.Tensor, wr: np.ndarray, tag: str):
         c = self.case
-        C = self.B.qgemm(A.cuda(), self.d_packed, self.d_scales, self.d_zeros, self.wtype, c.group, c.N)
+        C = self.B.qgemm(A.cuda(), self.d_packed, self.d_scales, self.d_zeros, self.wtype, c.group, c.N,
+                         layout=self.layout)
         got = to_f64(C[:, self.d_cols])
         ref = O.gemm_fp64(to_f64(A), wr)
         ok = O.within_tolerance(got, ref)
@@ -103,6 +106,22 @@ def test_config5_prefill_full(bits):
     wr = f.check_weights()
     for M in (1024, 4096):
         f.check_gemm(_A_of(WL.cfg5(bits, M)), wr, f"cfg5 u{bits} M={M}")
+
+
+def test_config5_prefill_full_on_the_second_layout():
+    f = FullCase(WL.cfg5(6, 1024), layout=1)
+    wr = f.check_weights()
+    for M in (1024, 4096):
+        f.check_gemm(_A_of(WL.cfg5(6, M)), wr, f"cfg5 u6 M={M} layout 1")
+
+
+@pytest.mark.parametrize("kind,bits", [(WL.KIND_UINT, 1), (WL.KIND_UINT, 7), (WL.KIND_FLOAT, 3), (WL.KIND_FLOAT, 5),
+                                       (WL.KIND_FLOAT, 7)])
+def test_type_sweep_shapes_full(kind, bits):
+    # the wide sweep shape (N = 57344) for types the five configurations do not cover
+    f = FullCase(WL.sweep(kind, bits))
+    wr = f.check_weights()
+    f.check_gemm(f.inp["A"], wr, f.case.name)
 
 
 def test_generator_draw_order_gives_A_first():
