@@ -13,12 +13,15 @@ namespace qg {
 typedef uint32_t u4_t __attribute__((ext_vector_type(4)));
 typedef float f16_t __attribute__((ext_vector_type(16)));
 
-__global__ __launch_bounds__(256) void probe_stream_kernel(const uint4* __restrict__ src, size_t n16, uint32_t* sink) {
+// grid-stride, four independent non-temporal 16-byte loads per lane and iteration
+// (the fastest plain read found on this chip: 4.85 us for 22 MB, 6.2 TB/s for 235 MB)
+__global__ __launch_bounds__(256) void probe_stream_kernel(const u4_t* __restrict__ src, size_t n16, uint32_t* sink) {
   size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   const size_t stride = (size_t)gridDim.x * blockDim.x;
   uint32_t acc = 0;
   for (; i + 3 * stride < n16; i += 4 * stride) {
-    uint4 a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
+    u4_t a = __builtin_nontemporal_load(src + i), b = __builtin_nontemporal_load(src + i + stride);
+    u4_t c = __builtin_nontemporal_load(src + i + 2 * stride), d = __builtin_nontemporal_load(src + i + 3 * stride);
     acc ^= a.x + b.y + c.z + d.w;
   }
   for (; i < n16; i += stride) acc ^= src[i].x;
@@ -64,8 +67,10 @@ __global__ __launch_bounds__(256) void probe_mfma_kernel(int iters, int random_d
 }
 
 int launch_probe_stream(const void* buf, size_t bytes, void* sink, hipStream_t st) {
-  hipLaunchKernelGGL(probe_stream_kernel, dim3(2048), dim3(256), 0, st, static_cast<const uint4*>(buf), bytes / 16,
-                     static_cast<uint32_t*>(sink));
+  size_t blocks = bytes / 32768;                         // about two iterations per lane
+  blocks = blocks < 2048 ? 2048 : (blocks > 8192 ? 8192 : blocks);
+  hipLaunchKernelGGL(probe_stream_kernel, dim3((unsigned)blocks), dim3(256), 0, st, static_cast<const u4_t*>(buf),
+                     bytes / 16, static_cast<uint32_t*>(sink));
   return hipGetLastError() == hipSuccess ? QG_OK : QG_EHIP;
 }
 
