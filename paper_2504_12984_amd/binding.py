@@ -14,7 +14,8 @@ from dataclasses import dataclass
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libqgemm.so")
+# QGEMM_LIB names another build of the same library (experiments with kernel variants)
+LIB_PATH = os.environ.get("QGEMM_LIB") or os.path.join(_HERE, "libqgemm.so")
 
 QG_OK, QG_EINVAL, QG_EUNSUPPORTED, QG_EHIP = 0, -1, -2, -3
 QG_UINT, QG_INT, QG_FLOAT = 0, 1, 2

@@ -156,23 +156,26 @@ struct Decoder<WT, ROUTE_F16, LY> {
     }
   };
 
-  static __device__ __forceinline__ void make_consts(Consts& gc, uint2 sraw, uint32_t zraw, int zbias, int /*scale_bf16*/) {
-    uint32_t sw[2] = {sraw.x, sraw.y};
+  // constants of one of the lane's columns (callers that spread the work over
+  // several places build column by column)
+  static __device__ __forceinline__ void make_col(Consts& gc, int nt, uint2 sraw, uint32_t zraw, int zbias, int /*scale_bf16*/) {
+    const uint32_t sw = (nt >> 1) ? sraw.y : sraw.x;
+    const uint32_t s16 = (nt & 1) ? (sw >> 16) : (sw & 0xffffu);
+    gc.s[nt] = as_h2(s16 | (s16 << 16));
+    if constexpr (!IS_FLOAT) {
+      uint32_t z = ((zraw >> (8 * nt)) & 0xffu) + (uint32_t)zbias;   // < 1024
+      h2_t c0 = as_h2(dup16(0x6400u) | z | (z << 16));               // 1024 + z', exact
+      gc.c[0][nt] = c0;
 #pragma unroll
-    for (int nt = 0; nt < NTL; ++nt) {
-      uint32_t s16 = (nt & 1) ? (sw[nt >> 1] >> 16) : (sw[nt >> 1] & 0xffffu);
-      gc.s[nt] = as_h2(s16 | (s16 << 16));
-      if constexpr (!IS_FLOAT) {
-        uint32_t z = ((zraw >> (8 * nt)) & 0xffu) + (uint32_t)zbias;   // < 1024
-        h2_t c0 = as_h2(dup16(0x6400u) | z | (z << 16));               // 1024 + z', exact
-        gc.c[0][nt] = c0;
-#pragma unroll
-        for (int w = 1; w < WN; ++w) {
-          const _Float16 d = (_Float16)(float)((1 << (10 - w * BITS)) - 1024);
-          gc.c[w][nt] = c0 + (h2_t){d, d};                             // exact: integers < 2048
-        }
+      for (int w = 1; w < WN; ++w) {
+        const _Float16 d = (_Float16)(float)((1 << (10 - w * BITS)) - 1024);
+        gc.c[w][nt] = c0 + (h2_t){d, d};                             // exact: integers < 2048
       }
     }
+  }
+  static __device__ __forceinline__ void make_consts(Consts& gc, uint2 sraw, uint32_t zraw, int zbias, int scale_bf16) {
+#pragma unroll
+    for (int nt = 0; nt < NTL; ++nt) make_col(gc, nt, sraw, zraw, zbias, scale_bf16);
   }
 
   // The same pair in three separately schedulable phases (extract / centre or
@@ -268,28 +271,29 @@ struct Decoder<WT, ROUTE_BF16, LY> {
     }
   };
 
-  static __device__ __forceinline__ void make_consts(Consts& gc, uint2 sraw, uint32_t zraw, int zbias, int scale_bf16) {
-    uint32_t sw[2] = {sraw.x, sraw.y};
+  static __device__ __forceinline__ void make_col(Consts& gc, int nt, uint2 sraw, uint32_t zraw, int zbias, int scale_bf16) {
+    const uint32_t sw = (nt >> 1) ? sraw.y : sraw.x;
+    const uint32_t s16 = (nt & 1) ? (sw >> 16) : (sw & 0xffffu);
+    // widen the 16-bit scale exactly; both forms are computed and one is
+    // selected with a mask so that no branch lands in the pipelined loops
+    const uint32_t from_h = __builtin_bit_cast(uint32_t, (float)__builtin_bit_cast(_Float16, (uint16_t)s16));
+    const uint32_t sel = scale_bf16 ? 0xffffffffu : 0u;
+    float s = __builtin_bit_cast(float, ((s16 << 16) & sel) | (from_h & ~sel));
+    if constexpr (!IS_FLOAT) {
+      gc.s[nt] = s;
+      float z = (float)(int)(((zraw >> (8 * nt)) & 0xffu) + (uint32_t)zbias);
 #pragma unroll
-    for (int nt = 0; nt < NTL; ++nt) {
-      uint32_t s16 = (nt & 1) ? (sw[nt >> 1] >> 16) : (sw[nt >> 1] & 0xffffu);
-      // widen the 16-bit scale exactly; both forms are computed and one is
-      // selected with a mask so that no branch lands in the pipelined loops
-      const uint32_t from_h = __builtin_bit_cast(uint32_t, (float)__builtin_bit_cast(_Float16, (uint16_t)s16));
-      const uint32_t sel = scale_bf16 ? 0xffffffffu : 0u;
-      float s = __builtin_bit_cast(float, ((s16 << 16) & sel) | (from_h & ~sel));
-      if constexpr (!IS_FLOAT) {
-        gc.s[nt] = s;
-        float z = (float)(int)(((zraw >> (8 * nt)) & 0xffu) + (uint32_t)zbias);
-#pragma unroll
-        for (int w = 0; w < WN; ++w) gc.ncs[w][nt] = -((float)(1 << (10 - w * BITS)) + z) * s;
-      } else if constexpr (NATURAL) {
-        gc.s[nt] = s;
-      } else {
-        constexpr int ADJ = 15 - ((1 << (EB - 1)) - 1);
-        gc.s[nt] = s * (float)(1 << ADJ);
-      }
+      for (int w = 0; w < WN; ++w) gc.ncs[w][nt] = -((float)(1 << (10 - w * BITS)) + z) * s;
+    } else if constexpr (NATURAL) {
+      gc.s[nt] = s;
+    } else {
+      constexpr int ADJ = 15 - ((1 << (EB - 1)) - 1);
+      gc.s[nt] = s * (float)(1 << ADJ);
     }
+  }
+  static __device__ __forceinline__ void make_consts(Consts& gc, uint2 sraw, uint32_t zraw, int zbias, int scale_bf16) {
+#pragma unroll
+    for (int nt = 0; nt < NTL; ++nt) make_col(gc, nt, sraw, zraw, zbias, scale_bf16);
   }
 
   static __device__ __forceinline__ uint32_t pk_bf16(float lo, float hi) {

@@ -49,7 +49,10 @@ __device__ __forceinline__ uint32_t pack_out32(float lo, float hi) {
 
 constexpr int L32_BN = 256;
 constexpr int L32_GROUP_M = 4;   // m-tiles per L2 panel
-constexpr int L32_AHEAD = 4;     // k-steps between the global load of an A piece and its LDS store
+#ifndef L32_AH
+#define L32_AH 4
+#endif
+constexpr int L32_AHEAD = L32_AH;   // k-steps between the global load of an A piece and its LDS store (2, 4 or 8)
 #ifndef L32_RA
 #define L32_RA 2
 #endif
@@ -109,17 +112,21 @@ __global__ __launch_bounds__(256) void large32_kernel(GemmParams p, int tiles_m,
   // ---- A staging: piece i of thread t is the 16 bytes at row (t/16) + 16*i, byte
   // 16*(t%16) of the chunk's 256-byte row segment (16 adjacent lanes read one
   // segment).  It lands in slice (t%16)/2, piece (t%16)%2 of that row.
-  const uint8_t* abytes = reinterpret_cast<const uint8_t*>(p.A);
+  // Loads go through a buffer resource over A: the per-lane part of the address is one
+  // 32-bit register (row and position inside the chunk's row segment), everything
+  // uniform (which 16-row block, which chunk) is scalar, and rows past M -- byte
+  // offsets at or beyond M*K*2 -- read as zeros by the resource's range check
+  // instead of needing a clamp.  (The host checks M*K*2 < 2^32.)
   const int srow = tid >> 4, spc = tid & 15;
-  // byte offsets into A (the host checks M*K*2 < 2^32); rows past M shadow row M-1,
-  // and since offsets grow with the row that is a min against the last row's offset
+  const __amdgpu_buffer_rsrc_t a_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<uint16_t*>(p.A), 0, (int)((uint32_t)p.M * (uint32_t)(2 * p.K)), 0x00020000);
   const uint32_t a_off0 = (uint32_t)(m0 + srow) * (uint32_t)(2 * p.K) + 16u * spc;
-  const uint32_t a_offmax = (uint32_t)(p.M - 1) * (uint32_t)(2 * p.K) + 16u * spc;
   const uint32_t a_step = 16u * (uint32_t)(2 * p.K);                      // 16 rows further
   const int a_dst = (spc >> 1) * L::SLICE + srow * 32 + 16 * ((spc & 1) ^ swz32(srow));   // + 512*i for piece i
   auto a_load = [&](int i, int c) __attribute__((always_inline)) {
-    const uint32_t off = min(a_off0 + (uint32_t)i * a_step, a_offmax);
-    return *reinterpret_cast<const u4_t*>(abytes + (size_t)min(c, KC - 1) * (2 * TILE_K) + off);
+    // the row part stays in the vector offset so that the range check sees it
+    return __builtin_amdgcn_raw_buffer_load_b128(a_rsrc, (int)(a_off0 + (uint32_t)i * a_step),
+                                                 min(c, KC - 1) * (2 * TILE_K), 0);
   };
   u4_t stage[L32_AHEAD][PPS];
 
@@ -130,28 +137,33 @@ __global__ __launch_bounds__(256) void large32_kernel(GemmParams p, int tiles_m,
     uint32_t z0, z1;
   };
   const uint4* wstrip = reinterpret_cast<const uint4*>(p.W + (int64_t)nc * KC * (1024 * BITS)) + l;
-  auto w_issue = [&](WStage& s, int c) __attribute__((always_inline)) {
+  // The loads of one chunk are 2 (4 with two groups per chunk) + BITS separate
+  // pieces, so that the main loop can issue them a few at a time in different gaps
+  // between matrix instructions.  Pieces: s0, z0, (s1, z1,) then BITS x 16 bytes of codes.
+  constexpr int WMETA = TWO_GROUPS ? 4 : 2;
+  constexpr int WPIECES = WMETA + BITS;
+  auto w_piece = [&](WStage& s, int c, auto Ic) __attribute__((always_inline)) {
+    constexpr int I = decltype(Ic)::value;
     c = min(c, KC - 1);
-    const uint4* src = wstrip + (int64_t)c * (64 * BITS);
-#pragma unroll
-    for (int i = 0; i < BITS; ++i) {
-      uint4 q = src[i * 64];
-      s.r[4 * i + 0] = q.x; s.r[4 * i + 1] = q.y; s.r[4 * i + 2] = q.z; s.r[4 * i + 3] = q.w;
-    }
-    const int g0 = TWO_GROUPS ? 2 * c : ((c >> p.gshift) & p.gmask);
-    s.s0 = *reinterpret_cast<const uint32_t*>(p.S + (int64_t)g0 * p.N + n0);
-    s.z0 = *reinterpret_cast<const uint16_t*>(zbase + (int64_t)g0 * p.N + n0);
-    if constexpr (TWO_GROUPS) {
-      s.s1 = *reinterpret_cast<const uint32_t*>(p.S + (int64_t)(g0 + 1) * p.N + n0);
-      s.z1 = *reinterpret_cast<const uint16_t*>(zbase + (int64_t)(g0 + 1) * p.N + n0);
+    if constexpr (I >= WMETA) {
+      constexpr int B = I - WMETA;
+      const uint4 q = (wstrip + (int64_t)c * (64 * BITS))[B * 64];
+      s.r[4 * B + 0] = q.x; s.r[4 * B + 1] = q.y; s.r[4 * B + 2] = q.z; s.r[4 * B + 3] = q.w;
+    } else {
+      const int g0 = TWO_GROUPS ? 2 * c : ((c >> p.gshift) & p.gmask);
+      if constexpr (I == 0) s.s0 = *reinterpret_cast<const uint32_t*>(p.S + (int64_t)g0 * p.N + n0);
+      if constexpr (I == 1) s.z0 = *reinterpret_cast<const uint16_t*>(zbase + (int64_t)g0 * p.N + n0);
+      if constexpr (I == 2) s.s1 = *reinterpret_cast<const uint32_t*>(p.S + (int64_t)(g0 + 1) * p.N + n0);
+      if constexpr (I == 3) s.z1 = *reinterpret_cast<const uint16_t*>(zbase + (int64_t)(g0 + 1) * p.N + n0);
     }
   };
-  // constants of the first (or only) group of a chunk, and of its second group
-  auto consts0 = [&](typename D::Consts& g, const WStage& s) __attribute__((always_inline)) {
-    D::make_consts(g, make_uint2(s.s0, 0u), s.z0 & zmask, p.zbias, p.scale_bf16);
+  auto w_issue = [&](WStage& s, int c) __attribute__((always_inline)) {
+    static_for<WPIECES>([&](auto Ic) __attribute__((always_inline)) { w_piece(s, c, Ic); });
   };
-  auto consts1 = [&](typename D::Consts& g, const WStage& s) __attribute__((always_inline)) {
-    D::make_consts(g, make_uint2(s.s1, 0u), s.z1 & zmask, p.zbias, p.scale_bf16);
+  // constants of one column of the first (G = 0) or second (G = 1) group of a chunk
+  auto consts_col = [&](typename D::Consts& g, const WStage& s, auto Gc, int nt) __attribute__((always_inline)) {
+    if constexpr (decltype(Gc)::value == 0) D::make_col(g, nt, make_uint2(s.s0, 0u), s.z0 & zmask, p.zbias, p.scale_bf16);
+    else                                    D::make_col(g, nt, make_uint2(s.s1, 0u), s.z1 & zmask, p.zbias, p.scale_bf16);
   };
 
   // Accumulators live in the accumulation registers (AGPRs) for the whole
@@ -171,6 +183,9 @@ __global__ __launch_bounds__(256) void large32_kernel(GemmParams p, int tiles_m,
   // ---- prologue: chunk 0's A slab into buffer 0, ring primed for chunk 1 --------------
   WStage wA, wB;
   w_issue(wA, 0);
+#ifdef L32_DBG_NOW
+  wB = wA;
+#endif
 #pragma unroll
   for (int i = 0; i < PT; ++i) *reinterpret_cast<u4_t*>(lds + a_dst + 512 * i) = a_load(i, 0);
 #pragma unroll
@@ -184,27 +199,54 @@ __global__ __launch_bounds__(256) void large32_kernel(GemmParams p, int tiles_m,
   // Weight fragments are unpacked one k-step ahead of their use, and the unpack
   // of step J+1 is spread over the MFMAs of step J (PB pairs per 32-row tile),
   // so the vector ALU works in the shadow of the matrix pipeline.  Fragments
-  // ping-pong between two register sets by k-step parity, weight stages by chunk
-  // parity (the chunk loop is unrolled by two).  Group constants are rebuilt in
-  // place just before their first use: g0 (first half of a chunk, or all of it)
-  // during the last k-step of the chunk before, g1 (second half, group size 64)
-  // during the k-step before the half -- each is dead by then.
-  typename D::Consts g0, g1;
-  consts0(g0, wA);
+  // ping-pong between two register sets by k-step parity, weight stages and
+  // their constants by chunk parity (the chunk loop is unrolled by two).
+  //
+  // With one wavefront per SIMD every instruction of any kind takes an issue slot
+  // of that one wavefront, and only about five fit behind a 32x32x16 MFMA before
+  // the matrix pipeline starts to idle.  So everything that is not an MFMA is cut
+  // into small items and dealt out over the 2*MTS gaps of every k-step:
+  //   gap after the first MFMA of a tile:   extract this tile's pairs, read the A
+  //                                         fragment RA tiles ahead, round the
+  //                                         previous tile's pairs
+  //   gap after the second MFMA of a tile:  centre / widen this tile's pairs, plus
+  //                                         ONE extra item: an A staging piece
+  //                                         (store + next load), or one load of the
+  //                                         next chunk's weights, or the constants
+  //                                         of one column of the next chunk
+  // Constants of a chunk's first (or only) group ping-pong with the weight stages; those
+  // of its second group (group size 64) live in one set that is rebuilt in place at the
+  // start of the chunk, after its last use by the chunk before and before its first use.
+  typename D::Consts gA0, gB0, g1;
+  consts_col(gA0, wA, std::integral_constant<int, 0>{}, 0);
+  consts_col(gA0, wA, std::integral_constant<int, 0>{}, 1);
   u4_t wf[2][2];
   static_for<2>([&](auto NTc) __attribute__((always_inline)) {
     constexpr int NT = decltype(NTc)::value;
     uint32_t o[4];
-    D::template frag<0, NT>(wA.r, g0, u, o);
+    D::template frag<0, NT>(wA.r, gA0, u, o);
     wf[0][NT] = (u4_t){o[0], o[1], o[2], o[3]};
   });
   __syncthreads();
 
-  // one chunk: weights wc are consumed, wn is loaded; CUR is the LDS buffer holding
-  // this chunk's A slab
-  auto chunk = [&](auto CURc, WStage& wc, WStage& wn, int kc) __attribute__((always_inline)) {
+  // Extra-item table.  Tiles whose second gap carries an A staging piece: MT = 1 + q*(MTS/PPS).
+  // The other tiles of the chunk, in order, are numbered FS = 0, 1, ...:
+  //   FS 0, 1 (two groups per chunk only): this chunk's second-group constants, one column each
+  //   then WPS pieces of the next chunk's weights per tile until all are issued
+  //   from k-step 5 on: the next chunk's first-group constants, one column per tile
+  //   (its scale loads went out in k-step 0 and have long arrived).
+  constexpr int STAGE_EVERY = MTS / PPS;
+  constexpr int FREE_PER_STEP = MTS - PPS;
+  constexpr int WPS = (BM == 128) ? 2 : 1;             // shorter k-steps: issue the loads twice as densely
+  constexpr int W0 = TWO_GROUPS ? 2 : 0;
+  constexpr int WSLOTS = (WPIECES + WPS - 1) / WPS;
+  static_assert(W0 + WSLOTS <= 3 * FREE_PER_STEP, "weight loads must be issued by the end of k-step 2");
+
+  // one chunk: weights wc (constants gc0, g1) are consumed, wn is loaded and its
+  // constants gn0 built; CUR is the LDS buffer holding this chunk's A slab
+  auto chunk = [&](auto CURc, WStage& wc, WStage& wn, typename D::Consts& gc0, typename D::Consts& gn0,
+                   int kc) __attribute__((always_inline)) {
     constexpr int CUR = decltype(CURc)::value, NXT = CUR ^ 1;
-    w_issue(wn, kc + 1);
     // A fragments: flat index f = J*MTS + MT over the chunk, read RA tiles ahead
     const uint8_t* abase = lds + CUR * L::BUF + a_rd;
     auto a_read = [&](int f) __attribute__((always_inline)) {
@@ -217,20 +259,14 @@ __global__ __launch_bounds__(256) void large32_kernel(GemmParams p, int tiles_m,
     static_for<NS>([&](auto Jc) __attribute__((always_inline)) {
       constexpr int J = decltype(Jc)::value;
       constexpr int JN = (J + 1) % NS;
-      if constexpr (J == NS - 1) consts0(g0, wn);
-      if constexpr (TWO_GROUPS && J == NS / 2 - 1) consts1(g1, wc);
       uint32_t nf[2][4];                 // fragments of k-step J+1 under construction
       uint32_t xe[PB];
       typename D::Mid mid[PB], mid_prev[PB];
-      const typename D::Consts& g = (TWO_GROUPS && JN >= NS / 2) ? g1 : g0;
+      const typename D::Consts& g = (J < NS - 1) ? ((TWO_GROUPS && JN >= NS / 2) ? g1 : gc0) : gn0;
       const uint32_t (&rw)[RAW] = (J < NS - 1) ? wc.r : wn.r;
       static_for<MTS>([&](auto MTc) __attribute__((always_inline)) {
         constexpr int MT = decltype(MTc)::value;
         constexpr int F = J * MTS + MT;
-        // The unpack of this tile's PB pairs is cut into three phases placed in
-        // different gaps between matrix instructions, the last phase one tile
-        // later: a consumer never directly follows its producer (the compiler
-        // cannot see through the asm MFMA and would pad such pairs with s_nop).
         mfma32_acc<ROUTE>(acc[MT][0], wf[J & 1][0], ar[F % (RA + 1)]);
         __builtin_amdgcn_sched_barrier(0);
         static_for<PB>([&](auto Qc) __attribute__((always_inline)) {          // extract
@@ -251,15 +287,30 @@ __global__ __launch_bounds__(256) void large32_kernel(GemmParams p, int tiles_m,
           constexpr int Q = decltype(Qc)::value, R = MT * PB + Q;
           mid[Q] = D::template pair_s<LY::t0(JN, R / 4) + R % 4>(xe[Q], g, R / 4);
         });
-        // A slab of the next chunk, PPS 16-byte pieces per thread per k-step:
-        // store the piece loaded L32_AHEAD steps ago, then start the load that
-        // will be stored L32_AHEAD steps from now
-        if constexpr ((MT - 1) % (MTS / PPS) == 0 && MT >= 1) {
-          constexpr int Q = (MT - 1) / (MTS / PPS);
+        // ---- the one extra item of this tile --------------------------------------------
+        constexpr bool STAGES = (MT >= 1) && ((MT - 1) % STAGE_EVERY == 0);
+        if constexpr (STAGES) {
+          // A slab of the next chunk: store the piece loaded L32_AHEAD steps ago, then
+          // start the load that will be stored L32_AHEAD steps from now
+#ifndef L32_DBG_NOSTAGE
+          constexpr int Q = (MT - 1) / STAGE_EVERY;
           constexpr int SET = J % L32_AHEAD;
           *reinterpret_cast<u4_t*>(lds + NXT * L::BUF + a_dst + 512 * (PPS * J + Q)) = stage[SET][Q];
           constexpr int TS = J + L32_AHEAD;            // target step, counted from this chunk's first
           stage[SET][Q] = a_load(PPS * (TS % NS) + Q, kc + 1 + TS / NS);
+#endif
+        } else {
+          constexpr int BEFORE = (MT == 0) ? 0 : (MT - 1 - (MT - 1) / STAGE_EVERY);   // free tiles before MT in this step
+          constexpr int FS = J * FREE_PER_STEP + BEFORE;
+          if constexpr (TWO_GROUPS && FS < 2) consts_col(g1, wc, std::integral_constant<int, 1>{}, FS);
+#ifndef L32_DBG_NOW
+          static_for<WPS>([&](auto Xc) __attribute__((always_inline)) {
+            constexpr int I = (FS - W0) * WPS + decltype(Xc)::value;
+            if constexpr (FS >= W0 && I < WPIECES) w_piece(wn, kc + 1, std::integral_constant<int, I>{});
+          });
+#endif
+          constexpr int CS = FS - 5 * FREE_PER_STEP;   // first free tiles of k-step 5
+          if constexpr (CS == 0 || CS == 1) consts_col(gn0, wn, std::integral_constant<int, 0>{}, CS);
         }
 #pragma unroll
         for (int q = 0; q < PB; ++q) mid_prev[q] = mid[q];
@@ -272,15 +323,17 @@ __global__ __launch_bounds__(256) void large32_kernel(GemmParams p, int tiles_m,
 #pragma unroll
       for (int nt = 0; nt < 2; ++nt) wf[JN & 1][nt] = (u4_t){nf[nt][0], nf[nt][1], nf[nt][2], nf[nt][3]};
     });
+#ifndef L32_DBG_NOBARRIER
     __syncthreads();
+#endif
   };
 
   int kc = 0;
   for (; kc + 2 <= KC; kc += 2) {
-    chunk(std::integral_constant<int, 0>{}, wA, wB, kc);
-    chunk(std::integral_constant<int, 1>{}, wB, wA, kc + 1);
+    chunk(std::integral_constant<int, 0>{}, wA, wB, gA0, gB0, kc);
+    chunk(std::integral_constant<int, 1>{}, wB, wA, gB0, gA0, kc + 1);
   }
-  if (kc < KC) chunk(std::integral_constant<int, 0>{}, wA, wB, kc);
+  if (kc < KC) chunk(std::integral_constant<int, 0>{}, wA, wB, gA0, gB0, kc);
 
   // the matrix pipeline may still be writing the accumulators (the compiler
   // does not see the asm MFMAs, so it inserts no wait states of its own)
