@@ -19,6 +19,9 @@
 // the last workgroup to arrive (the k-dimension parallelisation the paper names
 // in Section "End-to-End Performance").
 // Compiled once per weight type (QG_WT).
+// QG_DBG_NODECODE / NOMFMA / NOSZ / NOREDUCE (never defined by the build) each cut one
+// stage out for timing experiments -- results are wrong with them; QG_SZ_BCAST and
+// QG_W_FIRST are two measured-and-rejected orderings of the scale and weight loads.
 #include "qg_decode.h"
 #include "qg_static_for.h"
 

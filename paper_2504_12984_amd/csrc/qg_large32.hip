@@ -49,14 +49,9 @@ __device__ __forceinline__ uint32_t pack_out32(float lo, float hi) {
 
 constexpr int L32_BN = 256;
 constexpr int L32_GROUP_M = 4;   // m-tiles per L2 panel
-#ifndef L32_AH
-#define L32_AH 4
-#endif
-constexpr int L32_AHEAD = L32_AH;   // k-steps between the global load of an A piece and its LDS store (2, 4 or 8)
-#ifndef L32_RA
-#define L32_RA 2
-#endif
-constexpr int L32_READ_AHEAD = L32_RA;   // row tiles between the LDS read of an A fragment and its use
+constexpr int L32_AHEAD = 4;        // k-steps between the global load of an A piece and its LDS store (2, 4 or 8;
+                                    // measured: no difference between them)
+constexpr int L32_READ_AHEAD = 2;   // row tiles between the LDS read of an A fragment and its use (2..6 measure alike)
 
 // LDS: the A slab of one chunk = 8 k-step slices, each [BM rows][2 pieces of 16 B]
 // plus 32 bytes of padding; piece h of row r sits at slot h ^ swz(r).  A fragment
@@ -183,9 +178,6 @@ __global__ __launch_bounds__(256) void large32_kernel(GemmParams p, int tiles_m,
   // ---- prologue: chunk 0's A slab into buffer 0, ring primed for chunk 1 --------------
   WStage wA, wB;
   w_issue(wA, 0);
-#ifdef L32_DBG_NOW
-  wB = wA;
-#endif
 #pragma unroll
   for (int i = 0; i < PT; ++i) *reinterpret_cast<u4_t*>(lds + a_dst + 512 * i) = a_load(i, 0);
 #pragma unroll
@@ -292,23 +284,19 @@ __global__ __launch_bounds__(256) void large32_kernel(GemmParams p, int tiles_m,
         if constexpr (STAGES) {
           // A slab of the next chunk: store the piece loaded L32_AHEAD steps ago, then
           // start the load that will be stored L32_AHEAD steps from now
-#ifndef L32_DBG_NOSTAGE
           constexpr int Q = (MT - 1) / STAGE_EVERY;
           constexpr int SET = J % L32_AHEAD;
           *reinterpret_cast<u4_t*>(lds + NXT * L::BUF + a_dst + 512 * (PPS * J + Q)) = stage[SET][Q];
           constexpr int TS = J + L32_AHEAD;            // target step, counted from this chunk's first
           stage[SET][Q] = a_load(PPS * (TS % NS) + Q, kc + 1 + TS / NS);
-#endif
         } else {
           constexpr int BEFORE = (MT == 0) ? 0 : (MT - 1 - (MT - 1) / STAGE_EVERY);   // free tiles before MT in this step
           constexpr int FS = J * FREE_PER_STEP + BEFORE;
           if constexpr (TWO_GROUPS && FS < 2) consts_col(g1, wc, std::integral_constant<int, 1>{}, FS);
-#ifndef L32_DBG_NOW
           static_for<WPS>([&](auto Xc) __attribute__((always_inline)) {
             constexpr int I = (FS - W0) * WPS + decltype(Xc)::value;
             if constexpr (FS >= W0 && I < WPIECES) w_piece(wn, kc + 1, std::integral_constant<int, I>{});
           });
-#endif
           constexpr int CS = FS - 5 * FREE_PER_STEP;   // first free tiles of k-step 5
           if constexpr (CS == 0 || CS == 1) consts_col(gn0, wn, std::integral_constant<int, 0>{}, CS);
         }
@@ -323,9 +311,7 @@ __global__ __launch_bounds__(256) void large32_kernel(GemmParams p, int tiles_m,
 #pragma unroll
       for (int nt = 0; nt < 2; ++nt) wf[JN & 1][nt] = (u4_t){nf[nt][0], nf[nt][1], nf[nt][2], nf[nt][3]};
     });
-#ifndef L32_DBG_NOBARRIER
     __syncthreads();
-#endif
   };
 
   int kc = 0;
