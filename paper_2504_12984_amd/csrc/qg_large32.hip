@@ -369,7 +369,18 @@ static int launch_bm(const GemmParams& p, hipStream_t st) {
 
 template <int ROUTE>
 static int launch_route(const GemmParams& p, int bm, hipStream_t st) {
-  if (bm == 0) bm = (p.M > 128) ? 256 : 128;
+  if (bm == 0) {
+    // Row-tile height by a small cost model: workgroups run in rounds of 256 (one per
+    // CU), a tile costs its rows plus about 64 rows' worth of unpack and start-up.
+    // 128 rows win when they fill a round that 256 rows leave half empty (M <= 256 on
+    // 28672 columns, M = 384 on 57344: measured 20-30 % shorter), 256 rows otherwise.
+    const long tiles_n = (p.N + L32_BN - 1) / L32_BN;
+    auto cost = [&](int rows) {
+      const long tiles = ((p.M + rows - 1) / rows) * tiles_n;
+      return ((tiles + 255) / 256) * (rows + 64);
+    };
+    bm = (p.M <= 128 || cost(128) < cost(256)) ? 128 : 256;
+  }
   const bool tg = (p.group == 64);
   if (bm == 128) return tg ? launch_bm<ROUTE, true, 128>(p, st) : launch_bm<ROUTE, false, 128>(p, st);
   if (bm == 256) return tg ? launch_bm<ROUTE, true, 256>(p, st) : launch_bm<ROUTE, false, 256>(p, st);
