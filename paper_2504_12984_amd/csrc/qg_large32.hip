@@ -131,7 +131,17 @@ __global__ __launch_bounds__(256) void large32_kernel(GemmParams p, int tiles_m,
     uint32_t s0, s1;
     uint32_t z0, z1;
   };
-  const uint4* wstrip = reinterpret_cast<const uint4*>(p.W + (int64_t)nc * KC * (1024 * BITS)) + l;
+  // All of these go through buffer resources too: the lane's part of the address is
+  // a constant 32-bit register, the chunk / group part a scalar.  (The host checks that
+  // the packed weight and the scale array are below 4 GiB.)
+  const __amdgpu_buffer_rsrc_t w_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<uint8_t*>(p.W), 0, (int)(uint32_t)((int64_t)p.K * p.N / 8 * BITS), 0x00020000);
+  const __amdgpu_buffer_rsrc_t s_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<uint16_t*>(p.S), 0, (int)(uint32_t)((int64_t)(p.K / p.group) * p.N * 2), 0x00020000);
+  const __amdgpu_buffer_rsrc_t z_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<uint8_t*>(zbase), 0, (int)(uint32_t)((int64_t)(p.K / p.group) * p.N), 0x00020000);
+  const int w_lane = 16 * l, s_lane = 2 * n0, z_lane = n0;
+  const int w_strip = nc * KC * (1024 * BITS);          // byte offset of my strip (scalar)
   // The loads of one chunk are 2 (4 with two groups per chunk) + BITS separate
   // pieces, so that the main loop can issue them a few at a time in different gaps
   // between matrix instructions.  Pieces: s0, z0, (s1, z1,) then BITS x 16 bytes of codes.
@@ -142,14 +152,14 @@ __global__ __launch_bounds__(256) void large32_kernel(GemmParams p, int tiles_m,
     c = min(c, KC - 1);
     if constexpr (I >= WMETA) {
       constexpr int B = I - WMETA;
-      const uint4 q = (wstrip + (int64_t)c * (64 * BITS))[B * 64];
+      const u4_t q = __builtin_amdgcn_raw_buffer_load_b128(w_rsrc, w_lane, w_strip + c * (1024 * BITS) + B * 1024, 0);
       s.r[4 * B + 0] = q.x; s.r[4 * B + 1] = q.y; s.r[4 * B + 2] = q.z; s.r[4 * B + 3] = q.w;
     } else {
       const int g0 = TWO_GROUPS ? 2 * c : ((c >> p.gshift) & p.gmask);
-      if constexpr (I == 0) s.s0 = *reinterpret_cast<const uint32_t*>(p.S + (int64_t)g0 * p.N + n0);
-      if constexpr (I == 1) s.z0 = *reinterpret_cast<const uint16_t*>(zbase + (int64_t)g0 * p.N + n0);
-      if constexpr (I == 2) s.s1 = *reinterpret_cast<const uint32_t*>(p.S + (int64_t)(g0 + 1) * p.N + n0);
-      if constexpr (I == 3) s.z1 = *reinterpret_cast<const uint16_t*>(zbase + (int64_t)(g0 + 1) * p.N + n0);
+      if constexpr (I == 0) s.s0 = __builtin_amdgcn_raw_buffer_load_b32(s_rsrc, s_lane, g0 * p.N * 2, 0);
+      if constexpr (I == 1) s.z0 = __builtin_amdgcn_raw_buffer_load_b16(z_rsrc, z_lane, g0 * p.N, 0);
+      if constexpr (I == 2) s.s1 = __builtin_amdgcn_raw_buffer_load_b32(s_rsrc, s_lane, (g0 + 1) * p.N * 2, 0);
+      if constexpr (I == 3) s.z1 = __builtin_amdgcn_raw_buffer_load_b16(z_rsrc, z_lane, (g0 + 1) * p.N, 0);
     }
   };
   auto w_issue = [&](WStage& s, int c) __attribute__((always_inline)) {
