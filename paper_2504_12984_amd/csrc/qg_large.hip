@@ -101,24 +101,30 @@ __global__ __launch_bounds__(256) void large_kernel(GemmParams p, int tiles_m, i
   const uint32_t zmask = p.Z ? 0xffffffffu : 0u;
 
   // ---- A staging: thread t moves pieces q = t + 256*i, row = q/4, piece = q%4 ---------
-  const uint16_t* a_src[PIECES];
-  int a_dst[PIECES];
-#pragma unroll
-  for (int i = 0; i < PIECES; ++i) {
-    const int q = tid + 256 * i, row = q >> 2, pc = q & 3;
-    a_src[i] = p.A + (int64_t)min(m0 + row, p.M - 1) * p.K + 8 * pc;   // rows past M shadow row M-1
-    a_dst[i] = row * 64 + 16 * (pc ^ lds_swizzle(row));
-  }
+  // Loads go through a buffer resource over A: the lane's part of the address is one
+  // 32-bit register, which 64-row block and which k-step is scalar, and rows past M --
+  // byte offsets at or beyond M*K*2 -- read as zeros by the resource's range check
+  // instead of needing a clamp.  (The host checks M*K*2 < 2^32.)
+  const __amdgpu_buffer_rsrc_t a_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<uint16_t*>(p.A), 0, (int)((uint32_t)p.M * (uint32_t)(2 * p.K)), 0x00020000);
+  const int srow = tid >> 2, spc = tid & 3;
+  const uint32_t a_off0 = (uint32_t)(m0 + srow) * (uint32_t)(2 * p.K) + 16u * spc;
+  const uint32_t a_step = 64u * (uint32_t)(2 * p.K);                      // 64 rows further
+  const int a_dst0 = srow * 64 + 16 * (spc ^ lds_swizzle(srow));          // + 4096*i for piece i
+  auto a_load = [&](int i, int kstep) __attribute__((always_inline)) {     // kstep = 4*chunk + slice
+    // the row part stays in the vector offset so that the range check sees it
+    return __builtin_amdgcn_raw_buffer_load_b128(a_rsrc, (int)(a_off0 + (uint32_t)i * a_step),
+                                                 min(kstep, 4 * KC - 1) * 64, 0);
+  };
   u4_t stage[2][PIECES];
-  auto a_issue = [&](int set, int kstep) __attribute__((always_inline)) {   // kstep = 4*chunk + slice
-    const int ks = min(kstep, 4 * KC - 1);
+  auto a_issue = [&](int set, int kstep) __attribute__((always_inline)) {
 #pragma unroll
-    for (int i = 0; i < PIECES; ++i) stage[set][i] = *reinterpret_cast<const u4_t*>(a_src[i] + ks * 32);
+    for (int i = 0; i < PIECES; ++i) stage[set][i] = a_load(i, kstep);
   };
   auto a_commit = [&](int set, int buf, int slice) __attribute__((always_inline)) {
 #pragma unroll
     for (int i = 0; i < PIECES; ++i)
-      *reinterpret_cast<u4_t*>(lds + buf * L::BUF + slice * L::SLICE + a_dst[i]) = stage[set][i];
+      *reinterpret_cast<u4_t*>(lds + buf * L::BUF + slice * L::SLICE + a_dst0 + 4096 * i) = stage[set][i];
   };
 
   // ---- W prefetch: raw chunk + its scales / zero-points -------------------------------
@@ -127,22 +133,44 @@ __global__ __launch_bounds__(256) void large_kernel(GemmParams p, int tiles_m, i
     uint2 s0, s1;
     uint32_t z0, z1;
   };
-  const uint4* wstrip = reinterpret_cast<const uint4*>(p.W + (int64_t)nc * KC * (1024 * BITS)) + l;
-  auto w_issue = [&](WStage& s, int c) __attribute__((always_inline)) {
+  // Through buffer resources as well (the host checks that the packed weight and the
+  // scale array are below 4 GiB): lane part constant, chunk / group part scalar.
+  const __amdgpu_buffer_rsrc_t w_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<uint8_t*>(p.W), 0, (int)(uint32_t)((int64_t)p.K * p.N / 8 * BITS), 0x00020000);
+  const __amdgpu_buffer_rsrc_t s_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<uint16_t*>(p.S), 0, (int)(uint32_t)((int64_t)(p.K / p.group) * p.N * 2), 0x00020000);
+  const __amdgpu_buffer_rsrc_t z_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<uint8_t*>(zbase), 0, (int)(uint32_t)((int64_t)(p.K / p.group) * p.N), 0x00020000);
+  const int w_lane = 16 * l, s_lane = 2 * n0, z_lane = n0;
+  const int w_strip = nc * KC * (1024 * BITS);          // byte offset of my strip (scalar)
+  // The loads of one chunk are 2 (4 with two groups per chunk) + BITS separate pieces,
+  // so that the main loop can issue them a few at a time in different gaps between
+  // matrix instructions.  Pieces: s0, z0, (s1, z1,) then BITS x 16 bytes of codes.
+  constexpr int WMETA = TWO_GROUPS ? 4 : 2;
+  constexpr int WPIECES = WMETA + BITS;
+  auto w_piece = [&](WStage& s, int c, auto Ic) __attribute__((always_inline)) {
+    constexpr int I = decltype(Ic)::value;
     c = min(c, KC - 1);
-    const uint4* src = wstrip + (int64_t)c * (64 * BITS);
-#pragma unroll
-    for (int i = 0; i < BITS; ++i) {
-      uint4 q = src[i * 64];
-      s.r[4 * i + 0] = q.x; s.r[4 * i + 1] = q.y; s.r[4 * i + 2] = q.z; s.r[4 * i + 3] = q.w;
+    if constexpr (I >= WMETA) {
+      constexpr int B = I - WMETA;
+      const u4_t q = __builtin_amdgcn_raw_buffer_load_b128(w_rsrc, w_lane, w_strip + c * (1024 * BITS) + B * 1024, 0);
+      s.r[4 * B + 0] = q.x; s.r[4 * B + 1] = q.y; s.r[4 * B + 2] = q.z; s.r[4 * B + 3] = q.w;
+    } else {
+      const int g0 = TWO_GROUPS ? 2 * c : ((c >> p.gshift) & p.gmask);
+      typedef uint32_t u2_t __attribute__((ext_vector_type(2)));
+      if constexpr (I == 0) { const u2_t v = __builtin_amdgcn_raw_buffer_load_b64(s_rsrc, s_lane, g0 * p.N * 2, 0); s.s0 = make_uint2(v.x, v.y); }
+      if constexpr (I == 1) s.z0 = __builtin_amdgcn_raw_buffer_load_b32(z_rsrc, z_lane, g0 * p.N, 0);
+      if constexpr (I == 2) { const u2_t v = __builtin_amdgcn_raw_buffer_load_b64(s_rsrc, s_lane, (g0 + 1) * p.N * 2, 0); s.s1 = make_uint2(v.x, v.y); }
+      if constexpr (I == 3) s.z1 = __builtin_amdgcn_raw_buffer_load_b32(z_rsrc, z_lane, (g0 + 1) * p.N, 0);
     }
-    const int g0 = TWO_GROUPS ? 2 * c : ((c >> p.gshift) & p.gmask);
-    s.s0 = *reinterpret_cast<const uint2*>(p.S + (int64_t)g0 * p.N + n0);
-    s.z0 = *reinterpret_cast<const uint32_t*>(zbase + (int64_t)g0 * p.N + n0);
-    if constexpr (TWO_GROUPS) {
-      s.s1 = *reinterpret_cast<const uint2*>(p.S + (int64_t)(g0 + 1) * p.N + n0);
-      s.z1 = *reinterpret_cast<const uint32_t*>(zbase + (int64_t)(g0 + 1) * p.N + n0);
-    }
+  };
+  auto w_issue = [&](WStage& s, int c) __attribute__((always_inline)) {
+    static_for<WPIECES>([&](auto Ic) __attribute__((always_inline)) { w_piece(s, c, Ic); });
+  };
+  // constants of one column of the first (G = 0) or second (G = 1) group of a chunk
+  auto consts_col = [&](typename D::Consts& g, const WStage& s, auto Gc, int nt) __attribute__((always_inline)) {
+    if constexpr (decltype(Gc)::value == 0) D::make_col(g, nt, s.s0, s.z0 & zmask, p.zbias, p.scale_bf16);
+    else                                    D::make_col(g, nt, s.s1, s.z1 & zmask, p.zbias, p.scale_bf16);
   };
 
   // Accumulators live in the accumulation registers (AGPRs) for the whole
@@ -172,28 +200,50 @@ __global__ __launch_bounds__(256) void large_kernel(GemmParams p, int tiles_m, i
   // Weight fragments are unpacked one k-step ahead of their use, and the unpack
   // of step J+1 is spread over the MFMAs of step J (one pair per 16-row tile),
   // so the vector ALU works in the shadow of the matrix pipeline.  Fragments
-  // ping-pong between two register sets by k-step parity, weight stages by chunk
-  // parity (the chunk loop is unrolled by two).  Group constants are rebuilt in
-  // place just before their first use: g0 (first half of a chunk, or all of it)
-  // during the last k-step of the chunk before, g1 (second half, group size 64)
-  // during the k-step before the half -- each is dead by then.
-  typename D::Consts g0, g1;
-  D::make_consts(g0, wA.s0, wA.z0 & zmask, p.zbias, p.scale_bf16);
+  // ping-pong between two register sets by k-step parity, weight stages and
+  // their first-group constants by chunk parity (the chunk loop is unrolled by two);
+  // the second-group constants (group size 64) live in one set rebuilt in place at
+  // the start of each chunk.
+  //
+  // With one wavefront per SIMD every instruction of any kind takes an issue slot
+  // of that one wavefront, and only about two fit behind a 16x16x32 MFMA before the
+  // matrix pipeline starts to idle.  So everything that is not an MFMA is cut into
+  // small items and dealt out over the four gaps of every row tile:
+  //   gap 0: extract this tile's pair          gap 1: read the A fragment two tiles
+  //   gap 2: centre / widen this tile's pair          ahead, round the previous pair
+  //   gap 3: ONE extra item -- an A staging piece (store + next load), or a load of
+  //          the next chunk's weights, or the constants of one column
+  typename D::Consts gA0, gB0, g1;
+  static_for<4>([&](auto NTc) __attribute__((always_inline)) {
+    consts_col(gA0, wA, std::integral_constant<int, 0>{}, decltype(NTc)::value);
+  });
   u4_t wf[2][4];
   static_for<4>([&](auto NTc) __attribute__((always_inline)) {
     constexpr int NT = decltype(NTc)::value;
     uint32_t o[4];
-    D::template frag<0, NT>(wA.r, g0, u, o);
+    D::template frag<0, NT>(wA.r, gA0, u, o);
     wf[0][NT] = (u4_t){o[0], o[1], o[2], o[3]};
   });
   __syncthreads();
 
-  // one chunk: weights wc are consumed, wn is loaded; CUR is the LDS buffer holding
-  // this chunk's A slab
-  auto chunk = [&](auto CURc, WStage& wc, WStage& wn, int kc) __attribute__((always_inline)) {
+  // Extra-item table.  Row tiles with MT % 4 == 0 (and MT / 4 < PIECES) carry a staging
+  // piece.  The other tiles of the chunk, in order, are numbered FS = 0, 1, ...:
+  //   FS 0..3 (two groups per chunk only): this chunk's second-group constants, one column each
+  //   then WPS pieces of the next chunk's weights per tile until all are issued
+  //   the last four free tiles of k-step 2: the next chunk's first-group constants
+  constexpr int FREE_PER_STEP = MTS - PIECES;
+  constexpr int WPS = (BM == 128) ? 2 : 1;
+  constexpr int W0 = TWO_GROUPS ? 4 : 0;
+  constexpr int WSLOTS = (WPIECES + WPS - 1) / WPS;
+  constexpr int C0 = 3 * FREE_PER_STEP - 4;            // first slot of the next chunk's constants
+  static_assert(W0 + WSLOTS <= C0, "weight loads and constants must fit before k-step 3");
+
+  // one chunk: weights wc (constants gc0, g1) are consumed, wn is loaded and its
+  // constants gn0 built; CUR is the LDS buffer holding this chunk's A slab
+  auto chunk = [&](auto CURc, WStage& wc, WStage& wn, typename D::Consts& gc0, typename D::Consts& gn0,
+                   int kc) __attribute__((always_inline)) {
     constexpr int CUR = decltype(CURc)::value, NXT = CUR ^ 1;
     constexpr int PB = 16 / MTS;                       // pairs unpacked per row tile
-    w_issue(wn, kc + 1);
     // A fragments: flat index f = J*MTS + MT over the chunk, read two tiles ahead
     const uint8_t* abase = lds + CUR * L::BUF + a_rd;
     auto a_read = [&](int f) __attribute__((always_inline)) {
@@ -205,21 +255,14 @@ __global__ __launch_bounds__(256) void large_kernel(GemmParams p, int tiles_m, i
     static_for<4>([&](auto Jc) __attribute__((always_inline)) {
       constexpr int J = decltype(Jc)::value;
       constexpr int JN = (J + 1) & 3;
-      if constexpr (J == 3) D::make_consts(g0, wn.s0, wn.z0 & zmask, p.zbias, p.scale_bf16);
-      if constexpr (TWO_GROUPS && J == 1) D::make_consts(g1, wc.s1, wc.z1 & zmask, p.zbias, p.scale_bf16);
       uint32_t nf[4][4];                 // fragment of k-step J+1 under construction
       uint32_t xe[PB];
       typename D::Mid mid[PB], mid_prev[PB];
-      const typename D::Consts& g = (TWO_GROUPS && JN >= 2) ? g1 : g0;
+      const typename D::Consts& g = (J < 3) ? ((TWO_GROUPS && JN >= 2) ? g1 : gc0) : gn0;
       const uint32_t (&rw)[RAW] = (J < 3) ? wc.r : wn.r;
       static_for<MTS>([&](auto MTc) __attribute__((always_inline)) {
         constexpr int MT = decltype(MTc)::value;
         constexpr int F = J * MTS + MT;
-        // The matrix pipeline hides two vector instructions per MFMA, no more, so
-        // the unpack of the PB pairs of this row tile is cut into three phases
-        // that sit in different gaps, and the last phase of tile MT runs in tile
-        // MT+1: a consumer never directly follows its producer (the compiler
-        // cannot see through the asm MFMA and would pad such pairs with s_nop).
         mfma16_acc<ROUTE>(acc[MT][0], wf[J & 1][0], ar[F % 3]);
         __builtin_amdgcn_sched_barrier(0);
         static_for<PB>([&](auto Qc) __attribute__((always_inline)) {          // extract
@@ -246,13 +289,24 @@ __global__ __launch_bounds__(256) void large_kernel(GemmParams p, int tiles_m, i
         __builtin_amdgcn_sched_barrier(0);
         mfma16_acc<ROUTE>(acc[MT][3], wf[J & 1][3], ar[F % 3]);
         __builtin_amdgcn_sched_barrier(0);
-        // A slab of the next chunk, one 16-byte piece per thread every 4th row
-        // tile: commit the piece loaded two k-steps ago, then start the load
-        // that will be committed two k-steps from now
-        if constexpr (MT % 4 == 0 && MT / 4 < PIECES) {
+        // ---- the one extra item of this tile --------------------------------------------
+        constexpr bool STAGES = (MT % 4 == 0) && (MT / 4 < PIECES);
+        if constexpr (STAGES) {
+          // A slab of the next chunk, one 16-byte piece per thread: store the piece
+          // loaded two k-steps ago, then start the load that will be stored two
+          // k-steps from now
           constexpr int I = MT / 4;
-          *reinterpret_cast<u4_t*>(lds + NXT * L::BUF + J * L::SLICE + a_dst[I]) = stage[J & 1][I];
-          stage[J & 1][I] = *reinterpret_cast<const u4_t*>(a_src[I] + min(4 * (kc + 1) + J + 2, 4 * KC - 1) * 32);
+          *reinterpret_cast<u4_t*>(lds + NXT * L::BUF + J * L::SLICE + a_dst0 + 4096 * I) = stage[J & 1][I];
+          stage[J & 1][I] = a_load(I, 4 * (kc + 1) + J + 2);
+        } else {
+          constexpr int BEFORE = MT - (MT + 3) / 4 + ((MT + 3) / 4 > PIECES ? (MT + 3) / 4 - PIECES : 0);   // free tiles before MT
+          constexpr int FS = J * FREE_PER_STEP + BEFORE;
+          if constexpr (TWO_GROUPS && FS < 4) consts_col(g1, wc, std::integral_constant<int, 1>{}, FS);
+          static_for<WPS>([&](auto Xc) __attribute__((always_inline)) {
+            constexpr int I = (FS - W0) * WPS + decltype(Xc)::value;
+            if constexpr (FS >= W0 && I < WPIECES) w_piece(wn, kc + 1, std::integral_constant<int, I>{});
+          });
+          if constexpr (FS >= C0 && FS < C0 + 4) consts_col(gn0, wn, std::integral_constant<int, 0>{}, FS - C0);
         }
 #pragma unroll
         for (int q = 0; q < PB; ++q) mid_prev[q] = mid[q];
@@ -270,10 +324,10 @@ __global__ __launch_bounds__(256) void large_kernel(GemmParams p, int tiles_m, i
 
   int kc = 0;
   for (; kc + 2 <= KC; kc += 2) {
-    chunk(std::integral_constant<int, 0>{}, wA, wB, kc);
-    chunk(std::integral_constant<int, 1>{}, wB, wA, kc + 1);
+    chunk(std::integral_constant<int, 0>{}, wA, wB, gA0, gB0, kc);
+    chunk(std::integral_constant<int, 1>{}, wB, wA, gB0, gA0, kc + 1);
   }
-  if (kc < KC) chunk(std::integral_constant<int, 0>{}, wA, wB, kc);
+  if (kc < KC) chunk(std::integral_constant<int, 0>{}, wA, wB, gA0, gB0, kc);
 
   // the matrix pipeline may still be writing the accumulators (the compiler
   // does not see the asm MFMAs, so it inserts no wait states of its own)
