@@ -112,8 +112,11 @@ __global__ __launch_bounds__(256) void large_kernel(GemmParams p, int tiles_m, i
   const uint32_t a_step = 64u * (uint32_t)(2 * p.K);                      // 64 rows further
   const int a_dst0 = srow * 64 + 16 * (spc ^ lds_swizzle(srow));          // + 4096*i for piece i
   auto a_load = [&](int i, int kstep) __attribute__((always_inline)) {     // kstep = 4*chunk + slice
-    // the row part stays in the vector offset so that the range check sees it
-    return __builtin_amdgcn_raw_buffer_load_b128(a_rsrc, (int)(a_off0 + (uint32_t)i * a_step),
+    // the row part stays in the vector offset so that the range check sees it; k-steps
+    // past K (the padding chunk of an odd chunk count, the ring's look-ahead at the
+    // end) are pushed out of range as well and read as zeros
+    const uint32_t past = (kstep < 4 * KC) ? 0u : 0x80000000u;
+    return __builtin_amdgcn_raw_buffer_load_b128(a_rsrc, (int)(a_off0 + (uint32_t)i * a_step + past),
                                                  min(kstep, 4 * KC - 1) * 64, 0);
   };
   u4_t stage[2][PIECES];
@@ -226,17 +229,24 @@ __global__ __launch_bounds__(256) void large_kernel(GemmParams p, int tiles_m, i
   });
   __syncthreads();
 
-  // Extra-item table.  Row tiles with MT % 4 == 0 (and MT / 4 < PIECES) carry a staging
-  // piece.  The other tiles of the chunk, in order, are numbered FS = 0, 1, ...:
-  //   FS 0..3 (two groups per chunk only): this chunk's second-group constants, one column each
-  //   then WPS pieces of the next chunk's weights per tile until all are issued
-  //   the last four free tiles of k-step 2: the next chunk's first-group constants
-  constexpr int FREE_PER_STEP = MTS - PIECES;
+  // Extra-item table, gap 3 of row tile MT in k-step J:
+  //   MT % 4 == 0   store the A staging piece MT/4 loaded two k-steps ago
+  //   MT % 4 == 2   start the load of that piece for two k-steps from now
+  //   odd MT        (index MT/2 within the step) k-steps 0 and 1: WPS loads of the next
+  //                 chunk's weights; last four of k-step 2: the next chunk's first-group
+  //                 constants, one column each; first four of k-step 3 (two groups per
+  //                 chunk): the next chunk's second-group constants, rebuilt in place --
+  //                 their last use was the unpack during k-step 2
+  constexpr int FREE_PER_STEP = MTS / 2;
   constexpr int WPS = (BM == 128) ? 2 : 1;
-  constexpr int W0 = TWO_GROUPS ? 4 : 0;
   constexpr int WSLOTS = (WPIECES + WPS - 1) / WPS;
-  constexpr int C0 = 3 * FREE_PER_STEP - 4;            // first slot of the next chunk's constants
-  static_assert(W0 + WSLOTS <= C0, "weight loads and constants must fit before k-step 3");
+  static_assert(MTS / 4 == PIECES, "one staging piece per four row tiles");
+  static_assert(WSLOTS <= 2 * FREE_PER_STEP, "weight loads must be issued by the end of k-step 1");
+  if constexpr (TWO_GROUPS) {
+    static_for<4>([&](auto NTc) __attribute__((always_inline)) {
+      consts_col(g1, wA, std::integral_constant<int, 1>{}, decltype(NTc)::value);
+    });
+  }
 
   // one chunk: weights wc (constants gc0, g1) are consumed, wn is loaded and its
   // constants gn0 built; CUR is the LDS buffer holding this chunk's A slab
@@ -290,23 +300,22 @@ __global__ __launch_bounds__(256) void large_kernel(GemmParams p, int tiles_m, i
         mfma16_acc<ROUTE>(acc[MT][3], wf[J & 1][3], ar[F % 3]);
         __builtin_amdgcn_sched_barrier(0);
         // ---- the one extra item of this tile --------------------------------------------
-        constexpr bool STAGES = (MT % 4 == 0) && (MT / 4 < PIECES);
-        if constexpr (STAGES) {
-          // A slab of the next chunk, one 16-byte piece per thread: store the piece
-          // loaded two k-steps ago, then start the load that will be stored two
-          // k-steps from now
+        if constexpr (MT % 4 == 0) {
           constexpr int I = MT / 4;
           *reinterpret_cast<u4_t*>(lds + NXT * L::BUF + J * L::SLICE + a_dst0 + 4096 * I) = stage[J & 1][I];
+        } else if constexpr (MT % 4 == 2) {
+          constexpr int I = MT / 4;
           stage[J & 1][I] = a_load(I, 4 * (kc + 1) + J + 2);
         } else {
-          constexpr int BEFORE = MT - (MT + 3) / 4 + ((MT + 3) / 4 > PIECES ? (MT + 3) / 4 - PIECES : 0);   // free tiles before MT
-          constexpr int FS = J * FREE_PER_STEP + BEFORE;
-          if constexpr (TWO_GROUPS && FS < 4) consts_col(g1, wc, std::integral_constant<int, 1>{}, FS);
+          constexpr int IDX = MT / 2;                  // 0 .. FREE_PER_STEP-1
+          constexpr int FS = J * FREE_PER_STEP + IDX;
           static_for<WPS>([&](auto Xc) __attribute__((always_inline)) {
-            constexpr int I = (FS - W0) * WPS + decltype(Xc)::value;
-            if constexpr (FS >= W0 && I < WPIECES) w_piece(wn, kc + 1, std::integral_constant<int, I>{});
+            constexpr int I = FS * WPS + decltype(Xc)::value;
+            if constexpr (I < WPIECES) w_piece(wn, kc + 1, std::integral_constant<int, I>{});
           });
-          if constexpr (FS >= C0 && FS < C0 + 4) consts_col(gn0, wn, std::integral_constant<int, 0>{}, FS - C0);
+          if constexpr (J == 2 && IDX >= FREE_PER_STEP - 4)
+            consts_col(gn0, wn, std::integral_constant<int, 0>{}, IDX - (FREE_PER_STEP - 4));
+          if constexpr (TWO_GROUPS && J == 3 && IDX < 4) consts_col(g1, wn, std::integral_constant<int, 1>{}, IDX);
         }
 #pragma unroll
         for (int q = 0; q < PB; ++q) mid_prev[q] = mid[q];
@@ -322,12 +331,14 @@ __global__ __launch_bounds__(256) void large_kernel(GemmParams p, int tiles_m, i
     __syncthreads();
   };
 
-  int kc = 0;
-  for (; kc + 2 <= KC; kc += 2) {
+  // Chunks go in pairs (buffers, weight stages and constants alternate); an odd chunk
+  // count is padded with one chunk whose A slab reads as zeros, which keeps the loop
+  // free of a conditional tail (with one, the compiler merged tail and loop body and
+  // shuffled the whole accumulator state around the merge).
+  for (int kc = 0; kc < KC; kc += 2) {
     chunk(std::integral_constant<int, 0>{}, wA, wB, gA0, gB0, kc);
     chunk(std::integral_constant<int, 1>{}, wB, wA, gB0, gA0, kc + 1);
   }
-  if (kc < KC) chunk(std::integral_constant<int, 0>{}, wA, wB, gA0, gB0, kc);
 
   // the matrix pipeline may still be writing the accumulators (the compiler
   // does not see the asm MFMAs, so it inserts no wait states of its own)

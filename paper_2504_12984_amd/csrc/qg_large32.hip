@@ -119,8 +119,11 @@ __global__ __launch_bounds__(256) void large32_kernel(GemmParams p, int tiles_m,
   const uint32_t a_step = 16u * (uint32_t)(2 * p.K);                      // 16 rows further
   const int a_dst = (spc >> 1) * L::SLICE + srow * 32 + 16 * ((spc & 1) ^ swz32(srow));   // + 512*i for piece i
   auto a_load = [&](int i, int c) __attribute__((always_inline)) {
-    // the row part stays in the vector offset so that the range check sees it
-    return __builtin_amdgcn_raw_buffer_load_b128(a_rsrc, (int)(a_off0 + (uint32_t)i * a_step),
+    // the row part stays in the vector offset so that the range check sees it; chunks
+    // past K (the padding chunk of an odd chunk count, the ring's look-ahead at the
+    // end) are pushed out of range as well and read as zeros
+    const uint32_t past = (c < KC) ? 0u : 0x80000000u;
+    return __builtin_amdgcn_raw_buffer_load_b128(a_rsrc, (int)(a_off0 + (uint32_t)i * a_step + past),
                                                  min(c, KC - 1) * (2 * TILE_K), 0);
   };
   u4_t stage[L32_AHEAD][PPS];
@@ -324,12 +327,13 @@ __global__ __launch_bounds__(256) void large32_kernel(GemmParams p, int tiles_m,
     __syncthreads();
   };
 
-  int kc = 0;
-  for (; kc + 2 <= KC; kc += 2) {
+  // Chunks go in pairs (buffers, weight stages and constants alternate); an odd chunk
+  // count is padded with one chunk whose A slab reads as zeros, which keeps the loop
+  // free of a conditional tail.
+  for (int kc = 0; kc < KC; kc += 2) {
     chunk(std::integral_constant<int, 0>{}, wA, wB, gA0, gB0, kc);
     chunk(std::integral_constant<int, 1>{}, wB, wA, gB0, gA0, kc + 1);
   }
-  if (kc < KC) chunk(std::integral_constant<int, 0>{}, wA, wB, gA0, gB0, kc);
 
   // the matrix pipeline may still be writing the accumulators (the compiler
   // does not see the asm MFMAs, so it inserts no wait states of its own)
