@@ -31,7 +31,7 @@ MFMA_PEAK_TFLOPS = 2500.0      # dense fp16/bf16
 # HBM bytes per launch of the dominant kernel from the rocprofv3 FETCH_SIZE / WRITE_SIZE
 # counter runs of this same command, scaled by what the counters read for a plain copy of
 # known size (profiles/decode_kernel_cfg2_w3a16.txt).  Only workloads that were measured.
-MEASURED_TRAFFIC_BYTES = {"cfg2": 24.69e6}
+MEASURED_TRAFFIC_BYTES = {"cfg2": 24.63e6}
 
 
 def parse():
