@@ -118,15 +118,18 @@ QG_API int qdequant(const void* packed_W, const void* scales, const uint8_t* zer
 
 /* C[M,N] (row-major, `act`) = A[M,K] (row-major, `act`) . dequant(W).
  * Arguments as for qdequant; M >= 1 is arbitrary, C is overwritten.
- * Path choice (by M) is internal: M <= 64 streams the weights once through
+ * Path choice (by shape) is internal: M <= 64 streams the weights once through
  * a split-K kernel (1, 2 or 4 tiles of 16 rows per wavefront); larger M uses
- * the LDS-staged tiled kernel. */
+ * the LDS-staged tiled kernel, except 64 < M <= 256 with so few output tiles
+ * that most CUs would idle, which runs the streaming kernel over blocks of 64
+ * rows (several launches on `stream`). */
 QG_API int qgemm(const void* A, const void* packed_W, const void* scales, const uint8_t* zeros,
           qg_wtype t, int layout, int act, int scale_dtype, int64_t group,
           int64_t M, int64_t N, int64_t K, void* C, void* stream);
 
 /* Optional: path/tuning override for experiments (0 = automatic).  Returns the
- * previous value.  knob 0: forced path (1 = small-M kernel, 2 = tiled kernel);
+ * previous value.  knob 0: forced path (1 = streaming kernel, 2 = tiled kernel, 3 =
+ * streaming kernel over blocks of 64 rows);
  * knob 1: forced split-K factor of the small-M kernels; knob 2: forced row-tile
  * (128 / 256) of the tiled kernel; knob 3: pipeline variant of the M <= 64
  * kernel (10*row tiles + 0/1/2 for 8/4/16 wavefronts per strip: 10, 11, 12,

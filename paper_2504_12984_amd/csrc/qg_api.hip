@@ -110,6 +110,42 @@ static int check_common(qg_wtype t, int layout, int act, int scale_dtype, int64_
   return QG_OK;
 }
 
+// One launch of the streaming kernel (M <= 64): wavefront arrangement and split-K by shape.
+static int launch_streaming(GemmParams& p, int wt, int route, hipStream_t st) {
+  const int M = p.M;
+  const int KC = p.K / TILE_K, NCH = p.N / TILE_N;
+  const int mt = M <= 16 ? 1 : (M <= 32 ? 2 : 4);
+  // 16 wavefronts per strip for one row tile and short K (two chunks per wavefront,
+  // every load of the strip in flight at once), 4 wavefronts otherwise
+  int variant = 10 * mt + ((mt == 1 && KC <= 32) ? 2 : 1);
+  // long K and enough strips to fill the chip with pairs of them: 8 wavefronts on 2
+  // adjacent strips, 4 along K each -- wavefronts at the same K position share
+  // their A rows in the vector cache (measured 2-4 % shorter at K = 8192, N = 28672;
+  // with 2 or 4 row tiles: 2 strips x 2 wavefronts along K, 10-15 % shorter)
+  if (KC > 32 && NCH % 2 == 0 && NCH / 2 >= 192) variant = (mt == 1) ? 14 : (mt == 2) ? 26 : 46;
+  if (g_knob[3] > 0) variant = g_knob[3];
+  const int waves = kDecodeWaves[wt](variant);
+  // Split K over workgroups only when the column strips alone cannot fill the
+  // 256 CUs, and never below 4 chunks per wavefront.
+  int splitk = g_knob[1];
+  if (splitk <= 0) {
+    splitk = 1;
+    while (NCH * splitk < 256 && KC / (splitk * 2) >= 4 * waves) splitk *= 2;
+  }
+  if (splitk > KC) splitk = KC;
+  int cps = (KC + splitk - 1) / splitk;
+  splitk = (KC + cps - 1) / cps;
+  p.splitk = splitk; p.chunks_per_split = cps;
+  if (splitk > 1) {
+    Workspace* w = nullptr;
+    size_t pbytes = (size_t)splitk * NCH * (size_t)(mt * 16 * TILE_N) * sizeof(float);
+    int rc = get_workspace(pbytes, (size_t)NCH, st, &w);
+    if (rc != QG_OK) return rc;
+    p.ws = w->partial; p.tickets = w->tickets;
+  }
+  return kDecode[wt](p, route, variant, st);
+}
+
 }  // namespace qg
 
 using namespace qg;
@@ -212,41 +248,27 @@ int qgemm(const void* A, const void* packed_W, const void* scales, const uint8_t
   }
 
   int path = g_knob[0];
-  if (path == 0) path = (M <= 64) ? 1 : 2;
+  if (path == 0) {
+    path = (M <= 64) ? 1 : 2;
+    // Few output tiles (narrow N) and a moderate M leave most CUs without a tile of the
+    // tiled kernel (M = 128 on N = 8192: 32 workgroups); the streaming kernel run over
+    // blocks of 64 rows fills the chip and is about twice as fast there (measured:
+    // 55 us against 114 us at K = N = 8192, M = 128; 106 against 112 at M = 256).
+    const int64_t tiles128 = ((M + 127) / 128) * ((N + 255) / 256);
+    if (M > 64 && M <= 256 && tiles128 <= 64) path = 3;
+  }
   if (path == 1 && M > 64) return QG_EINVAL;
 
-  if (path == 1) {
-    const int KC = (int)(K / TILE_K), NCH = (int)(N / TILE_N);
-    const int mt = M <= 16 ? 1 : (M <= 32 ? 2 : 4);
-    // 16 wavefronts per strip for one row tile and short K (two chunks per wavefront,
-    // every load of the strip in flight at once), 4 wavefronts otherwise
-    int variant = 10 * mt + ((mt == 1 && KC <= 32) ? 2 : 1);
-    // long K and enough strips to fill the chip with pairs of them: 8 wavefronts on 2
-    // adjacent strips, 4 along K each -- wavefronts at the same K position share
-    // their A rows in the vector cache (measured 5-13 % shorter at K = 8192, N = 28672;
-    // with 2 or 4 row tiles: 2 strips x 2 wavefronts along K)
-    if (KC > 32 && NCH % 2 == 0 && NCH / 2 >= 192) variant = (mt == 1) ? 14 : (mt == 2) ? 26 : 46;
-    if (g_knob[3] > 0) variant = g_knob[3];
-    const int waves = kDecodeWaves[wt](variant);
-    // Split K over workgroups only when the column strips alone cannot fill the
-    // 256 CUs, and never below 4 chunks per wavefront.
-    int splitk = g_knob[1];
-    if (splitk <= 0) {
-      splitk = 1;
-      while (NCH * splitk < 256 && KC / (splitk * 2) >= 4 * waves) splitk *= 2;
-    }
-    if (splitk > KC) splitk = KC;
-    int cps = (KC + splitk - 1) / splitk;
-    splitk = (KC + cps - 1) / cps;
-    p.splitk = splitk; p.chunks_per_split = cps;
-    if (splitk > 1) {
-      Workspace* w = nullptr;
-      size_t pbytes = (size_t)splitk * NCH * (size_t)(mt * 16 * TILE_N) * sizeof(float);
-      rc = get_workspace(pbytes, (size_t)NCH, st, &w);
+  if (path == 1 || path == 3) {
+    for (int64_t r0 = 0; r0 < M; r0 += 64) {
+      GemmParams q = p;
+      q.A = p.A + r0 * K;
+      q.C = p.C + r0 * N;
+      q.M = (int)((M - r0 < 64) ? (M - r0) : 64);
+      rc = launch_streaming(q, wt, route, st);
       if (rc != QG_OK) return rc;
-      p.ws = w->partial; p.tickets = w->tickets;
     }
-    return kDecode[wt](p, route, variant, st);
+    return QG_OK;
   }
   return kLarge[wt](p, route, g_knob[2], st);
 }

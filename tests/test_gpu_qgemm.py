@@ -144,6 +144,7 @@ def test_tiled_path_ragged_shapes(M, K, N, bm):
     case = WL.Case(f"tiled_{M}_{K}_{N}_{bm}", M, K, N, U, 5, group=64, act="bf16", scale_dtype="bf16",
                    zero=16, seed=8700 + M)
     P = Prepared(case)
+    B.qg_set_knob(0, 2)                 # the tiled kernel, whatever the automatic choice would be
     B.qg_set_knob(2, bm)
     assert_c_close(P.gpu_c(), P.oracle_c(), case.name)
 
@@ -152,9 +153,11 @@ def test_tiled_path_ragged_shapes(M, K, N, bm):
 @pytest.mark.parametrize("kind,bits,e,m", [(U, 1, 0, 0), (I, 2, 0, 0), (U, 3, 0, 0), (I, 4, 0, 0), (U, 6, 0, 0),
                                            (I, 7, 0, 0), (U, 8, 0, 0), (F, 4, 2, 1), (F, 6, 3, 2), (F, 8, 4, 3)])
 def test_tiled_path_weight_types(kind, bits, e, m, act):
+    from paper_2504_12984_amd import binding as B
     case = WL.Case(f"tiled_t{kind}_{bits}_{act}", 130, 640, 192, kind, bits, e, m, group=128, act=act,
                    scale_dtype="f16", zero=(1 << (bits - 1)) if kind == U else None, seed=8800 + bits)
     P = Prepared(case)
+    B.qg_set_knob(0, 2)
     assert_c_close(P.gpu_c(), P.oracle_c(), case.name)
 
 
@@ -169,6 +172,21 @@ def test_tiled_path_fp16_two_groups_per_chunk(bits, bm):
     B.qg_set_knob(0, 2)
     B.qg_set_knob(2, bm)
     assert_c_close(P.gpu_c(), P.oracle_c(), case.name)
+
+
+@pytest.mark.parametrize("M", [65, 100, 128, 129, 192])
+def test_moderate_m_on_few_tiles_runs_the_streaming_kernel_in_row_blocks(M):
+    # automatic choice for 64 < M <= 256 with few output tiles; also forced on a ragged last block
+    from paper_2504_12984_amd import binding as B
+    case = WL.Case(f"blocks_{M}", M, 1152, 320, I, 5, group=128, act="bf16", scale_dtype="f16", zero=None,
+                   seed=8870 + M)
+    P = Prepared(case)
+    ref = P.oracle_c()
+    assert_c_close(P.gpu_c(), ref, case.name + " auto")
+    B.qg_set_knob(0, 3)
+    assert_c_close(P.gpu_c(), ref, case.name + " forced")
+    B.qg_set_knob(0, 2)
+    assert_c_close(P.gpu_c(), ref, case.name + " tiled")
 
 
 def test_both_paths_agree_with_the_oracle_on_the_same_small_problem():
