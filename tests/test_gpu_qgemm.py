@@ -210,3 +210,37 @@ def test_tiled_path_one_hot_rows_bit_exact():
     _, wbits = P.oracle_w()
     B.qg_set_knob(0, 2)
     assert np.array_equal(bits_of(P.gpu_c()), wbits)
+
+
+# ------------------------------------------------------------------ binding extras
+def test_bound_call_gives_the_same_bits_as_the_plain_call_and_checks_its_arguments():
+    from paper_2504_12984_amd import binding as B
+    case = WL.Case("bound", 7, 640, 192, U, 4, group=128, zero=8, seed=9100)
+    P = Prepared(case)
+    want = P.gpu_c()
+    out = torch.empty_like(want)
+    call = B.BoundQgemm(P.d_A, P.d_packed, P.d_scales, P.d_zeros, P.wtype, case.group, case.N, out)
+    for _ in range(3):                               # repeated calls reuse the marshalled arguments
+        got = call()
+        assert got is out
+        assert np.array_equal(bits_of(got), bits_of(want))
+    with pytest.raises(ValueError):                  # output of the wrong shape
+        B.BoundQgemm(P.d_A, P.d_packed, P.d_scales, P.d_zeros, P.wtype, case.group, case.N, out[:, :64])
+    with pytest.raises(ValueError):                  # scales of the wrong shape
+        B.BoundQgemm(P.d_A, P.d_packed, P.d_scales[:2], P.d_zeros, P.wtype, case.group, case.N, out)
+
+
+def test_measurement_probes_run_and_report_their_flops():
+    from paper_2504_12984_amd import binding as B
+    sink = torch.zeros(1024, dtype=torch.float32, device="cuda")
+    buf = torch.ones(1 << 22, dtype=torch.uint8, device="cuda")
+    probe = B.qg_probe_stream_read(buf, sink)
+    probe()
+    flops = B.qg_probe_mfma(True, True, 10, 1, sink)
+    assert flops == 8.0 * 32768.0 * 10 * 4.0 * 256.0
+    flops2 = B.qg_probe_mfma(False, False, 5, 2, sink)
+    assert flops2 == 8.0 * 32768.0 * 5 * 4.0 * 512.0
+    torch.cuda.synchronize()
+    assert float(sink.abs().sum()) == 0.0            # the probes never write their sink
+    with pytest.raises(B.QgError):
+        B.qg_probe_mfma(True, True, 0, 1, sink)
