@@ -69,7 +69,7 @@ struct LargeLds {
 };
 
 template <int WT, int ROUTE, bool TWO_GROUPS, int BM>
-__global__ __launch_bounds__(256) void large_kernel(GemmParams p, int tiles_m, int tiles_n, int per_xcd) {
+__global__ __launch_bounds__(256) void large_kernel(GemmParams p, int tiles_m, int tiles_n, int per_xcd, int tn0) {
   typedef Decoder<WT, ROUTE> D;
   constexpr int BITS = D::BITS, RAW = D::RAW;
   constexpr int MTS = BM / 16;                 // 16-row MFMA tiles per workgroup
@@ -85,7 +85,7 @@ __global__ __launch_bounds__(256) void large_kernel(GemmParams p, int tiles_m, i
   const int first_m = (logical / panel) * LARGE_GROUP_M;
   const int gsize = min(tiles_m - first_m, LARGE_GROUP_M);
   const int tm = first_m + (logical % panel) % gsize;
-  const int tn = (logical % panel) / gsize;
+  const int tn = tn0 + (logical % panel) / gsize;       // tn0: first column tile of this launch
 
   const int tid = threadIdx.x, l = tid & 63;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, kept in a scalar register
@@ -367,10 +367,10 @@ __global__ __launch_bounds__(256) void large_kernel(GemmParams p, int tiles_m, i
 #define QG_CAT2(a, b) a##b
 #define QG_CAT(a, b) QG_CAT2(a, b)
 
+// One launch over the column tiles [tn0, tn0 + tiles_n) and all row tiles of height BM.
 template <int ROUTE, bool TG, int BM>
-static int launch_bm(const GemmParams& p, hipStream_t st) {
+static int launch_bm(const GemmParams& p, hipStream_t st, int tn0, int tiles_n) {
   const int tiles_m = (p.M + BM - 1) / BM;
-  const int tiles_n = (p.N + LARGE_BN - 1) / LARGE_BN;
   const int total = tiles_m * tiles_n;
   const int per_xcd = (total + 7) / 8;
   const size_t lds_bytes = 2 * LargeLds<BM>::BUF;
@@ -382,28 +382,42 @@ static int launch_bm(const GemmParams& p, hipStream_t st) {
       return QG_EHIP;
     attr_done = true;
   }
-  hipLaunchKernelGGL(kern, dim3((unsigned)(8 * per_xcd)), dim3(256), lds_bytes, st, p, tiles_m, tiles_n, per_xcd);
+  hipLaunchKernelGGL(kern, dim3((unsigned)(8 * per_xcd)), dim3(256), lds_bytes, st, p, tiles_m, tiles_n, per_xcd, tn0);
   return hipGetLastError() == hipSuccess ? QG_OK : QG_EHIP;
 }
 
 template <int ROUTE>
-static int launch_route(const GemmParams& p, int bm, hipStream_t st) {
-  if (bm == 0) {
-    // Row-tile height by a small cost model: workgroups run in rounds of 256 (one per
-    // CU), a tile costs its rows plus about 64 rows' worth of unpack and start-up.
-    // 128 rows win when they fill a round that 256 rows leave half empty (M <= 256 on
-    // 28672 columns, M = 384 on 57344: measured 20-30 % shorter), 256 rows otherwise.
-    const long tiles_n = (p.N + LARGE_BN - 1) / LARGE_BN;
-    auto cost = [&](int rows) {
-      const long tiles = ((p.M + rows - 1) / rows) * tiles_n;
-      return ((tiles + 255) / 256) * (rows + 64);
-    };
-    bm = (p.M <= 128 || cost(128) < cost(256)) ? 128 : 256;
-  }
+static int launch_rows(const GemmParams& p, int bm, hipStream_t st, int tn0, int tiles_n) {
   const bool tg = (p.group == 64);
-  if (bm == 128) return tg ? launch_bm<ROUTE, true, 128>(p, st) : launch_bm<ROUTE, false, 128>(p, st);
-  if (bm == 256) return tg ? launch_bm<ROUTE, true, 256>(p, st) : launch_bm<ROUTE, false, 256>(p, st);
+  if (bm == 128) return tg ? launch_bm<ROUTE, true, 128>(p, st, tn0, tiles_n) : launch_bm<ROUTE, false, 128>(p, st, tn0, tiles_n);
+  if (bm == 256) return tg ? launch_bm<ROUTE, true, 256>(p, st, tn0, tiles_n) : launch_bm<ROUTE, false, 256>(p, st, tn0, tiles_n);
   return QG_EINVAL;
+}
+
+template <int ROUTE>
+static int launch_route(const GemmParams& p, int bm, hipStream_t st) {
+  const int tiles_n = (p.N + LARGE_BN - 1) / LARGE_BN;
+  if (bm != 0) return launch_rows<ROUTE>(p, bm, st, 0, tiles_n);
+  // Row-tile height by a small cost model: workgroups run in rounds of 256 (one per
+  // CU), a tile costs its rows plus about 64 rows' worth of unpack and start-up.
+  // 128 rows win when they fill a round that 256 rows leave half empty (M <= 256 on
+  // 28672 columns, M = 384 on 57344: measured 20-30 % shorter), 256 rows otherwise.
+  auto cost = [&](int rows, long cols) {
+    const long tiles = ((p.M + rows - 1) / rows) * cols;
+    return ((tiles + 255) / 256) * (rows + 64);
+  };
+  if (p.M <= 128) return launch_rows<ROUTE>(p, 128, st, 0, tiles_n);
+  // Whole rounds of 256-row tiles first; the column tiles that would start a partly
+  // filled last round go into a second launch with whichever height is cheaper for
+  // them (M = 1024 on 57344 columns: 3.5 rounds become 3 + one round of 128-row tiles).
+  const int tm256 = (p.M + 255) / 256;
+  const long rounds = ((long)tm256 * tiles_n) / 256;
+  const int tn_full = (int)((rounds * 256) / tm256 < tiles_n ? (rounds * 256) / tm256 : tiles_n);
+  if (tn_full == 0) return launch_rows<ROUTE>(p, cost(128, tiles_n) < cost(256, tiles_n) ? 128 : 256, st, 0, tiles_n);
+  int rc = launch_rows<ROUTE>(p, 256, st, 0, tn_full);
+  if (rc != QG_OK || tn_full == tiles_n) return rc;
+  const int rest = tiles_n - tn_full;
+  return launch_rows<ROUTE>(p, cost(128, rest) < cost(256, rest) ? 128 : 256, st, tn_full, rest);
 }
 
 int QG_CAT(large_launch_wt, QG_WT)(const GemmParams& p, int route, int bm, hipStream_t st) {

@@ -212,6 +212,19 @@ def test_tiled_path_one_hot_rows_bit_exact():
     assert np.array_equal(bits_of(P.gpu_c()), wbits)
 
 
+@pytest.mark.parametrize("layout", [0, 1])
+def test_tiled_path_split_into_whole_rounds_plus_remainder(layout):
+    # 2 x 140 tiles of 256 rows: one whole round of 256 workgroups (128 column tiles) and a
+    # second launch for the last 12 column tiles; columns from both parts are checked
+    case = WL.Case(f"rounds_{layout}", 512, 256, 35840, U, 4, group=128, act="bf16", scale_dtype="bf16",
+                   zero=8, seed=9050)
+    P = Prepared(case)
+    cols = np.concatenate([np.arange(0, 64), np.arange(32704, 32832), np.arange(35776, 35840),
+                           np.random.default_rng(5).integers(0, 35840, size=64)])
+    got = P.gpu_c(layout=layout)
+    assert_c_close(got[:, torch.from_numpy(cols).cuda()], P.oracle_c(cols=cols), case.name)
+
+
 # ------------------------------------------------------------------ binding extras
 def test_bound_call_gives_the_same_bits_as_the_plain_call_and_checks_its_arguments():
     from paper_2504_12984_amd import binding as B
