@@ -47,17 +47,27 @@ __global__ __launch_bounds__(256) void dequant_kernel(DequantParams p) {
     }
     typename D::Consts gc;
     D::make_consts(gc, sraw, zraw, p.zbias, p.scale_bf16);
+    // all of the lane's columns for this k-step, then one store per row: the lane's
+    // NT adjacent columns are 2*NT contiguous bytes, and the 16 (32) lanes of a k-block
+    // together write 128 contiguous bytes of the row
+    uint32_t o[L::NT][4];
     static_for<L::NT>([&](auto NTc) __attribute__((always_inline)) {
       constexpr int NT = decltype(NTc)::value;
-      uint32_t o[4];
-      D::template frag<J, NT>(r, gc, u, o);
-#pragma unroll
-      for (int v = 0; v < 4; ++v) {
-        const int k = TILE_K * kc + L::pair_k(l, L::t0(J, NT) + v);
-        p.out[(int64_t)k * p.N + n0 + NT] = (uint16_t)(o[v] & 0xffffu);
-        p.out[(int64_t)(k + 1) * p.N + n0 + NT] = (uint16_t)(o[v] >> 16);
-      }
+      D::template frag<J, NT>(r, gc, u, o[NT]);
     });
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      const int k = TILE_K * kc + L::pair_k(l, L::t0(J, 0) + v);
+      uint16_t* row0 = p.out + (int64_t)k * p.N + n0;          // the pair's lo code: row k
+      uint16_t* row1 = row0 + p.N;                              // its hi code: row k + 1
+      if constexpr (L::NT == 4) {
+        *reinterpret_cast<uint2*>(row0) = make_uint2((o[0][v] & 0xffffu) | (o[1][v] << 16), (o[2][v] & 0xffffu) | (o[3][v] << 16));
+        *reinterpret_cast<uint2*>(row1) = make_uint2((o[0][v] >> 16) | (o[1][v] & 0xffff0000u), (o[2][v] >> 16) | (o[3][v] & 0xffff0000u));
+      } else {
+        *reinterpret_cast<uint32_t*>(row0) = (o[0][v] & 0xffffu) | (o[1][v] << 16);
+        *reinterpret_cast<uint32_t*>(row1) = (o[0][v] >> 16) | (o[1][v] & 0xffff0000u);
+      }
+    }
   });
 }
 
