@@ -123,6 +123,9 @@ static int launch_streaming(GemmParams& p, int wt, int route, hipStream_t st) {
   // their A rows in the vector cache (measured 2-4 % shorter at K = 8192, N = 28672;
   // with 2 or 4 row tiles: 2 strips x 2 wavefronts along K, 10-15 % shorter)
   if (KC > 32 && NCH % 2 == 0 && NCH / 2 >= 192) variant = (mt == 1) ? 14 : (mt == 2) ? 26 : 46;
+  // up to 6 bits per code a wavefront needs few enough registers for 16 of them per
+  // workgroup (2 strips x 8 along K): twice the wavefronts in flight, 1-6 % shorter
+  if (variant == 14 && wt_bits(wt) <= 6 && p.group != 64) variant = 15;
   if (g_knob[3] > 0) variant = g_knob[3];
   const int waves = kDecodeWaves[wt](variant);
   // Split K over workgroups only when the column strips alone cannot fill the
