@@ -126,14 +126,19 @@ static int launch_streaming(GemmParams& p, int wt, int route, hipStream_t st) {
   // up to 6 bits per code a wavefront needs few enough registers for 16 of them per
   // workgroup (2 strips x 8 along K): twice the wavefronts in flight, 1-6 % shorter
   if (variant == 14 && wt_bits(wt) <= 6 && p.group != 64) variant = 15;
+  // long K but too few strips to fill the chip (K is split over workgroups below): more
+  // wavefronts per strip for narrow codes -- 16 up to 4 bits, 8 up to 6 (measured on
+  // K = N = 8192: 11 % and 7 % shorter at 4 bits, no gain at 8)
+  if (variant == 11 && KC > 32 && NCH < 256) variant = wt_bits(wt) <= 4 ? 12 : (wt_bits(wt) <= 6 ? 10 : 11);
   if (g_knob[3] > 0) variant = g_knob[3];
   const int waves = kDecodeWaves[wt](variant);
   // Split K over workgroups only when the column strips alone cannot fill the
-  // 256 CUs, and never below 4 chunks per wavefront.
+  // 256 CUs, and never below 4 chunks per wavefront (2 with 16 wavefronts per strip).
   int splitk = g_knob[1];
   if (splitk <= 0) {
     splitk = 1;
-    while (NCH * splitk < 256 && KC / (splitk * 2) >= 4 * waves) splitk *= 2;
+    const int min_chunks = (waves >= 16) ? 2 : 4;      // per wavefront
+    while (NCH * splitk < 256 && KC / (splitk * 2) >= min_chunks * waves) splitk *= 2;
   }
   if (splitk > KC) splitk = KC;
   int cps = (KC + splitk - 1) / splitk;
