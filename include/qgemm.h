@@ -122,7 +122,8 @@ QG_API int qdequant(const void* packed_W, const void* scales, const uint8_t* zer
  * a split-K kernel (1, 2 or 4 tiles of 16 rows per wavefront); larger M uses
  * the LDS-staged tiled kernel, except 64 < M <= 256 with so few output tiles
  * that most CUs would idle, which runs the streaming kernel over blocks of 64
- * rows (several launches on `stream`). */
+ * rows (several launches on `stream`).  The tiled kernel needs M*K*2, the packed
+ * weight and the scale array each below 4 GiB (QG_EUNSUPPORTED otherwise). */
 QG_API int qgemm(const void* A, const void* packed_W, const void* scales, const uint8_t* zeros,
           qg_wtype t, int layout, int act, int scale_dtype, int64_t group,
           int64_t M, int64_t N, int64_t K, void* C, void* stream);

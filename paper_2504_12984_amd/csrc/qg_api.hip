@@ -246,12 +246,13 @@ int qgemm(const void* A, const void* packed_W, const void* scales, const uint8_t
   p.splitk = 1; p.chunks_per_split = (int)(K / TILE_K);
   if (!set_group_index(p)) return QG_EUNSUPPORTED;
 
-  if (layout == QG_LAYOUT_TILE128x64_R32) {
-    // one kernel for every M; it addresses A, the packed weight and the scales through
-    // buffer resources with 32-bit byte offsets
-    if ((uint64_t)M * (uint64_t)K * 2u >= (1ull << 32)) return QG_EUNSUPPORTED;
-    if ((uint64_t)K * (uint64_t)N / 8u * (uint64_t)t.bits >= (1ull << 32)) return QG_EUNSUPPORTED;
-    if ((uint64_t)(K / group) * (uint64_t)N * 2u >= (1ull << 32)) return QG_EUNSUPPORTED;
+  // The tiled kernels address A, the packed weight and the scales through buffer
+  // resources with 32-bit byte offsets.
+  const bool fits32 = (uint64_t)M * (uint64_t)K * 2u < (1ull << 32) &&
+                      (uint64_t)K * (uint64_t)N / 8u * (uint64_t)t.bits < (1ull << 32) &&
+                      (uint64_t)(K / group) * (uint64_t)N * 2u < (1ull << 32);
+  if (layout == QG_LAYOUT_TILE128x64_R32) {      // one kernel for every M
+    if (!fits32) return QG_EUNSUPPORTED;
     return kLarge32[wt](p, route, g_knob[2], st);
   }
 
@@ -278,6 +279,7 @@ int qgemm(const void* A, const void* packed_W, const void* scales, const uint8_t
     }
     return QG_OK;
   }
+  if (!fits32) return QG_EUNSUPPORTED;
   return kLarge[wt](p, route, g_knob[2], st);
 }
 
