@@ -11,7 +11,7 @@ more copies than the last-level cache holds has the same effect without a
 second kernel inside the timed region).  Inputs are seeded and synthetic and
 already in HBM when the timed region starts.  Prints one JSON line.
 
-Other workloads (for the tables in the design doc): cfg1, cfg2_M<m>, cfg3_i<k>[_M<m>],
+Other workloads (for the result tables): cfg1, cfg2_M<m>, cfg3_i<k>[_M<m>],
 cfg4_f<bits>_M<m>, cfg5_u<k>_M<m> [--layout 1], sweep_{u,i,f}<bits>.
 """
 from __future__ import annotations
