@@ -72,10 +72,10 @@ def test_split_k_factors_agree_with_oracle_and_leave_counters_clean(splitk):
 
 
 @pytest.mark.parametrize("splitk", [1, 3])
-@pytest.mark.parametrize("variant", [10, 11, 12, 13, 14, 15, 16])
+@pytest.mark.parametrize("variant", [10, 11, 12, 14, 15])
 @pytest.mark.parametrize("M", [1, 16])
 def test_every_wavefront_arrangement_of_the_streaming_kernel(M, variant, splitk):
-    # 8, 4 or 16 wavefronts on one strip, or 2 / 4 strips per workgroup
+    # 8, 4 or 16 wavefronts on one strip, or 8 / 16 on two strips
     from paper_2504_12984_amd import binding as B
     case = WL.Case(f"arr_{M}_{variant}_{splitk}", M, 1408, 512, I, 3, group=128, zero=None, seed=8350 + M)
     P = Prepared(case)
@@ -84,7 +84,7 @@ def test_every_wavefront_arrangement_of_the_streaming_kernel(M, variant, splitk)
     assert_c_close(P.gpu_c(), P.oracle_c(), case.name)
 
 
-@pytest.mark.parametrize("M,variant", [(17, 21), (32, 24), (30, 26), (33, 41), (64, 46), (50, 46)])
+@pytest.mark.parametrize("M,variant", [(17, 21), (32, 26), (30, 26), (33, 41), (64, 46), (50, 46)])
 def test_two_strip_arrangements_with_several_row_tiles(M, variant):
     from paper_2504_12984_amd import binding as B
     case = WL.Case(f"arr2_{M}_{variant}", M, 1152, 256, U, 6, group=128, act="bf16", scale_dtype="bf16",
