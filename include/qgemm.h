@@ -120,7 +120,7 @@ QG_API int qdequant(const void* packed_W, const void* scales, const uint8_t* zer
  * Arguments as for qdequant; M >= 1 is arbitrary, C is overwritten.
  * Path choice (by shape) is internal: M <= 64 streams the weights once through
  * a split-K kernel (1, 2 or 4 tiles of 16 rows per wavefront); larger M uses
- * the LDS-staged tiled kernel, except 64 < M <= 256 with so few output tiles
+ * the LDS-staged tiled kernel, except 64 < M <= 192 with so few output tiles
  * that most CUs would idle, which runs the streaming kernel over blocks of 64
  * rows (several launches on `stream`).  The tiled kernel needs M*K*2, the packed
  * weight and the scale array each below 4 GiB (QG_EUNSUPPORTED otherwise). */
@@ -132,7 +132,7 @@ QG_API int qgemm(const void* A, const void* packed_W, const void* scales, const 
  * previous value.  knob 0: forced path (1 = streaming kernel, 2 = tiled kernel, 3 =
  * streaming kernel over blocks of 64 rows);
  * knob 1: forced split-K factor of the small-M kernels; knob 2: forced row-tile
- * (128 / 256) of the tiled kernel; knob 3: pipeline variant of the M <= 64
+ * (64 / 128 / 256; 64 on the first layout only) of the tiled kernel; knob 3: pipeline variant of the M <= 64
  * kernel (10*row tiles + 0/1/2 for 8/4/16 wavefronts per strip: 10, 11, 12,
  * 21, 41; 14, 15, 26, 46: 8, 16 or 4 wavefronts on 2 adjacent strips).  Knobs 0, 1 and 3 apply to QG_LAYOUT_TILE128x64 only. */
 QG_API int qg_set_knob(int knob, int value);

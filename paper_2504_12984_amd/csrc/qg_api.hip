@@ -262,9 +262,10 @@ int qgemm(const void* A, const void* packed_W, const void* scales, const uint8_t
     // Few output tiles (narrow N) and a moderate M leave most CUs without a tile of the
     // tiled kernel (M = 128 on N = 8192: 32 workgroups); the streaming kernel run over
     // blocks of 64 rows fills the chip and is about twice as fast there (measured:
-    // 55 us against 114 us at K = N = 8192, M = 128; 106 against 112 at M = 256).
+    // 53 us against 96 us at K = N = 8192, M = 128; from M = 256 on the tiled kernel with
+    // 64-row tiles is the faster one).
     const int64_t tiles128 = ((M + 127) / 128) * ((N + 255) / 256);
-    if (M > 64 && M <= 256 && tiles128 <= 64) path = 3;
+    if (M > 64 && M <= 192 && tiles128 <= 64) path = 3;
   }
   if (path == 1 && M > 64) return QG_EINVAL;
 

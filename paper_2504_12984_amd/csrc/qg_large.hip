@@ -233,13 +233,15 @@ __global__ __launch_bounds__(256) void large_kernel(GemmParams p, int tiles_m, i
   //   MT % 4 == 0   store the A staging piece MT/4 loaded two k-steps ago
   //   MT % 4 == 2   start the load of that piece for two k-steps from now
   //   odd MT        (index MT/2 within the step) k-steps 0 and 1: WPS loads of the next
-  //                 chunk's weights; last four of k-step 2: the next chunk's first-group
-  //                 constants, one column each; first four of k-step 3 (two groups per
+  //                 chunk's weights; last CSLOTS of k-step 2: the next chunk's first-group
+  //                 constants, CPS columns each; first CSLOTS of k-step 3 (two groups per
   //                 chunk): the next chunk's second-group constants, rebuilt in place --
   //                 their last use was the unpack during k-step 2
   constexpr int FREE_PER_STEP = MTS / 2;
-  constexpr int WPS = (BM == 128) ? 2 : 1;
+  constexpr int WPS = (WPIECES + 2 * FREE_PER_STEP - 1) / (2 * FREE_PER_STEP);   // weight loads per odd tile
   constexpr int WSLOTS = (WPIECES + WPS - 1) / WPS;
+  constexpr int CPS = (4 + FREE_PER_STEP - 1) / FREE_PER_STEP;                  // constant columns per odd tile
+  constexpr int CSLOTS = 4 / CPS;
   static_assert(MTS / 4 == PIECES, "one staging piece per four row tiles");
   static_assert(WSLOTS <= 2 * FREE_PER_STEP, "weight loads must be issued by the end of k-step 1");
   if constexpr (TWO_GROUPS) {
@@ -313,9 +315,13 @@ __global__ __launch_bounds__(256) void large_kernel(GemmParams p, int tiles_m, i
             constexpr int I = FS * WPS + decltype(Xc)::value;
             if constexpr (I < WPIECES) w_piece(wn, kc + 1, std::integral_constant<int, I>{});
           });
-          if constexpr (J == 2 && IDX >= FREE_PER_STEP - 4)
-            consts_col(gn0, wn, std::integral_constant<int, 0>{}, IDX - (FREE_PER_STEP - 4));
-          if constexpr (TWO_GROUPS && J == 3 && IDX < 4) consts_col(g1, wn, std::integral_constant<int, 1>{}, IDX);
+          static_for<CPS>([&](auto Xc) __attribute__((always_inline)) {
+            constexpr int X = decltype(Xc)::value;
+            if constexpr (J == 2 && IDX >= FREE_PER_STEP - CSLOTS)
+              consts_col(gn0, wn, std::integral_constant<int, 0>{}, (IDX - (FREE_PER_STEP - CSLOTS)) * CPS + X);
+            if constexpr (TWO_GROUPS && J == 3 && IDX < CSLOTS)
+              consts_col(g1, wn, std::integral_constant<int, 1>{}, IDX * CPS + X);
+          });
         }
 #pragma unroll
         for (int q = 0; q < PB; ++q) mid_prev[q] = mid[q];
@@ -389,6 +395,7 @@ static int launch_bm(const GemmParams& p, hipStream_t st, int tn0, int tiles_n) 
 template <int ROUTE>
 static int launch_rows(const GemmParams& p, int bm, hipStream_t st, int tn0, int tiles_n) {
   const bool tg = (p.group == 64);
+  if (bm == 64) return tg ? launch_bm<ROUTE, true, 64>(p, st, tn0, tiles_n) : launch_bm<ROUTE, false, 64>(p, st, tn0, tiles_n);
   if (bm == 128) return tg ? launch_bm<ROUTE, true, 128>(p, st, tn0, tiles_n) : launch_bm<ROUTE, false, 128>(p, st, tn0, tiles_n);
   if (bm == 256) return tg ? launch_bm<ROUTE, true, 256>(p, st, tn0, tiles_n) : launch_bm<ROUTE, false, 256>(p, st, tn0, tiles_n);
   return QG_EINVAL;
@@ -406,6 +413,10 @@ static int launch_route(const GemmParams& p, int bm, hipStream_t st) {
     const long tiles = ((p.M + rows - 1) / rows) * cols;
     return ((tiles + 255) / 256) * (rows + 64);
   };
+  // 128-row tiles that would occupy at most half of the CUs: 64-row tiles instead -- a tile
+  // costs 0.89 of a 128-row one (the unpack per matrix instruction doubles) but twice as many
+  // CUs work (measured 10-15 % shorter: M = 128 on 28672 columns, M = 256..512 on 8192)
+  if ((long)((p.M + 127) / 128) * tiles_n <= 128) return launch_rows<ROUTE>(p, 64, st, 0, tiles_n);
   if (p.M <= 128) return launch_rows<ROUTE>(p, 128, st, 0, tiles_n);
   // Whole rounds of 256-row tiles first; the column tiles that would start a partly
   // filled last round go into a second launch with whichever height is cheaper for

@@ -137,7 +137,7 @@ def test_empty_m_and_bad_arguments():
 
 
 # ------------------------------------------------------------------ tiled path
-@pytest.mark.parametrize("bm", [128, 256])
+@pytest.mark.parametrize("bm", [64, 128, 256])
 @pytest.mark.parametrize("M,K,N", [(200, 512, 256), (257, 384, 320), (65, 128, 64), (512, 1024, 512)])
 def test_tiled_path_ragged_shapes(M, K, N, bm):
     from paper_2504_12984_amd import binding as B
@@ -161,7 +161,7 @@ def test_tiled_path_weight_types(kind, bits, e, m, act):
     assert_c_close(P.gpu_c(), P.oracle_c(), case.name)
 
 
-@pytest.mark.parametrize("bm", [128, 256])
+@pytest.mark.parametrize("bm", [64, 128, 256])
 @pytest.mark.parametrize("bits", [1, 3, 4, 7, 8])
 def test_tiled_path_fp16_two_groups_per_chunk(bits, bm):
     # group 64 puts two sets of scales / zero-points in every 128-row chunk
@@ -176,7 +176,7 @@ def test_tiled_path_fp16_two_groups_per_chunk(bits, bm):
 
 @pytest.mark.parametrize("M", [65, 100, 128, 129, 192])
 def test_moderate_m_on_few_tiles_runs_the_streaming_kernel_in_row_blocks(M):
-    # automatic choice for 64 < M <= 256 with few output tiles; also forced on a ragged last block
+    # automatic choice for 64 < M <= 192 with few output tiles; also forced on a ragged last block
     from paper_2504_12984_amd import binding as B
     case = WL.Case(f"blocks_{M}", M, 1152, 320, I, 5, group=128, act="bf16", scale_dtype="f16", zero=None,
                    seed=8870 + M)
