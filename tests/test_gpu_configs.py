@@ -115,10 +115,14 @@ def test_config5_prefill_full_on_the_second_layout():
         f.check_gemm(_A_of(WL.cfg5(6, M)), wr, f"cfg5 u6 M={M} layout 1")
 
 
-@pytest.mark.parametrize("kind,bits", [(WL.KIND_UINT, 1), (WL.KIND_UINT, 7), (WL.KIND_FLOAT, 3), (WL.KIND_FLOAT, 5),
-                                       (WL.KIND_FLOAT, 7)])
+SWEEP = ([(WL.KIND_UINT, b) for b in range(1, 9)] + [(WL.KIND_INT, b) for b in range(2, 9)] +
+         [(WL.KIND_FLOAT, b) for b in range(3, 9)])
+
+
+@pytest.mark.parametrize("kind,bits", SWEEP)
 def test_type_sweep_shapes_full(kind, bits):
-    # the wide sweep shape (N = 57344) for types the five configurations do not cover
+    # the paper's full type sweep at its shape (M = 16, K = 8192, N = 57344): uint1..8, int2..8 and
+    # the representative float of every width from 3 to 8 bits
     f = FullCase(WL.sweep(kind, bits))
     wr = f.check_weights()
     f.check_gemm(f.inp["A"], wr, f.case.name)
