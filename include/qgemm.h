@@ -120,9 +120,9 @@ QG_API int qdequant(const void* packed_W, const void* scales, const uint8_t* zer
  * Arguments as for qdequant; M >= 1 is arbitrary, C is overwritten.
  * Path choice (by shape) is internal: M <= 64 streams the weights once through
  * a split-K kernel (1, 2 or 4 tiles of 16 rows per wavefront); larger M uses
- * the LDS-staged tiled kernel, except 64 < M <= 192 with so few output tiles
- * that most CUs would idle, which runs the streaming kernel over blocks of 64
- * rows (several launches on `stream`).  The tiled kernel needs M*K*2, the packed
+ * the LDS-staged tiled kernel, which also splits K (partial sums meet in a
+ * per-device workspace the library allocates on first use) when its 64- or
+ * 128-row tiles would leave most CUs idle.  The tiled kernel needs M*K*2, the packed
  * weight and the scale array each below 4 GiB (QG_EUNSUPPORTED otherwise). */
 QG_API int qgemm(const void* A, const void* packed_W, const void* scales, const uint8_t* zeros,
           qg_wtype t, int layout, int act, int scale_dtype, int64_t group,
@@ -131,7 +131,7 @@ QG_API int qgemm(const void* A, const void* packed_W, const void* scales, const 
 /* Optional: path/tuning override for experiments (0 = automatic).  Returns the
  * previous value.  knob 0: forced path (1 = streaming kernel, 2 = tiled kernel, 3 =
  * streaming kernel over blocks of 64 rows);
- * knob 1: forced split-K factor of the small-M kernels; knob 2: forced row-tile
+ * knob 1: forced split-K factor (streaming kernel; tiled kernel with 64- or 128-row tiles); knob 2: forced row-tile
  * (64 / 128 / 256; 64 on the first layout only) of the tiled kernel; knob 3: pipeline variant of the M <= 64
  * kernel (10*row tiles + 0/1/2 for 8/4/16 wavefronts per strip: 10, 11, 12,
  * 21, 41; 14, 15, 26, 46: 8, 16 or 4 wavefronts on 2 adjacent strips).  Knobs 0, 1 and 3 apply to QG_LAYOUT_TILE128x64 only. */

@@ -259,13 +259,6 @@ int qgemm(const void* A, const void* packed_W, const void* scales, const uint8_t
   int path = g_knob[0];
   if (path == 0) {
     path = (M <= 64) ? 1 : 2;
-    // Few output tiles (narrow N) and a moderate M leave most CUs without a tile of the
-    // tiled kernel (M = 128 on N = 8192: 32 workgroups); the streaming kernel run over
-    // blocks of 64 rows fills the chip and is about twice as fast there (measured:
-    // 53 us against 96 us at K = N = 8192, M = 128; from M = 256 on the tiled kernel with
-    // 64-row tiles is the faster one).
-    const int64_t tiles128 = ((M + 127) / 128) * ((N + 255) / 256);
-    if (M > 64 && M <= 192 && tiles128 <= 64) path = 3;
   }
   if (path == 1 && M > 64) return QG_EINVAL;
 
@@ -281,7 +274,51 @@ int qgemm(const void* A, const void* packed_W, const void* scales, const uint8_t
     return QG_OK;
   }
   if (!fits32) return QG_EUNSUPPORTED;
-  return kLarge[wt](p, route, g_knob[2], st);
+  // Split-K for the lower row tiles when they would leave CUs idle.  Candidates: 64- or
+  // 128-row tiles, K cut into 1, 2, 4 or 8 slabs of an even number of chunks (the kernel
+  // works in pairs of chunks), at most one workgroup per CU when split.  Cost in
+  // microseconds, fitted to measurements at K = 1024 .. 8192, N = 2048 .. 14336:
+  // chunks per workgroup x time per chunk (1.33 at up to 4 bits, + 0.33 per bit above,
+  // x 1.13 for 128 rows) + for the exchange of partial sums 5 + 0.4 per MB with 64-row
+  // tiles, 11 + 0.6 per MB with 128-row tiles.
+  int bm = g_knob[2], splitk = g_knob[1];
+  const int KC = (int)(K / TILE_K);
+  const int64_t tiles_n = (N + 255) / 256;
+  if (bm == 0 && large_prefers_64_rows(M, N)) {
+    bm = 64;
+    if (splitk <= 0) {
+      const double tc = 1.33 + 0.33 * (t.bits > 4 ? t.bits - 4 : 0);
+      double best = 1e30;
+      for (int cand_bm = 64; cand_bm <= 128; cand_bm *= 2)
+        for (int sk = 1; sk <= 8; sk *= 2) {
+          const int64_t tiles_m = (M + cand_bm - 1) / cand_bm;
+          int cps = (KC + sk - 1) / sk;
+          if (sk > 1 && (cps & 1)) ++cps;
+          if (sk > 1 && (cps < 4 || tiles_m * tiles_n * sk > 256)) continue;
+          const double rounds = (double)((tiles_m * tiles_n * sk + 255) / 256);
+          const double mb = (double)sk * (double)(tiles_m * cand_bm) * (double)(tiles_n * 256) * 4.0 / 1e6;
+          const double cost = rounds * cps * tc * (cand_bm == 64 ? 1.0 : 1.13) +
+                              (sk > 1 ? (cand_bm == 64 ? 5.0 + 0.4 * mb : 11.0 + 0.6 * mb) : 0.0);
+          if (cost < best) { best = cost; bm = cand_bm; splitk = sk; }
+        }
+    }
+  }
+  if (splitk <= 0) splitk = 1;
+  if (bm == 64 || bm == 128) {
+    const int64_t tiles = ((M + bm - 1) / bm) * tiles_n;
+    if (splitk > KC) splitk = KC;
+    int cps = (KC + splitk - 1) / splitk;
+    if (splitk > 1 && (cps & 1)) ++cps;
+    splitk = (KC + cps - 1) / cps;
+    if (splitk > 1) {
+      Workspace* w = nullptr;
+      rc = get_workspace((size_t)splitk * (size_t)tiles * (size_t)(bm * 256) * sizeof(float), (size_t)tiles, st, &w);
+      if (rc != QG_OK) return rc;
+      p.ws = w->partial; p.tickets = w->tickets;
+      p.splitk = splitk; p.chunks_per_split = cps;
+    }
+  }
+  return kLarge[wt](p, route, bm, st);
 }
 
 int qg_probe_stream_read(const void* buf, size_t bytes, void* sink, void* stream) {

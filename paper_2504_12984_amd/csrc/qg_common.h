@@ -136,6 +136,10 @@ inline bool set_group_index(GemmParams& p) {
   return true;
 }
 
+// The 16x16 tiled kernel's own choice of 64-row tiles: when 128-row tiles would occupy at
+// most half of the 256 CUs (column tiles are 256 wide).
+inline bool large_prefers_64_rows(int64_t M, int64_t N) { return ((M + 127) / 128) * ((N + 255) / 256) <= 128; }
+
 typedef int (*dequant_launch_fn)(const DequantParams&, hipStream_t);
 typedef int (*gemm_launch_fn)(const GemmParams&, int mt, hipStream_t);
 

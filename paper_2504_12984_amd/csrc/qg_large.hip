@@ -78,19 +78,24 @@ __global__ __launch_bounds__(256) void large_kernel(GemmParams p, int tiles_m, i
   extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
 
   // ---- which tile ----------------------------------------------------------------
-  const int total = tiles_m * tiles_n;
+  // With split-K every tile is computed by p.splitk workgroups, one per slab of
+  // chunks_per_split K-chunks; the slab is the slowest index, so the workgroups of a slab
+  // keep the panel order among themselves.
+  const int tiles = tiles_m * tiles_n;
   const int logical = (int)(blockIdx.x % 8) * per_xcd + (int)(blockIdx.x / 8);
-  if (logical >= total) return;
+  if (logical >= tiles * p.splitk) return;
+  const int slab = logical / tiles, tile = logical % tiles;
   const int panel = LARGE_GROUP_M * tiles_n;
-  const int first_m = (logical / panel) * LARGE_GROUP_M;
+  const int first_m = (tile / panel) * LARGE_GROUP_M;
   const int gsize = min(tiles_m - first_m, LARGE_GROUP_M);
-  const int tm = first_m + (logical % panel) % gsize;
-  const int tn = tn0 + (logical % panel) / gsize;       // tn0: first column tile of this launch
+  const int tm = first_m + (tile % panel) % gsize;
+  const int tn = tn0 + (tile % panel) / gsize;          // tn0: first column tile of this launch
 
   const int tid = threadIdx.x, l = tid & 63;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, kept in a scalar register
   const int b = l >> 4, i16 = l & 15;
   const int KC = p.K / TILE_K, NCH = p.N / TILE_N;
+  const int kbeg = slab * p.chunks_per_split, kend = min(KC, kbeg + p.chunks_per_split);   // my K-chunks
   const int m0 = tm * BM;
   const int ncw = tn * (LARGE_BN / TILE_N) + w;          // my 64-column strip
   const bool active = ncw < NCH;
@@ -113,9 +118,9 @@ __global__ __launch_bounds__(256) void large_kernel(GemmParams p, int tiles_m, i
   const int a_dst0 = srow * 64 + 16 * (spc ^ lds_swizzle(srow));          // + 4096*i for piece i
   auto a_load = [&](int i, int kstep) __attribute__((always_inline)) {     // kstep = 4*chunk + slice
     // the row part stays in the vector offset so that the range check sees it; k-steps
-    // past K (the padding chunk of an odd chunk count, the ring's look-ahead at the
-    // end) are pushed out of range as well and read as zeros
-    const uint32_t past = (kstep < 4 * KC) ? 0u : 0x80000000u;
+    // past my last chunk (the padding chunk of an odd chunk count, the ring's look-ahead
+    // at the end) are pushed out of range as well and read as zeros
+    const uint32_t past = (kstep < 4 * kend) ? 0u : 0x80000000u;
     return __builtin_amdgcn_raw_buffer_load_b128(a_rsrc, (int)(a_off0 + (uint32_t)i * a_step + past),
                                                  min(kstep, 4 * KC - 1) * 64, 0);
   };
@@ -190,12 +195,13 @@ __global__ __launch_bounds__(256) void large_kernel(GemmParams p, int tiles_m, i
 
   // ---- prologue: chunk 0's A slab into buffer 0, ring primed for chunk 1 --------------
   WStage wA, wB;
-  w_issue(wA, 0);
-  a_issue(0, 0); a_issue(1, 1);
-  a_commit(0, 0, 0); a_issue(0, 2);
-  a_commit(1, 0, 1); a_issue(1, 3);
-  a_commit(0, 0, 2); a_issue(0, 4);     // slice 0 of chunk 1
-  a_commit(1, 0, 3); a_issue(1, 5);     // slice 1 of chunk 1
+  w_issue(wA, kbeg);
+  const int ks0 = 4 * kbeg;
+  a_issue(0, ks0); a_issue(1, ks0 + 1);
+  a_commit(0, 0, 0); a_issue(0, ks0 + 2);
+  a_commit(1, 0, 1); a_issue(1, ks0 + 3);
+  a_commit(0, 0, 2); a_issue(0, ks0 + 4);     // slice 0 of the second chunk
+  a_commit(1, 0, 3); a_issue(1, ks0 + 5);     // slice 1 of the second chunk
 
   // my A fragment of row-tile mt, k-step slice j: piece b of row mt*16 + i16
   const int a_rd = i16 * 64 + 16 * (b ^ lds_swizzle(i16));
@@ -341,7 +347,7 @@ __global__ __launch_bounds__(256) void large_kernel(GemmParams p, int tiles_m, i
   // count is padded with one chunk whose A slab reads as zeros, which keeps the loop
   // free of a conditional tail (with one, the compiler merged tail and loop body and
   // shuffled the whole accumulator state around the merge).
-  for (int kc = 0; kc < KC; kc += 2) {
+  for (int kc = kbeg; kc < kend; kc += 2) {
     chunk(std::integral_constant<int, 0>{}, wA, wB, gA0, gB0, kc);
     chunk(std::integral_constant<int, 1>{}, wB, wA, gB0, gA0, kc + 1);
   }
@@ -349,6 +355,70 @@ __global__ __launch_bounds__(256) void large_kernel(GemmParams p, int tiles_m, i
   // the matrix pipeline may still be writing the accumulators (the compiler
   // does not see the asm MFMAs, so it inserts no wait states of its own)
   asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+
+  // ---- split-K: partial tiles meet in the workspace ------------------------------------
+  // Partial sums cross workgroups (and XCDs, whose L2s are not coherent with each other)
+  // through 16-byte buffer stores and loads that carry the sc1 cache-policy bit, which is
+  // what a device-scope relaxed atomic store / load compiles to on this target: the store
+  // writes through, the load bypasses the local caches.  My stores complete, barrier, one
+  // arrival count per workgroup; the workgroup that counts splitk-1 earlier arrivals sums
+  // all slabs in slab order, so the result does not depend on arrival order.  Only the
+  // lower tiles use this (the host never splits 256-row tiles).
+  if constexpr (BM <= 128) {
+    if (p.splitk > 1) {
+      constexpr int SC1 = 16;                                   // cache policy: device coherence
+      constexpr int TILE_BYTES = BM * LARGE_BN * 4;
+      auto ws_rsrc = [&](int sp) __attribute__((always_inline)) {
+        return __builtin_amdgcn_make_buffer_rsrc(p.ws + ((int64_t)tile * p.splitk + sp) * (BM * LARGE_BN), 0, TILE_BYTES, 0x00020000);
+      };
+      // lane layout of a partial tile: fragment (mt, nt) of thread tid at 16 * ((mt*4+nt)*256 + tid)
+      if (active) {
+        const __amdgpu_buffer_rsrc_t mine = ws_rsrc(slab);
+#pragma unroll
+        for (int mt = 0; mt < MTS; ++mt)
+          if (m0 + mt * 16 + i16 < p.M) {
+#pragma unroll
+            for (int nt = 0; nt < 4; ++nt)
+              __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u4_t, acc[mt][nt]), mine, 16 * tid, (mt * 4 + nt) * 4096, SC1);
+          }
+      }
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // a workgroup barrier alone does not wait for global stores
+      __syncthreads();
+      unsigned* s_last = reinterpret_cast<unsigned*>(lds);          // the A slabs are dead by now
+      if (tid == 0)
+        *s_last = (__hip_atomic_fetch_add(&p.tickets[tile], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (unsigned)(p.splitk - 1));
+      __syncthreads();
+      if (!*s_last) return;
+#pragma unroll
+      for (int mt = 0; mt < MTS; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < 4; ++nt) acc[mt][nt] = (f4_t){0.f, 0.f, 0.f, 0.f};
+      if (active) {
+        // two slabs' loads are in flight together (the second of an odd count is a repeat
+        // of the last slab whose values are dropped)
+        for (int sp = 0; sp < p.splitk; sp += 2) {
+          const bool two = sp + 1 < p.splitk;
+          const __amdgpu_buffer_rsrc_t r0 = ws_rsrc(sp), r1 = ws_rsrc(two ? sp + 1 : sp);
+          u4_t v0[MTS][4], v1[MTS][4];
+#pragma unroll
+          for (int mt = 0; mt < MTS; ++mt)
+#pragma unroll
+            for (int nt = 0; nt < 4; ++nt) {
+              v0[mt][nt] = __builtin_amdgcn_raw_buffer_load_b128(r0, 16 * tid, (mt * 4 + nt) * 4096, SC1);
+              v1[mt][nt] = __builtin_amdgcn_raw_buffer_load_b128(r1, 16 * tid, (mt * 4 + nt) * 4096, SC1);
+            }
+#pragma unroll
+          for (int mt = 0; mt < MTS; ++mt)
+#pragma unroll
+            for (int nt = 0; nt < 4; ++nt) {
+              acc[mt][nt] += __builtin_bit_cast(f4_t, v0[mt][nt]);
+              if (two) acc[mt][nt] += __builtin_bit_cast(f4_t, v1[mt][nt]);
+            }
+        }
+      }
+      if (tid == 0) __hip_atomic_store(&p.tickets[tile], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next call
+    }
+  }
 
   // ---- epilogue: a lane holds 16 consecutive columns of row mt*16 + i16 ---------------
   if (!active) return;
@@ -377,7 +447,8 @@ __global__ __launch_bounds__(256) void large_kernel(GemmParams p, int tiles_m, i
 template <int ROUTE, bool TG, int BM>
 static int launch_bm(const GemmParams& p, hipStream_t st, int tn0, int tiles_n) {
   const int tiles_m = (p.M + BM - 1) / BM;
-  const int total = tiles_m * tiles_n;
+  if (p.splitk > 1 && BM > 128) return QG_EINVAL;
+  const int total = tiles_m * tiles_n * p.splitk;
   const int per_xcd = (total + 7) / 8;
   const size_t lds_bytes = 2 * LargeLds<BM>::BUF;
   auto kern = large_kernel<QG_WT, ROUTE, TG, BM>;
@@ -416,7 +487,7 @@ static int launch_route(const GemmParams& p, int bm, hipStream_t st) {
   // 128-row tiles that would occupy at most half of the CUs: 64-row tiles instead -- a tile
   // costs 0.89 of a 128-row one (the unpack per matrix instruction doubles) but twice as many
   // CUs work (measured 10-15 % shorter: M = 128 on 28672 columns, M = 256..512 on 8192)
-  if ((long)((p.M + 127) / 128) * tiles_n <= 128) return launch_rows<ROUTE>(p, 64, st, 0, tiles_n);
+  if (large_prefers_64_rows(p.M, p.N)) return launch_rows<ROUTE>(p, 64, st, 0, tiles_n);
   if (p.M <= 128) return launch_rows<ROUTE>(p, 128, st, 0, tiles_n);
   // Whole rounds of 256-row tiles first; the column tiles that would start a partly
   // filled last round go into a second launch with whichever height is cheaper for

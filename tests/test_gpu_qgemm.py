@@ -161,6 +161,28 @@ def test_tiled_path_weight_types(kind, bits, e, m, act):
     assert_c_close(P.gpu_c(), P.oracle_c(), case.name)
 
 
+@pytest.mark.parametrize("bm", [64, 128])
+@pytest.mark.parametrize("splitk", [2, 3, 4, 11])
+@pytest.mark.parametrize("M,K,N,group", [(40, 1408, 320, 128), (64, 1024, 256, 64), (150, 896, 192, 128)])
+def test_tiled_path_split_k(M, K, N, group, splitk, bm):
+    # slabs of an even number of chunks with a shorter (odd: 11 chunks in slabs of 4, 7 in
+    # slabs of 4) last slab, idle wavefronts (N not a multiple of 256), rows past M, more
+    # slabs asked for than there are chunk pairs; the second call must find the arrival
+    # counters at zero and give identical bits
+    from paper_2504_12984_amd import binding as B
+    case = WL.Case(f"tiled_splitk_{M}_{K}_{N}_{splitk}_{bm}", M, K, N, U, 4, group=group, act="bf16",
+                   scale_dtype="bf16", zero=8, seed=8870 + M + splitk)
+    P = Prepared(case)
+    ref = P.oracle_c()
+    B.qg_set_knob(0, 2)
+    B.qg_set_knob(1, splitk)
+    B.qg_set_knob(2, bm)
+    first = P.gpu_c()
+    assert_c_close(first, ref, case.name)
+    second = P.gpu_c()
+    assert np.array_equal(bits_of(first), bits_of(second))
+
+
 @pytest.mark.parametrize("bm", [64, 128, 256])
 @pytest.mark.parametrize("bits", [1, 3, 4, 7, 8])
 def test_tiled_path_fp16_two_groups_per_chunk(bits, bm):
@@ -175,8 +197,8 @@ def test_tiled_path_fp16_two_groups_per_chunk(bits, bm):
 
 
 @pytest.mark.parametrize("M", [65, 100, 128, 129, 192])
-def test_moderate_m_on_few_tiles_runs_the_streaming_kernel_in_row_blocks(M):
-    # automatic choice for 64 < M <= 192 with few output tiles; also forced on a ragged last block
+def test_moderate_m_on_few_tiles_automatic_row_blocks_and_tiled(M):
+    # the automatic choice, the streaming kernel over blocks of 64 rows (ragged last block) and the tiled kernel
     from paper_2504_12984_amd import binding as B
     case = WL.Case(f"blocks_{M}", M, 1152, 320, I, 5, group=128, act="bf16", scale_dtype="f16", zero=None,
                    seed=8870 + M)
