@@ -134,7 +134,7 @@ QG_API int qgemm(const void* A, const void* packed_W, const void* scales, const 
  * knob 1: forced split-K factor (streaming kernel; tiled kernel with 64- or 128-row tiles); knob 2: forced row-tile
  * (64 / 128 / 256; 64 on the first layout only) of the tiled kernel; knob 3: pipeline variant of the M <= 64
  * kernel (10*row tiles + 0/1/2 for 8/4/16 wavefronts per strip: 10, 11, 12,
- * 21, 41; 14, 15, 26, 46: 8, 16 or 4 wavefronts on 2 adjacent strips).  Knobs 0, 1 and 3 apply to QG_LAYOUT_TILE128x64 only. */
+ * 21, 41; 14, 15, 26, 46: 8, 16 or 4 wavefronts on 2 adjacent strips; 16: 16 wavefronts on 4 strips).  Knobs 0, 1 and 3 apply to QG_LAYOUT_TILE128x64 only. */
 QG_API int qg_set_knob(int knob, int value);
 
 /* Measurement aids -- not part of the method (no passage of the paper defines

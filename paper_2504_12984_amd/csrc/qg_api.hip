@@ -126,6 +126,9 @@ static int launch_streaming(GemmParams& p, int wt, int route, hipStream_t st) {
   // up to 6 bits per code a wavefront needs few enough registers for 16 of them per
   // workgroup (2 strips x 8 along K): twice the wavefronts in flight, 1-6 % shorter
   if (variant == 14 && wt_bits(wt) <= 6 && p.group != 64) variant = 15;
+  // and with enough strips for groups of four: 4 strips x 4 along K, half as many, twice as
+  // long-lived workgroups (measured 5-9 % shorter at K = 8192, N = 57344, 2 to 6 bits)
+  if (variant == 15 && NCH % 4 == 0 && NCH / 4 >= 192) variant = 16;
   // long K but too few strips to fill the chip (K is split over workgroups below): more
   // wavefronts per strip for narrow codes -- 16 up to 4 bits, 8 up to 6 (measured on
   // K = N = 8192: 11 % and 7 % shorter at 4 bits, no gain at 8)

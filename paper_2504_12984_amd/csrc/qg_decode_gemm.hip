@@ -336,6 +336,7 @@ static int launch_variant(const GemmParams& p, int variant, hipStream_t st) {
     case 12: return launch_cfg<ROUTE, TG, 16, 2, 1>(p, st);
     case 14: return launch_cfg<ROUTE, TG, 8, 2, 1, 2>(p, st);     // 2 strips x 4
     case 15: return launch_cfg<ROUTE, TG, 16, 2, 1, 2>(p, st);    // 2 strips x 8
+    case 16: return launch_cfg<ROUTE, TG, 16, 2, 1, 4>(p, st);    // 4 strips x 4
     case 21: return launch_cfg<ROUTE, TG, 4, 2, 2>(p, st);
     case 26: return launch_cfg<ROUTE, TG, 4, 2, 2, 2>(p, st);     // 2 row tiles, 2 strips x 2
     case 46: return launch_cfg<ROUTE, TG, 4, 2, 4, 2>(p, st);     // 4 row tiles, 2 strips x 2
@@ -349,7 +350,7 @@ int QG_CAT(decode_waves_wt, QG_WT)(int variant) {
   switch (variant) {
     case 10: return 8;
     case 12: return 16;
-    case 14: return 4;
+    case 14: case 16: return 4;
     case 26: case 46: return 2;
     case 15: return 8;
     default: return 4;

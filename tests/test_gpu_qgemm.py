@@ -72,7 +72,7 @@ def test_split_k_factors_agree_with_oracle_and_leave_counters_clean(splitk):
 
 
 @pytest.mark.parametrize("splitk", [1, 3])
-@pytest.mark.parametrize("variant", [10, 11, 12, 14, 15])
+@pytest.mark.parametrize("variant", [10, 11, 12, 14, 15, 16])
 @pytest.mark.parametrize("M", [1, 16])
 def test_every_wavefront_arrangement_of_the_streaming_kernel(M, variant, splitk):
     # 8, 4 or 16 wavefronts on one strip, or 8 / 16 on two strips
