@@ -137,6 +137,17 @@ QG_API int qgemm(const void* A, const void* packed_W, const void* scales, const 
  * 21, 41; 14, 15, 26, 46: 8, 16 or 4 wavefronts on 2 adjacent strips; 16: 16 wavefronts on 4 strips).  Knobs 0, 1 and 3 apply to QG_LAYOUT_TILE128x64 only. */
 QG_API int qg_set_knob(int knob, int value);
 
+/* What qgemm would launch for a shape: host arithmetic only, no GPU call, usable without
+ * a device.  Arguments as for qgemm (M >= 1).  plan (host, 5 ints) receives
+ *   [0] path: 1 = streaming kernel, 2 = tiled kernel, 3 = streaming kernel over blocks of 64 rows
+ *   [1] wavefront arrangement of the streaming kernel (the values of knob 3), 0 on path 2
+ *   [2] row-tile height of the tiled kernel: 64 or 128, or 0 = whole rounds of 256-row
+ *       tiles, then 128 or 256 rows for the rest; 0 on paths 1 and 3
+ *   [3] K-slabs (split-K factor; 1 = none)   [4] K-chunks of 128 per slab
+ * The knobs apply as in qgemm.  Returns the status qgemm's argument checks would return. */
+QG_API int qg_plan(qg_wtype t, int layout, int act, int scale_dtype, int64_t group,
+            int64_t M, int64_t N, int64_t K, int plan[5]);
+
 /* Measurement aids -- not part of the method (no passage of the paper defines
  * them): the two empirical ceilings bench.py quotes beside the published peaks.
  * Both enqueue one kernel on `stream` and return; the caller times them.

@@ -25,7 +25,7 @@ QG_LAYOUT_TILE128x64_R32 = 1
 TILE_K, TILE_N = 128, 64
 
 EXPORTS = ("qg_status_string", "qg_last_error", "qg_canonical_bytes", "qgemm_packed_bytes",
-           "qg_pack_codes", "repack", "qdequant", "qgemm", "qg_set_knob", "qg_probe_stream_read",
+           "qg_pack_codes", "repack", "qdequant", "qgemm", "qg_set_knob", "qg_plan", "qg_probe_stream_read",
            "qg_probe_mfma")
 
 
@@ -78,6 +78,8 @@ def _load() -> ctypes.CDLL:
     lib.qgemm.restype = i32
     lib.qgemm.argtypes = [vp, vp, vp, vp, QgWType, i32, i32, i32, i64, i64, i64, i64, vp, vp]
     lib.qg_set_knob.restype = i32
+    lib.qg_plan.argtypes = [QgWType, i32, i32, i32, i64, i64, i64, i64, ctypes.POINTER(ctypes.c_int32)]
+    lib.qg_plan.restype = i32
     lib.qg_set_knob.argtypes = [i32, i32]
     lib.qg_probe_stream_read.restype = i32
     lib.qg_probe_stream_read.argtypes = [vp, sz, vp, vp]
@@ -227,3 +229,11 @@ def qg_probe_mfma(bf16: bool, random_data: bool, iters: int, waves_per_simd: int
 
 def qg_set_knob(knob: int, value: int) -> int:
     return _lib.qg_set_knob(knob, value)
+
+
+def qg_plan(t: WType, group: int, M: int, N: int, K: int, act: int = QG_F16, scale_dtype: int | None = None,
+            layout: int = QG_LAYOUT_TILE128x64) -> dict:
+    """What qgemm would launch for this shape (host arithmetic only, no GPU needed)."""
+    out = (ctypes.c_int32 * 5)()
+    _check("qg_plan", _lib.qg_plan(t.c(), layout, act, act if scale_dtype is None else scale_dtype, group, M, N, K, out))
+    return {"path": out[0], "variant": out[1], "row_tile": out[2], "splitk": out[3], "chunks_per_slab": out[4]}

@@ -110,10 +110,9 @@ static int check_common(qg_wtype t, int layout, int act, int scale_dtype, int64_
   return QG_OK;
 }
 
-// One launch of the streaming kernel (M <= 64): wavefront arrangement and split-K by shape.
-static int launch_streaming(GemmParams& p, int wt, int route, hipStream_t st) {
-  const int M = p.M;
-  const int KC = p.K / TILE_K, NCH = p.N / TILE_N;
+// Streaming kernel (M <= 64): wavefront arrangement and split-K by shape.  Host arithmetic only.
+static void plan_streaming(int M, int N, int K, int group, int wt, int* variant_out, int* splitk_out, int* cps_out) {
+  const int KC = K / TILE_K, NCH = N / TILE_N;
   const int mt = M <= 16 ? 1 : (M <= 32 ? 2 : 4);
   // 16 wavefronts per strip for one row tile and short K (two chunks per wavefront,
   // every load of the strip in flight at once), 4 wavefronts otherwise
@@ -125,7 +124,7 @@ static int launch_streaming(GemmParams& p, int wt, int route, hipStream_t st) {
   if (KC > 32 && NCH % 2 == 0 && NCH / 2 >= 192) variant = (mt == 1) ? 14 : (mt == 2) ? 26 : 46;
   // up to 6 bits per code a wavefront needs few enough registers for 16 of them per
   // workgroup (2 strips x 8 along K): twice the wavefronts in flight, 1-6 % shorter
-  if (variant == 14 && wt_bits(wt) <= 6 && p.group != 64) variant = 15;
+  if (variant == 14 && wt_bits(wt) <= 6 && group != 64) variant = 15;
   // and with enough strips for groups of four: 4 strips x 4 along K, half as many, twice as
   // long-lived workgroups (measured 5-9 % shorter at K = 8192, N = 57344, 2 to 6 bits)
   if (variant == 15 && NCH % 4 == 0 && NCH / 4 >= 192) variant = 16;
@@ -144,18 +143,72 @@ static int launch_streaming(GemmParams& p, int wt, int route, hipStream_t st) {
     while (NCH * splitk < 256 && KC / (splitk * 2) >= min_chunks * waves) splitk *= 2;
   }
   if (splitk > KC) splitk = KC;
-  int cps = (KC + splitk - 1) / splitk;
-  splitk = (KC + cps - 1) / cps;
-  p.splitk = splitk; p.chunks_per_split = cps;
-  if (splitk > 1) {
+  const int cps = (KC + splitk - 1) / splitk;
+  *variant_out = variant;
+  *splitk_out = (KC + cps - 1) / cps;
+  *cps_out = cps;
+}
+
+// One launch of the streaming kernel.
+static int launch_streaming(GemmParams& p, int wt, int route, hipStream_t st) {
+  int variant;
+  plan_streaming(p.M, p.N, p.K, p.group, wt, &variant, &p.splitk, &p.chunks_per_split);
+  if (p.splitk > 1) {
+    const int NCH = p.N / TILE_N, mt = p.M <= 16 ? 1 : (p.M <= 32 ? 2 : 4);
     Workspace* w = nullptr;
-    size_t pbytes = (size_t)splitk * NCH * (size_t)(mt * 16 * TILE_N) * sizeof(float);
+    size_t pbytes = (size_t)p.splitk * NCH * (size_t)(mt * 16 * TILE_N) * sizeof(float);
     int rc = get_workspace(pbytes, (size_t)NCH, st, &w);
     if (rc != QG_OK) return rc;
     p.ws = w->partial; p.tickets = w->tickets;
   }
   return kDecode[wt](p, route, variant, st);
 }
+
+// Tiled kernel of the first layout: row-tile height (0 = the kernel's own choice between
+// 256 and 128 rows by rounds of workgroups) and split-K.  Host arithmetic only.
+//
+// Split-K serves the lower row tiles when they would leave CUs idle.  Candidates: 64- or
+// 128-row tiles, K cut into 1, 2, 4 or 8 slabs of an even number of chunks (the kernel
+// works in pairs of chunks), at most one workgroup per CU when split.  Cost in
+// microseconds, fitted to measurements at K = 1024 .. 8192, N = 2048 .. 14336:
+// chunks per workgroup x time per chunk (1.33 at up to 4 bits, + 0.33 per bit above,
+// x 1.13 for 128 rows) + for the exchange of partial sums 5 + 0.4 per MB with 64-row
+// tiles, 11 + 0.6 per MB with 128-row tiles.
+static void plan_tiled(int64_t M, int64_t N, int64_t K, int bits, int* bm_out, int* splitk_out, int* cps_out) {
+  int bm = g_knob[2], splitk = g_knob[1];
+  const int KC = (int)(K / TILE_K);
+  const int64_t tiles_n = (N + 255) / 256;
+  if (bm == 0 && large_prefers_64_rows(M, N)) {
+    bm = 64;
+    if (splitk <= 0) {
+      const double tc = 1.33 + 0.33 * (bits > 4 ? bits - 4 : 0);
+      double best = 1e30;
+      for (int cand_bm = 64; cand_bm <= 128; cand_bm *= 2)
+        for (int sk = 1; sk <= 8; sk *= 2) {
+          const int64_t tiles_m = (M + cand_bm - 1) / cand_bm;
+          int cps = (KC + sk - 1) / sk;
+          if (sk > 1 && (cps & 1)) ++cps;
+          if (sk > 1 && (cps < 4 || tiles_m * tiles_n * sk > 256)) continue;
+          const double rounds = (double)((tiles_m * tiles_n * sk + 255) / 256);
+          const double mb = (double)sk * (double)(tiles_m * cand_bm) * (double)(tiles_n * 256) * 4.0 / 1e6;
+          const double cost = rounds * cps * tc * (cand_bm == 64 ? 1.0 : 1.13) +
+                              (sk > 1 ? (cand_bm == 64 ? 5.0 + 0.4 * mb : 11.0 + 0.6 * mb) : 0.0);
+          if (cost < best) { best = cost; bm = cand_bm; splitk = sk; }
+        }
+    }
+  }
+  if (splitk <= 0 || (bm != 64 && bm != 128)) splitk = 1;
+  if (splitk > KC) splitk = KC;
+  int cps = (KC + splitk - 1) / splitk;
+  if (splitk > 1 && (cps & 1)) ++cps;
+  *bm_out = bm;
+  *splitk_out = (KC + cps - 1) / cps;
+  *cps_out = cps;
+}
+
+// path of the first layout: 1 = streaming kernel, 2 = tiled kernel, 3 = streaming kernel
+// over blocks of 64 rows (forced only)
+static int plan_path(int64_t M) { return g_knob[0] ? g_knob[0] : (M <= 64 ? 1 : 2); }
 
 }  // namespace qg
 
@@ -259,10 +312,7 @@ int qgemm(const void* A, const void* packed_W, const void* scales, const uint8_t
     return kLarge32[wt](p, route, g_knob[2], st);
   }
 
-  int path = g_knob[0];
-  if (path == 0) {
-    path = (M <= 64) ? 1 : 2;
-  }
+  const int path = plan_path(M);
   if (path == 1 && M > 64) return QG_EINVAL;
 
   if (path == 1 || path == 3) {
@@ -277,49 +327,14 @@ int qgemm(const void* A, const void* packed_W, const void* scales, const uint8_t
     return QG_OK;
   }
   if (!fits32) return QG_EUNSUPPORTED;
-  // Split-K for the lower row tiles when they would leave CUs idle.  Candidates: 64- or
-  // 128-row tiles, K cut into 1, 2, 4 or 8 slabs of an even number of chunks (the kernel
-  // works in pairs of chunks), at most one workgroup per CU when split.  Cost in
-  // microseconds, fitted to measurements at K = 1024 .. 8192, N = 2048 .. 14336:
-  // chunks per workgroup x time per chunk (1.33 at up to 4 bits, + 0.33 per bit above,
-  // x 1.13 for 128 rows) + for the exchange of partial sums 5 + 0.4 per MB with 64-row
-  // tiles, 11 + 0.6 per MB with 128-row tiles.
-  int bm = g_knob[2], splitk = g_knob[1];
-  const int KC = (int)(K / TILE_K);
-  const int64_t tiles_n = (N + 255) / 256;
-  if (bm == 0 && large_prefers_64_rows(M, N)) {
-    bm = 64;
-    if (splitk <= 0) {
-      const double tc = 1.33 + 0.33 * (t.bits > 4 ? t.bits - 4 : 0);
-      double best = 1e30;
-      for (int cand_bm = 64; cand_bm <= 128; cand_bm *= 2)
-        for (int sk = 1; sk <= 8; sk *= 2) {
-          const int64_t tiles_m = (M + cand_bm - 1) / cand_bm;
-          int cps = (KC + sk - 1) / sk;
-          if (sk > 1 && (cps & 1)) ++cps;
-          if (sk > 1 && (cps < 4 || tiles_m * tiles_n * sk > 256)) continue;
-          const double rounds = (double)((tiles_m * tiles_n * sk + 255) / 256);
-          const double mb = (double)sk * (double)(tiles_m * cand_bm) * (double)(tiles_n * 256) * 4.0 / 1e6;
-          const double cost = rounds * cps * tc * (cand_bm == 64 ? 1.0 : 1.13) +
-                              (sk > 1 ? (cand_bm == 64 ? 5.0 + 0.4 * mb : 11.0 + 0.6 * mb) : 0.0);
-          if (cost < best) { best = cost; bm = cand_bm; splitk = sk; }
-        }
-    }
-  }
-  if (splitk <= 0) splitk = 1;
-  if (bm == 64 || bm == 128) {
-    const int64_t tiles = ((M + bm - 1) / bm) * tiles_n;
-    if (splitk > KC) splitk = KC;
-    int cps = (KC + splitk - 1) / splitk;
-    if (splitk > 1 && (cps & 1)) ++cps;
-    splitk = (KC + cps - 1) / cps;
-    if (splitk > 1) {
-      Workspace* w = nullptr;
-      rc = get_workspace((size_t)splitk * (size_t)tiles * (size_t)(bm * 256) * sizeof(float), (size_t)tiles, st, &w);
-      if (rc != QG_OK) return rc;
-      p.ws = w->partial; p.tickets = w->tickets;
-      p.splitk = splitk; p.chunks_per_split = cps;
-    }
+  int bm;
+  plan_tiled(M, N, K, t.bits, &bm, &p.splitk, &p.chunks_per_split);
+  if (p.splitk > 1) {
+    const int64_t tiles = ((M + bm - 1) / bm) * ((N + 255) / 256);
+    Workspace* w = nullptr;
+    rc = get_workspace((size_t)p.splitk * (size_t)tiles * (size_t)(bm * 256) * sizeof(float), (size_t)tiles, st, &w);
+    if (rc != QG_OK) return rc;
+    p.ws = w->partial; p.tickets = w->tickets;
   }
   return kLarge[wt](p, route, bm, st);
 }
@@ -334,6 +349,20 @@ int qg_probe_mfma(int bf16, int random_data, int iters, int waves_per_simd, void
   // 8 instructions of 32*32*16*2 flop per iteration and wavefront, 4 wavefronts per block
   if (flops_out) *flops_out = 8.0 * 32768.0 * (double)iters * 4.0 * 256.0 * waves_per_simd;
   return launch_probe_mfma(bf16 != 0, random_data != 0, iters, waves_per_simd, sink, static_cast<hipStream_t>(stream));
+}
+
+int qg_plan(qg_wtype t, int layout, int act, int scale_dtype, int64_t group, int64_t M, int64_t N, int64_t K, int plan[5]) {
+  int wt, route;
+  int rc = check_common(t, layout, act, scale_dtype, group, K, N, &wt, &route);
+  if (rc != QG_OK) return rc;
+  if (M < 1 || M > (1 << 24) || !plan) return QG_EINVAL;
+  plan[0] = plan[1] = plan[2] = 0; plan[3] = 1; plan[4] = (int)(K / TILE_K);
+  if (layout == QG_LAYOUT_TILE128x64_R32) { plan[0] = 2; plan[2] = g_knob[2]; return QG_OK; }
+  plan[0] = plan_path(M);
+  if (plan[0] == 1 && M > 64) return QG_EINVAL;
+  if (plan[0] == 1 || plan[0] == 3) plan_streaming((int)(M < 64 ? M : 64), (int)N, (int)K, (int)group, wt, &plan[1], &plan[3], &plan[4]);
+  else plan_tiled(M, N, K, t.bits, &plan[2], &plan[3], &plan[4]);
+  return QG_OK;
 }
 
 int qg_set_knob(int knob, int value) {

@@ -1,0 +1,91 @@
+"""Host logic: which kernel, tile height, wavefront arrangement and split-K the
+library picks for a shape (qg_plan: arithmetic only, runs without a GPU).
+Checks the invariants the kernels rely on and the choices the measurements in
+the design notes were taken with."""
+import pytest
+
+from paper_2504_12984_amd import binding as B
+
+U4 = B.WType(B.QG_UINT, 4)
+U3 = B.WType(B.QG_UINT, 3)
+U8 = B.WType(B.QG_UINT, 8)
+
+
+@pytest.fixture(autouse=True)
+def _reset_knobs():
+    yield
+    for k in range(4):
+        B.qg_set_knob(k, 0)
+
+
+def test_small_m_streams_and_large_m_tiles():
+    assert B.qg_plan(U4, 128, 1, 14336, 4096)["path"] == 1
+    assert B.qg_plan(U4, 128, 64, 14336, 4096)["path"] == 1
+    assert B.qg_plan(U4, 128, 65, 14336, 4096)["path"] == 2
+    assert B.qg_plan(U4, 128, 4096, 57344, 8192) == {"path": 2, "variant": 0, "row_tile": 0, "splitk": 1,
+                                                     "chunks_per_slab": 64}
+
+
+def test_streaming_arrangements_of_the_named_workloads():
+    # W3A16 decode: 224 strips, 32 chunks -> 16 wavefronts on one strip, no split
+    p = B.qg_plan(U3, 128, 16, 14336, 4096)
+    assert (p["variant"], p["splitk"]) == (12, 1)
+    # signed sweep shape: 448 strips, long K -> two strips per workgroup, 16 wavefronts up to 6 bits, 8 above
+    assert B.qg_plan(U4, 128, 16, 28672, 8192)["variant"] == 15
+    assert B.qg_plan(U8, 128, 16, 28672, 8192)["variant"] == 14
+    assert B.qg_plan(U4, 64, 16, 28672, 8192)["variant"] == 14      # two groups per chunk need the registers
+    # type sweep shape: 896 strips -> four strips per workgroup
+    assert B.qg_plan(U4, 128, 16, 57344, 8192)["variant"] == 16
+    # K = N = 8192: 128 strips cannot fill 256 CUs -> K is split over workgroups
+    p = B.qg_plan(U4, 128, 1, 8192, 8192)
+    assert p["variant"] == 12 and p["splitk"] == 2 and p["chunks_per_slab"] == 32
+    # 17..32 and 33..64 rows: 2 and 4 row tiles per wavefront
+    assert B.qg_plan(U4, 128, 32, 8192, 8192)["variant"] // 10 == 2
+    assert B.qg_plan(U4, 128, 64, 8192, 8192)["variant"] // 10 == 4
+
+
+@pytest.mark.parametrize("bits", [1, 4, 6, 8])
+@pytest.mark.parametrize("K", [128, 384, 1024, 1408, 4096, 8192])
+@pytest.mark.parametrize("N", [64, 2048, 8192, 14336, 57344])
+@pytest.mark.parametrize("M", [65, 96, 128, 200, 256, 384, 512, 768, 1024, 4096])
+def test_tiled_plan_invariants(M, N, K, bits):
+    p = B.qg_plan(B.WType(B.QG_UINT, bits), 128, M, N, K)
+    KC = K // 128
+    assert p["path"] == 2 and p["row_tile"] in (0, 64, 128)
+    sk, cps = p["splitk"], p["chunks_per_slab"]
+    assert 1 <= sk <= 8 and sk * cps >= KC > (sk - 1) * cps          # slabs cover K, none is empty
+    if sk > 1:
+        assert p["row_tile"] in (64, 128)                            # 256-row tiles are never split
+        assert cps % 2 == 0 and cps >= 4                             # whole pairs of chunks
+        tiles = -(-M // p["row_tile"]) * -(-N // 256)
+        assert tiles * sk <= 256                                     # one workgroup per CU at most
+    if p["row_tile"] == 0:
+        assert -(-M // 128) * -(-N // 256) > 128                     # big enough to fill the chip unsplit
+
+
+def test_split_k_choices_of_the_measured_shapes():
+    # K = N = 8192, 4-bit (the table in the design notes)
+    got = {M: B.qg_plan(U4, 128, M, 8192, 8192) for M in (128, 256, 512)}
+    assert (got[128]["row_tile"], got[128]["splitk"]) == (64, 4)
+    assert (got[256]["row_tile"], got[256]["splitk"]) in ((64, 2), (128, 4))
+    assert (got[512]["row_tile"], got[512]["splitk"]) == (128, 2)
+    # short K: nothing to split
+    assert B.qg_plan(U4, 128, 128, 8192, 1024)["splitk"] == 1
+
+
+def test_knobs_force_the_plan_and_bad_arguments_are_rejected():
+    B.qg_set_knob(0, 2); B.qg_set_knob(2, 128); B.qg_set_knob(1, 3)
+    p = B.qg_plan(U4, 128, 40, 320, 1408)                            # 11 chunks in 3 slabs of 4
+    assert (p["path"], p["row_tile"], p["splitk"], p["chunks_per_slab"]) == (2, 128, 3, 4)
+    B.qg_set_knob(2, 256)
+    assert B.qg_plan(U4, 128, 400, 320, 1408)["splitk"] == 1         # 256-row tiles are not split
+    B.qg_set_knob(0, 1)
+    with pytest.raises(Exception):
+        B.qg_plan(U4, 128, 65, 320, 1408)                            # streaming kernel forced beyond 64 rows
+    for k in range(4):
+        B.qg_set_knob(k, 0)
+    with pytest.raises(Exception):
+        B.qg_plan(U4, 128, 16, 100, 1408)                            # N not a multiple of 64
+    with pytest.raises(Exception):
+        B.qg_plan(U4, 96, 16, 128, 1408)                             # group does not divide K
+    assert B.qg_plan(U4, 128, 300, 512, 1024, layout=B.QG_LAYOUT_TILE128x64_R32)["path"] == 2
