@@ -332,7 +332,7 @@ int qgemm(const void* A, const void* packed_W, const void* scales, const uint8_t
   if (p.splitk > 1) {
     const int64_t tiles = ((M + bm - 1) / bm) * ((N + 255) / 256);
     Workspace* w = nullptr;
-    rc = get_workspace((size_t)p.splitk * (size_t)tiles * (size_t)(bm * 256) * sizeof(float), (size_t)tiles, st, &w);
+    rc = get_workspace((size_t)p.splitk * (size_t)tiles * (size_t)(bm * 256) * sizeof(float), (size_t)tiles * 4, st, &w);   // a ticket per 64-column strip
     if (rc != QG_OK) return rc;
     p.ws = w->partial; p.tickets = w->tickets;
   }

@@ -360,19 +360,25 @@ __global__ __launch_bounds__(256) void large_kernel(GemmParams p, int tiles_m, i
   // Partial sums cross workgroups (and XCDs, whose L2s are not coherent with each other)
   // through 16-byte buffer stores and loads that carry the sc1 cache-policy bit, which is
   // what a device-scope relaxed atomic store / load compiles to on this target: the store
-  // writes through, the load bypasses the local caches.  My stores complete, barrier, one
-  // arrival count per workgroup; the workgroup that counts splitk-1 earlier arrivals sums
-  // all slabs in slab order, so the result does not depend on arrival order.  Only the
-  // lower tiles use this (the host never splits 256-row tiles).
+  // writes through, the load bypasses the local caches.  Every wavefront handles its own
+  // 64-column strip of the tile by itself (no workgroup barrier after the main loop): its
+  // stores complete, lane 0 draws a ticket of that strip, and the wavefront that draws the
+  // last of the splitk tickets sums all slabs in slab order -- the result does not depend
+  // on arrival order.  The read-back is the expensive part (measured: one CU sustains only
+  // about 60 GB/s of such loads, and the four strips of a tile are in practice finished by
+  // the same, slowest workgroup), which is what the host's cost model charges per MB.
+  // Only the lower tiles use this (the host never splits 256-row tiles).
   if constexpr (BM <= 128) {
     if (p.splitk > 1) {
+      if (!active) return;
       constexpr int SC1 = 16;                                   // cache policy: device coherence
       constexpr int TILE_BYTES = BM * LARGE_BN * 4;
       auto ws_rsrc = [&](int sp) __attribute__((always_inline)) {
         return __builtin_amdgcn_make_buffer_rsrc(p.ws + ((int64_t)tile * p.splitk + sp) * (BM * LARGE_BN), 0, TILE_BYTES, 0x00020000);
       };
       // lane layout of a partial tile: fragment (mt, nt) of thread tid at 16 * ((mt*4+nt)*256 + tid)
-      if (active) {
+#ifndef QG_DBG_NOEXSTORE
+      {
         const __amdgpu_buffer_rsrc_t mine = ws_rsrc(slab);
 #pragma unroll
         for (int mt = 0; mt < MTS; ++mt)
@@ -382,41 +388,44 @@ __global__ __launch_bounds__(256) void large_kernel(GemmParams p, int tiles_m, i
               __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u4_t, acc[mt][nt]), mine, 16 * tid, (mt * 4 + nt) * 4096, SC1);
           }
       }
-      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // a workgroup barrier alone does not wait for global stores
-      __syncthreads();
-      unsigned* s_last = reinterpret_cast<unsigned*>(lds);          // the A slabs are dead by now
-      if (tid == 0)
-        *s_last = (__hip_atomic_fetch_add(&p.tickets[tile], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (unsigned)(p.splitk - 1));
-      __syncthreads();
-      if (!*s_last) return;
+#endif
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");           // my partial strip is out before my ticket is drawn
+      unsigned* ticket = p.tickets + 4 * tile + w;
+      unsigned drawn = 0;
+      if (l == 0) drawn = __hip_atomic_fetch_add(ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      drawn = __builtin_amdgcn_readfirstlane(drawn);
+      if (drawn != (unsigned)(p.splitk - 1)) return;
 #pragma unroll
       for (int mt = 0; mt < MTS; ++mt)
 #pragma unroll
         for (int nt = 0; nt < 4; ++nt) acc[mt][nt] = (f4_t){0.f, 0.f, 0.f, 0.f};
-      if (active) {
-        // two slabs' loads are in flight together (the second of an odd count is a repeat
-        // of the last slab whose values are dropped)
-        for (int sp = 0; sp < p.splitk; sp += 2) {
-          const bool two = sp + 1 < p.splitk;
-          const __amdgpu_buffer_rsrc_t r0 = ws_rsrc(sp), r1 = ws_rsrc(two ? sp + 1 : sp);
-          u4_t v0[MTS][4], v1[MTS][4];
+#if !defined(QG_DBG_NOEXLOAD) && !defined(QG_DBG_NOEXSTORE)
+      // two slabs' loads are in flight together (the second of an odd count is a repeat
+      // of the last slab whose values are dropped)
+      for (int sp = 0; sp < p.splitk; sp += 2) {
+        const bool two = sp + 1 < p.splitk;
+        const __amdgpu_buffer_rsrc_t r0 = ws_rsrc(sp), r1 = ws_rsrc(two ? sp + 1 : sp);
+        u4_t v0[MTS][4], v1[MTS][4];
 #pragma unroll
-          for (int mt = 0; mt < MTS; ++mt)
+        for (int mt = 0; mt < MTS; ++mt)
 #pragma unroll
-            for (int nt = 0; nt < 4; ++nt) {
+          for (int nt = 0; nt < 4; ++nt) {
+            v0[mt][nt] = v1[mt][nt] = (u4_t){0u, 0u, 0u, 0u};
+            if (m0 + mt * 16 + i16 < p.M) {                       // rows past M were not written
               v0[mt][nt] = __builtin_amdgcn_raw_buffer_load_b128(r0, 16 * tid, (mt * 4 + nt) * 4096, SC1);
               v1[mt][nt] = __builtin_amdgcn_raw_buffer_load_b128(r1, 16 * tid, (mt * 4 + nt) * 4096, SC1);
             }
+          }
 #pragma unroll
-          for (int mt = 0; mt < MTS; ++mt)
+        for (int mt = 0; mt < MTS; ++mt)
 #pragma unroll
-            for (int nt = 0; nt < 4; ++nt) {
-              acc[mt][nt] += __builtin_bit_cast(f4_t, v0[mt][nt]);
-              if (two) acc[mt][nt] += __builtin_bit_cast(f4_t, v1[mt][nt]);
-            }
-        }
+          for (int nt = 0; nt < 4; ++nt) {
+            acc[mt][nt] += __builtin_bit_cast(f4_t, v0[mt][nt]);
+            if (two) acc[mt][nt] += __builtin_bit_cast(f4_t, v1[mt][nt]);
+          }
       }
-      if (tid == 0) __hip_atomic_store(&p.tickets[tile], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next call
+#endif
+      if (l == 0) __hip_atomic_store(ticket, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next call
     }
   }
 
