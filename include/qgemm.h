@@ -28,9 +28,13 @@
  *     default stream) and the call returns without synchronising;
  *   - the return value is a qg_status (0 = ok, negative = error, nothing was
  *     enqueued); no call throws, none frees caller memory;
- *   - qgemm may use a library-owned, lazily grown per-device workspace for
- *     split-K partial sums; it is ordered on `stream`, so two qgemm calls that
- *     overlap on DIFFERENT streams of one device race on it.
+ *   - qgemm may use a library-owned, lazily grown workspace for split-K partial
+ *     sums: one per (device, stream), allocated on the first call that needs it
+ *     (hipMalloc; growing one synchronises the device) and kept until the
+ *     process ends, so calls on different streams may overlap.  At most 32
+ *     (device, stream) pairs per process (QG_EUNSUPPORTED beyond); a stream
+ *     that is destroyed and whose handle value is re-used simply inherits the
+ *     workspace.
  *
  * De-quantisation (the paper names the step but prints no formula; this is the
  * standard affine group form):

@@ -50,23 +50,36 @@ static int hip_fail(hipError_t e, const char* what) {
   return QG_EHIP;
 }
 
-// ---- per-device split-K workspace (partial sums + arrival counters) ------------
+// ---- split-K workspace (partial sums + arrival counters), one per device and stream -----
+// Kernels of one stream run in order, so they can share a workspace; kernels of different
+// streams may overlap, so each stream gets its own (created on first use, never freed:
+// at most 32 per process).
 struct Workspace {
+  int dev = -1;
+  hipStream_t stream = nullptr;
   float* partial = nullptr;
   size_t partial_bytes = 0;
   unsigned* tickets = nullptr;
   size_t ticket_count = 0;
 };
 static std::mutex g_ws_mutex;
-static Workspace g_ws[64];
+static Workspace g_ws[32];
+static int g_ws_used = 0;
 
 static int get_workspace(size_t partial_bytes, size_t ticket_count, hipStream_t st, Workspace** out) {
   int dev = 0;
   hipError_t e = hipGetDevice(&dev);
   if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
-  if (dev < 0 || dev >= 64) return QG_EINVAL;
   std::lock_guard<std::mutex> lock(g_ws_mutex);
-  Workspace& w = g_ws[dev];
+  Workspace* found = nullptr;
+  for (int i = 0; i < g_ws_used; ++i)
+    if (g_ws[i].dev == dev && g_ws[i].stream == st) { found = &g_ws[i]; break; }
+  if (!found) {
+    if (g_ws_used == 32) { g_last_error = "split-K workspaces for more than 32 (device, stream) pairs"; return QG_EUNSUPPORTED; }
+    found = &g_ws[g_ws_used++];
+    found->dev = dev; found->stream = st;
+  }
+  Workspace& w = *found;
   if (w.partial_bytes < partial_bytes) {
     // work already enqueued may still read the old buffer
     if (w.partial) { e = hipDeviceSynchronize(); if (e != hipSuccess) return hip_fail(e, "hipDeviceSynchronize"); (void)hipFree(w.partial); w.partial = nullptr; w.partial_bytes = 0; }

@@ -248,6 +248,31 @@ def test_tiled_path_split_into_whole_rounds_plus_remainder(layout):
 
 
 # ------------------------------------------------------------------ binding extras
+def test_split_k_calls_on_two_streams_keep_separate_workspaces():
+    # a streaming split-K matmul and a tiled split-K matmul enqueued alternately on two
+    # streams (free to overlap) must give the bits they give alone on the default stream
+    from paper_2504_12984_amd import binding as B
+    small = WL.Case("streams_small", 16, 8192, 2048, U, 4, group=128, zero=8, seed=8950)
+    mid = WL.Case("streams_mid", 128, 8192, 2048, U, 4, group=128, act="bf16", scale_dtype="bf16", zero=8, seed=8951)
+    P1, P2 = Prepared(small), Prepared(mid)
+    assert B.qg_plan(P1.wtype, 128, 16, 2048, 8192)["splitk"] > 1
+    assert B.qg_plan(P2.wtype, 128, 128, 2048, 8192, act=B.QG_BF16)["splitk"] > 1
+    alone1, alone2 = P1.gpu_c(), P2.gpu_c()
+    assert_c_close(alone1, P1.oracle_c(), small.name)
+    assert_c_close(alone2, P2.oracle_c(), mid.name)
+    torch.cuda.synchronize()
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    outs = []
+    for _ in range(10):
+        with torch.cuda.stream(s1):
+            outs.append((P1.gpu_c(), alone1))
+        with torch.cuda.stream(s2):
+            outs.append((P2.gpu_c(), alone2))
+    torch.cuda.synchronize()
+    for got, want in outs:
+        assert np.array_equal(bits_of(got), bits_of(want))
+
+
 def test_bound_call_gives_the_same_bits_as_the_plain_call_and_checks_its_arguments():
     from paper_2504_12984_amd import binding as B
     case = WL.Case("bound", 7, 640, 192, U, 4, group=128, zero=8, seed=9100)
