@@ -112,10 +112,11 @@ QG_API int repack(const void* canonical, qg_wtype t, int layout, int64_t K, int6
 /* W_out[K,N] (row-major, `act` dtype) = rounded de-quantised weights.
  *   scales [K/group, N] row-major, dtype `scale_dtype`
  *   zeros  [K/group, N] row-major uint8, or NULL for zero-point 0
- *   group  rows of W per scale: a multiple of 32 that divides 128 or is a
- *          multiple of 128, dividing K (K itself = one scale per column)
+ *   group  rows of W per scale, dividing K: 64, 128 * 2^s, or K itself (= one scale per
+ *          output column; 0 means the same).  32 and 128 * odd (other than K) are valid
+ *          group sizes this build has no kernel for: QG_EUNSUPPORTED.
  * QG_EINVAL on shape/group violations, QG_EUNSUPPORTED on an unsupported
- * float split. */
+ * float split or group size. */
 QG_API int qdequant(const void* packed_W, const void* scales, const uint8_t* zeros, qg_wtype t,
              int layout, int act, int scale_dtype, int64_t group, int64_t K, int64_t N,
              void* W_out, void* stream);

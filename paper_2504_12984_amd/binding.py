@@ -155,9 +155,10 @@ def qgemm(A: torch.Tensor, packed: torch.Tensor, scales: torch.Tensor, zeros, t:
     if A.dim() != 2 or A.dtype not in _DT:
         raise ValueError("A must be [M,K] fp16 or bf16")
     M, K = A.shape
-    if scales.dtype not in _DT or tuple(scales.shape) != (K // group, N):
+    rows = K // group if group > 0 else 1                    # group 0 = one scale per output column
+    if scales.dtype not in _DT or tuple(scales.shape) != (rows, N):
         raise ValueError("scales must be [K/group, N] fp16 or bf16")
-    if zeros is not None and (zeros.dtype != torch.uint8 or tuple(zeros.shape) != (K // group, N)):
+    if zeros is not None and (zeros.dtype != torch.uint8 or tuple(zeros.shape) != (rows, N)):
         raise ValueError("zeros must be uint8 [K/group, N]")
     if out is None:
         out = torch.empty((M, N), dtype=A.dtype, device=A.device)
@@ -183,9 +184,10 @@ class BoundQgemm:
         if A.dim() != 2 or A.dtype not in _DT:
             raise ValueError("A must be [M,K] fp16 or bf16")
         M, K = A.shape
-        if scales.dtype not in _DT or tuple(scales.shape) != (K // group, N):
+        rows = K // group if group > 0 else 1                    # group 0 = one scale per output column
+        if scales.dtype not in _DT or tuple(scales.shape) != (rows, N):
             raise ValueError("scales must be [K/group, N] fp16 or bf16")
-        if zeros is not None and (zeros.dtype != torch.uint8 or tuple(zeros.shape) != (K // group, N)):
+        if zeros is not None and (zeros.dtype != torch.uint8 or tuple(zeros.shape) != (rows, N)):
             raise ValueError("zeros must be uint8 [K/group, N]")
         if tuple(out.shape) != (M, N) or out.dtype != A.dtype:
             raise ValueError("out must be [M,N] of A's dtype")

@@ -274,6 +274,7 @@ int repack(const void* canonical, qg_wtype t, int layout, int64_t K, int64_t N, 
 
 int qdequant(const void* packed_W, const void* scales, const uint8_t* zeros, qg_wtype t, int layout, int act,
              int scale_dtype, int64_t group, int64_t K, int64_t N, void* W_out, void* stream) {
+  if (group == 0) group = K;               // 0 = one scale per output column
   int wt, route;
   int rc = check_common(t, layout, act, scale_dtype, group, K, N, &wt, &route);
   if (rc != QG_OK) return rc;
@@ -293,6 +294,7 @@ int qdequant(const void* packed_W, const void* scales, const uint8_t* zeros, qg_
 
 int qgemm(const void* A, const void* packed_W, const void* scales, const uint8_t* zeros, qg_wtype t, int layout,
           int act, int scale_dtype, int64_t group, int64_t M, int64_t N, int64_t K, void* C, void* stream) {
+  if (group == 0) group = K;               // 0 = one scale per output column
   int wt, route;
   int rc = check_common(t, layout, act, scale_dtype, group, K, N, &wt, &route);
   if (rc != QG_OK) return rc;
@@ -365,6 +367,7 @@ int qg_probe_mfma(int bf16, int random_data, int iters, int waves_per_simd, void
 }
 
 int qg_plan(qg_wtype t, int layout, int act, int scale_dtype, int64_t group, int64_t M, int64_t N, int64_t K, int plan[5]) {
+  if (group == 0) group = K;               // 0 = one scale per output column
   int wt, route;
   int rc = check_common(t, layout, act, scale_dtype, group, K, N, &wt, &route);
   if (rc != QG_OK) return rc;

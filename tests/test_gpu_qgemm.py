@@ -273,6 +273,19 @@ def test_split_k_calls_on_two_streams_keep_separate_workspaces():
         assert np.array_equal(bits_of(got), bits_of(want))
 
 
+def test_group_zero_means_one_scale_per_output_column():
+    from paper_2504_12984_amd import binding as B
+    from gpu_util import ACT
+    case = WL.Case("group0", 20, 512, 128, U, 4, group=512, act="bf16", scale_dtype="bf16", zero=8, seed=8960)
+    P = Prepared(case)
+    ref = P.oracle_c()
+    C0 = B.qgemm(P.d_A, P.packed(0), P.d_scales, P.d_zeros, P.wtype, 0, case.N)
+    assert_c_close(C0, ref, case.name)
+    assert np.array_equal(bits_of(C0), bits_of(P.gpu_c()))
+    W0 = B.qdequant(P.packed(0), P.d_scales, P.d_zeros, P.wtype, ACT[case.act], 0, case.K, case.N)
+    assert np.array_equal(bits_of(W0), bits_of(P.gpu_w(0)))
+
+
 def test_bound_call_gives_the_same_bits_as_the_plain_call_and_checks_its_arguments():
     from paper_2504_12984_amd import binding as B
     case = WL.Case("bound", 7, 640, 192, U, 4, group=128, zero=8, seed=9100)
