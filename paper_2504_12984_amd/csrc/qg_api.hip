@@ -115,7 +115,7 @@ static int check_common(qg_wtype t, int layout, int act, int scale_dtype, int64_
   if (wt < 0) return QG_EINVAL;
   if (K <= 0 || N <= 0 || K % TILE_K || N % TILE_N || K > (1 << 24) || N > (1 << 24)) return QG_EINVAL;
   if (group <= 0 || K % group) return QG_EINVAL;
-  if (!((group % TILE_K) == 0 || group == 64)) return (group % 32 == 0 && TILE_K % group == 0) ? QG_EUNSUPPORTED : QG_EINVAL;
+  if (!((group % TILE_K) == 0 || group == 64 || group == 32)) return QG_EINVAL;
   if ((act != QG_F16 && act != QG_BF16) || (scale_dtype != QG_F16 && scale_dtype != QG_BF16)) return QG_EINVAL;
   if (act == QG_F16 && scale_dtype == QG_BF16) return QG_EUNSUPPORTED;
   *wt_out = wt;
@@ -146,6 +146,7 @@ static void plan_streaming(int M, int N, int K, int group, int wt, int* variant_
   // K = N = 8192: 11 % and 7 % shorter at 4 bits, no gain at 8)
   if (variant == 11 && KC > 32 && NCH < 256) variant = wt_bits(wt) <= 4 ? 12 : (wt_bits(wt) <= 6 ? 10 : 11);
   if (g_knob[3] > 0) variant = g_knob[3];
+  if (group == 32) variant = 10 * mt + 1;          // four groups per chunk: the 4-wavefront arrangements only
   const int waves = kDecodeWaves[wt](variant);
   // Split K over workgroups only when the column strips alone cannot fill the
   // 256 CUs, and never below 4 chunks per wavefront (2 with 16 wavefronts per strip).
@@ -221,7 +222,11 @@ static void plan_tiled(int64_t M, int64_t N, int64_t K, int bits, int* bm_out, i
 
 // path of the first layout: 1 = streaming kernel, 2 = tiled kernel, 3 = streaming kernel
 // over blocks of 64 rows (forced only)
-static int plan_path(int64_t M) { return g_knob[0] ? g_knob[0] : (M <= 64 ? 1 : 2); }
+// (group size 32 has no tiled kernel: larger M run the streaming kernel over row blocks)
+static int plan_path(int64_t M, int64_t group) {
+  if (g_knob[0]) return g_knob[0];
+  return M <= 64 ? 1 : (group == 32 ? 3 : 2);
+}
 
 }  // namespace qg
 
@@ -323,11 +328,11 @@ int qgemm(const void* A, const void* packed_W, const void* scales, const uint8_t
                       (uint64_t)K * (uint64_t)N / 8u * (uint64_t)t.bits < (1ull << 32) &&
                       (uint64_t)(K / group) * (uint64_t)N * 2u < (1ull << 32);
   if (layout == QG_LAYOUT_TILE128x64_R32) {      // one kernel for every M
-    if (!fits32) return QG_EUNSUPPORTED;
+    if (!fits32 || group == 32) return QG_EUNSUPPORTED;      // no tiled kernel for four groups per chunk
     return kLarge32[wt](p, route, g_knob[2], st);
   }
 
-  const int path = plan_path(M);
+  const int path = plan_path(M, group);
   if (path == 1 && M > 64) return QG_EINVAL;
 
   if (path == 1 || path == 3) {
@@ -341,7 +346,7 @@ int qgemm(const void* A, const void* packed_W, const void* scales, const uint8_t
     }
     return QG_OK;
   }
-  if (!fits32) return QG_EUNSUPPORTED;
+  if (!fits32 || group == 32) return QG_EUNSUPPORTED;        // group 32: streaming kernel only (forced path 2)
   int bm;
   plan_tiled(M, N, K, t.bits, &bm, &p.splitk, &p.chunks_per_split);
   if (p.splitk > 1) {
@@ -373,8 +378,9 @@ int qg_plan(qg_wtype t, int layout, int act, int scale_dtype, int64_t group, int
   if (rc != QG_OK) return rc;
   if (M < 1 || M > (1 << 24) || !plan) return QG_EINVAL;
   plan[0] = plan[1] = plan[2] = 0; plan[3] = 1; plan[4] = (int)(K / TILE_K);
-  if (layout == QG_LAYOUT_TILE128x64_R32) { plan[0] = 2; plan[2] = g_knob[2]; return QG_OK; }
-  plan[0] = plan_path(M);
+  if (layout == QG_LAYOUT_TILE128x64_R32) { plan[0] = 2; plan[2] = g_knob[2]; return group == 32 ? QG_EUNSUPPORTED : QG_OK; }
+  plan[0] = plan_path(M, group);
+  if (plan[0] == 2 && group == 32) return QG_EUNSUPPORTED;
   if (plan[0] == 1 && M > 64) return QG_EINVAL;
   if (plan[0] == 1 || plan[0] == 3) plan_streaming((int)(M < 64 ? M : 64), (int)N, (int)K, (int)group, wt, &plan[1], &plan[3], &plan[4]);
   else plan_tiled(M, N, K, t.bits, &plan[2], &plan[3], &plan[4]);

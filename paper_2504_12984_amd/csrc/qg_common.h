@@ -120,7 +120,7 @@ struct GemmParams {
   int splitk;           // number of K-slabs (grid.y)
   int chunks_per_split; // K-chunks per slab (last slab may be shorter)
   // group index of K-chunk c without a division: group 64 -> 2c (two groups per
-  // chunk); group 128*2^s -> (c >> gshift) & gmask, with gmask 0 when one group
+  // chunk), group 32 -> 4c (four); group 128*2^s -> (c >> gshift) & gmask, with gmask 0 when one group
   // spans all of K
   int gshift, gmask;
 };
@@ -128,7 +128,7 @@ struct GemmParams {
 // Fills gshift/gmask; false if the group size has no shift form (128 * odd, != K).
 inline bool set_group_index(GemmParams& p) {
   p.gshift = 0; p.gmask = ~0;
-  if (p.group == 64) return true;
+  if (p.group == 64 || p.group == 32) return true;
   if (p.group == p.K) { p.gmask = 0; return true; }
   int q = p.group / TILE_K;
   if (q < 1 || p.group % TILE_K || (q & (q - 1))) return false;

@@ -59,7 +59,7 @@ __device__ __forceinline__ uint32_t pack_out(float lo, float hi) {
   else return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, b2_t));
 }
 
-template <int WT, int ROUTE, bool TWO_GROUPS, int NW, int DEPTH, int MT, int NS = 1>
+template <int WT, int ROUTE, int GPC, int NW, int DEPTH, int MT, int NS = 1>
 __global__ __launch_bounds__(NW * 64) void decode_kernel(GemmParams p) {
   // NS adjacent strips per workgroup, NK wavefronts along K for each: wavefront w
   // works on strip w % NS and takes every NK-th chunk of the slab starting at
@@ -93,8 +93,8 @@ __global__ __launch_bounds__(NW * 64) void decode_kernel(GemmParams p) {
   struct Stage {
     uint32_t r[RAW];
     u4_t a[MT][4];
-    uint2 s0, s1;
-    uint32_t z0, z1;
+    uint2 s[GPC];          // GPC groups per chunk (group size 128 or more: 1; 64: 2; 32: 4)
+    uint32_t z[GPC];
   };
   Stage st[DEPTH];
 
@@ -116,20 +116,20 @@ __global__ __launch_bounds__(NW * 64) void decode_kernel(GemmParams p) {
       s.r[4 * i + 0] = q.x; s.r[4 * i + 1] = q.y; s.r[4 * i + 2] = q.z; s.r[4 * i + 3] = q.w;
     }
 #ifdef QG_DBG_NOSZ
-    s.s0 = make_uint2(0x3c003c00u, 0x3c003c00u); s.s1 = s.s0; s.z0 = 0x04040404u; s.z1 = s.z0;
+#pragma unroll
+    for (int g = 0; g < GPC; ++g) { s.s[g] = make_uint2(0x3c003c00u, 0x3c003c00u); s.z[g] = 0x04040404u; }
     __builtin_amdgcn_sched_barrier(0);
     return;
 #endif
-    const int g0 = (p.group == 64) ? 2 * c : ((c >> p.gshift) & p.gmask);
+    const int g0 = (GPC > 1) ? GPC * c : ((c >> p.gshift) & p.gmask);
 #ifdef QG_SZ_BCAST
     if (b == 0) {
 #endif
-    s.s0 = *reinterpret_cast<const uint2*>(p.S + (int64_t)g0 * p.N + n0);
-    if constexpr (TWO_GROUPS) {
-      s.s1 = *reinterpret_cast<const uint2*>(p.S + (int64_t)(g0 + 1) * p.N + n0);
-      s.z1 = *reinterpret_cast<const uint32_t*>(zbase + (int64_t)(g0 + 1) * p.N + n0);
+#pragma unroll
+    for (int g = 0; g < GPC; ++g) {
+      s.s[g] = *reinterpret_cast<const uint2*>(p.S + (int64_t)(g0 + g) * p.N + n0);
+      s.z[g] = *reinterpret_cast<const uint32_t*>(zbase + (int64_t)(g0 + g) * p.N + n0);
     }
-    s.z0 = *reinterpret_cast<const uint32_t*>(zbase + (int64_t)g0 * p.N + n0);
 #ifdef QG_SZ_BCAST
     }
 #endif
@@ -154,29 +154,28 @@ __global__ __launch_bounds__(NW * 64) void decode_kernel(GemmParams p) {
   auto compute = [&](auto Sc) __attribute__((always_inline)) {
     constexpr int S = decltype(Sc)::value;
     Stage& s = st[S];
-    typename D::Consts gc0, gc1;
+    typename D::Consts gc[GPC];
 #ifdef QG_SZ_BCAST
     {
       const int ba = 4 * i16;
-      s.s0.x = __builtin_amdgcn_ds_bpermute(ba, s.s0.x); s.s0.y = __builtin_amdgcn_ds_bpermute(ba, s.s0.y);
-      s.z0 = __builtin_amdgcn_ds_bpermute(ba, s.z0);
-      if constexpr (TWO_GROUPS) {
-        s.s1.x = __builtin_amdgcn_ds_bpermute(ba, s.s1.x); s.s1.y = __builtin_amdgcn_ds_bpermute(ba, s.s1.y);
-        s.z1 = __builtin_amdgcn_ds_bpermute(ba, s.z1);
+#pragma unroll
+      for (int g = 0; g < GPC; ++g) {
+        s.s[g].x = __builtin_amdgcn_ds_bpermute(ba, s.s[g].x); s.s[g].y = __builtin_amdgcn_ds_bpermute(ba, s.s[g].y);
+        s.z[g] = __builtin_amdgcn_ds_bpermute(ba, s.z[g]);
       }
     }
 #endif
-    D::make_consts(gc0, s.s0, s.z0 & zmask, p.zbias, p.scale_bf16);
-    if constexpr (TWO_GROUPS) D::make_consts(gc1, s.s1, s.z1 & zmask, p.zbias, p.scale_bf16);
+#pragma unroll
+    for (int g = 0; g < GPC; ++g) D::make_consts(gc[g], s.s[g], s.z[g] & zmask, p.zbias, p.scale_bf16);
     static_for<4>([&](auto Jc) __attribute__((always_inline)) {
       constexpr int J = decltype(Jc)::value;
       static_for<4>([&](auto NTc) __attribute__((always_inline)) {
         constexpr int NT = decltype(NTc)::value;
         uint32_t o[4];
 #ifdef QG_DBG_NODECODE
-        o[0] = s.r[(J * 4 + NT) % RAW]; o[1] = s.r[(J * 4 + NT + 1) % RAW]; o[2] = s.r[(J * 4 + NT + 2) % RAW]; o[3] = s.r[(J * 4 + NT + 3) % RAW] ^ s.s0.x ^ s.z0;
+        o[0] = s.r[(J * 4 + NT) % RAW]; o[1] = s.r[(J * 4 + NT + 1) % RAW]; o[2] = s.r[(J * 4 + NT + 2) % RAW]; o[3] = s.r[(J * 4 + NT + 3) % RAW] ^ s.s[0].x ^ s.z[0];
 #else
-        D::template frag<J, NT>(s.r, (TWO_GROUPS && J >= 2) ? gc1 : gc0, u, o);
+        D::template frag<J, NT>(s.r, gc[J * GPC / 4], u, o);          // k-step J lies in group J*GPC/4 of the chunk
 #endif
         const u4_t wf = {o[0], o[1], o[2], o[3]};      // unpacked once, used by every row tile
 #ifdef QG_DBG_NOMFMA
@@ -318,29 +317,37 @@ __global__ __launch_bounds__(NW * 64) void decode_kernel(GemmParams p) {
 #define QG_CAT2(a, b) a##b
 #define QG_CAT(a, b) QG_CAT2(a, b)
 
-template <int ROUTE, bool TG, int NW, int DEPTH, int MT, int NS = 1>
+template <int ROUTE, int GPC, int NW, int DEPTH, int MT, int NS = 1>
 static int launch_cfg(const GemmParams& p, hipStream_t st) {
   if ((p.N / TILE_N) % NS) return QG_EINVAL;
-  auto kern = decode_kernel<QG_WT, ROUTE, TG, NW, DEPTH, MT, NS>;
+  auto kern = decode_kernel<QG_WT, ROUTE, GPC, NW, DEPTH, MT, NS>;
   dim3 grid((unsigned)(p.N / TILE_N / NS), (unsigned)p.splitk), block(NW * 64);
   hipLaunchKernelGGL(kern, grid, block, 0, st, p);
   return hipGetLastError() == hipSuccess ? QG_OK : QG_EHIP;
 }
 
 // variant = 10 * (row tiles: 1, 2, 4) + (0: 8 wavefronts per strip, 1: 4 wavefronts, 2: 16 wavefronts)
-template <int ROUTE, bool TG>
+template <int ROUTE, int GPC>
 static int launch_variant(const GemmParams& p, int variant, hipStream_t st) {
+  if constexpr (GPC == 4) {          // group size 32: the 4-wavefront arrangements only
+    switch (variant) {
+      case 11: return launch_cfg<ROUTE, 4, 4, 2, 1>(p, st);
+      case 21: return launch_cfg<ROUTE, 4, 4, 2, 2>(p, st);
+      case 41: return launch_cfg<ROUTE, 4, 4, 2, 4>(p, st);
+      default: return QG_EINVAL;
+    }
+  }
   switch (variant) {
-    case 10: return launch_cfg<ROUTE, TG, 8, 2, 1>(p, st);
-    case 11: return launch_cfg<ROUTE, TG, 4, 2, 1>(p, st);
-    case 12: return launch_cfg<ROUTE, TG, 16, 2, 1>(p, st);
-    case 14: return launch_cfg<ROUTE, TG, 8, 2, 1, 2>(p, st);     // 2 strips x 4
-    case 15: return launch_cfg<ROUTE, TG, 16, 2, 1, 2>(p, st);    // 2 strips x 8
-    case 16: return launch_cfg<ROUTE, TG, 16, 2, 1, 4>(p, st);    // 4 strips x 4
-    case 21: return launch_cfg<ROUTE, TG, 4, 2, 2>(p, st);
-    case 26: return launch_cfg<ROUTE, TG, 4, 2, 2, 2>(p, st);     // 2 row tiles, 2 strips x 2
-    case 46: return launch_cfg<ROUTE, TG, 4, 2, 4, 2>(p, st);     // 4 row tiles, 2 strips x 2
-    case 41: return launch_cfg<ROUTE, TG, 4, 2, 4>(p, st);
+    case 10: return launch_cfg<ROUTE, GPC, 8, 2, 1>(p, st);
+    case 11: return launch_cfg<ROUTE, GPC, 4, 2, 1>(p, st);
+    case 12: return launch_cfg<ROUTE, GPC, 16, 2, 1>(p, st);
+    case 14: return launch_cfg<ROUTE, GPC, 8, 2, 1, 2>(p, st);     // 2 strips x 4
+    case 15: return launch_cfg<ROUTE, GPC, 16, 2, 1, 2>(p, st);    // 2 strips x 8
+    case 16: return launch_cfg<ROUTE, GPC, 16, 2, 1, 4>(p, st);    // 4 strips x 4
+    case 21: return launch_cfg<ROUTE, GPC, 4, 2, 2>(p, st);
+    case 26: return launch_cfg<ROUTE, GPC, 4, 2, 2, 2>(p, st);     // 2 row tiles, 2 strips x 2
+    case 46: return launch_cfg<ROUTE, GPC, 4, 2, 4, 2>(p, st);     // 4 row tiles, 2 strips x 2
+    case 41: return launch_cfg<ROUTE, GPC, 4, 2, 4>(p, st);
     default: return QG_EINVAL;
   }
 }
@@ -358,9 +365,12 @@ int QG_CAT(decode_waves_wt, QG_WT)(int variant) {
 }
 
 int QG_CAT(decode_launch_wt, QG_WT)(const GemmParams& p, int route, int variant, hipStream_t st) {
-  const bool tg = (p.group == 64);
-  if (route == ROUTE_F16) return tg ? launch_variant<ROUTE_F16, true>(p, variant, st) : launch_variant<ROUTE_F16, false>(p, variant, st);
-  return tg ? launch_variant<ROUTE_BF16, true>(p, variant, st) : launch_variant<ROUTE_BF16, false>(p, variant, st);
+  const int gpc = (p.group == 32) ? 4 : (p.group == 64) ? 2 : 1;       // groups per 128-row chunk
+  if (route == ROUTE_F16)
+    return gpc == 4 ? launch_variant<ROUTE_F16, 4>(p, variant, st)
+         : gpc == 2 ? launch_variant<ROUTE_F16, 2>(p, variant, st) : launch_variant<ROUTE_F16, 1>(p, variant, st);
+  return gpc == 4 ? launch_variant<ROUTE_BF16, 4>(p, variant, st)
+       : gpc == 2 ? launch_variant<ROUTE_BF16, 2>(p, variant, st) : launch_variant<ROUTE_BF16, 1>(p, variant, st);
 }
 
 }  // namespace qg

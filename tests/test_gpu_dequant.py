@@ -43,7 +43,7 @@ def _check_w(case, inputs=None):
 @pytest.mark.parametrize("kind", [U, I])
 def test_integer_weights_bit_exact(kind, bits, act):
     zero = (1 << (bits - 1)) if kind == U else None
-    for group in (64, 128, 256):
+    for group in (32, 64, 128, 256):
         case = WL.Case(f"dq_{kind}_{bits}_{act}_{group}", 1, 256, 192, kind, bits, group=group, act=act,
                        scale_dtype="f16", zero=zero, seed=7000 + 10 * bits + kind)
         _check_w(case)

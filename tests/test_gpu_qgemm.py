@@ -131,9 +131,43 @@ def test_empty_m_and_bad_arguments():
     P = Prepared(case)
     A0 = torch.empty((0, 128), dtype=torch.float16, device="cuda")
     assert P.gpu_c(A0).shape == (0, 64)
-    with pytest.raises(B.QgError):      # group 32 has no kernel
-        s = torch.ones((4, 64), dtype=torch.float16, device="cuda")
-        B.qgemm(P.d_A, P.d_packed, s, None, P.wtype, 32, 64)
+    with pytest.raises(B.QgError):      # group 16 is no group size of this library
+        s = torch.ones((8, 64), dtype=torch.float16, device="cuda")
+        B.qgemm(P.d_A, P.d_packed, s, None, P.wtype, 16, 64)
+
+
+@pytest.mark.parametrize("act", ["f16", "bf16"])
+@pytest.mark.parametrize("M", [1, 16, 20, 40, 64, 65, 150])
+def test_group_size_32(M, act):
+    # four groups per 128-row chunk: the streaming kernel for every M (row blocks beyond 64);
+    # the tiled kernels have no such variant and say so
+    from paper_2504_12984_amd import binding as B
+    kind, bits = (U, 4) if M % 2 == 0 else (I, 3)
+    sdt = "f16" if act == "f16" else "bf16"
+    case = WL.Case(f"g32_{M}_{act}", M, 640, 192, kind, bits, group=32, act=act, scale_dtype=sdt,
+                   zero=8 if kind == U else None, seed=8610 + M)
+    P = Prepared(case)
+    ref = P.oracle_c()
+    assert_c_close(P.gpu_c(), ref, case.name)
+    plan = B.qg_plan(P.wtype, 32, M, case.N, case.K, act=B.QG_F16 if act == "f16" else B.QG_BF16)
+    assert plan["path"] == (1 if M <= 64 else 3)
+    B.qg_set_knob(0, 2)
+    with pytest.raises(B.QgError):
+        P.gpu_c()
+    B.qg_set_knob(0, 0)
+    with pytest.raises(B.QgError):
+        P.gpu_c(layout=1)
+
+
+def test_group_size_32_split_k_and_float_weights():
+    from paper_2504_12984_amd import binding as B
+    case = WL.Case("g32_f6", 7, 1408, 320, F, 6, 3, 2, group=32, act="bf16", scale_dtype="f16", zero=None,
+                   scale_lo=0.01, scale_hi=0.1, seed=8630)
+    P = Prepared(case)
+    ref = P.oracle_c()
+    for splitk in (0, 3):
+        B.qg_set_knob(1, splitk)
+        assert_c_close(P.gpu_c(), ref, f"{case.name} splitk {splitk}")
 
 
 # ------------------------------------------------------------------ tiled path

@@ -35,6 +35,8 @@ def _random_case(seed: int) -> tuple[WL.Case, int]:
         zero = None
     lo, hi = (0.01, 0.1) if kind == WL.KIND_FLOAT else (0.005, 0.02)
     layout = int(rng.integers(0, 2))
+    if layout == 0 and rng.integers(0, 4) == 0:        # group size 32 exists on the first layout only
+        group = 32
     case = WL.Case(f"rand{seed}_k{kind}b{bits}_M{M}_K{K}_N{N}_g{group}_{act}_L{layout}", M, K, N, kind, bits, e, m,
                    group=group, act=act, scale_dtype=sdt, zero=zero, scale_lo=lo, scale_hi=hi, seed=91000 + seed)
     return case, layout
