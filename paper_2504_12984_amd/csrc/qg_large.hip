@@ -377,6 +377,8 @@ __global__ __launch_bounds__(256) void large_kernel(GemmParams p, int tiles_m, i
         return __builtin_amdgcn_make_buffer_rsrc(p.ws + ((int64_t)tile * p.splitk + sp) * (BM * LARGE_BN), 0, TILE_BYTES, 0x00020000);
       };
       // lane layout of a partial tile: fragment (mt, nt) of thread tid at 16 * ((mt*4+nt)*256 + tid)
+      // (QG_DBG_NOEXSTORE / QG_DBG_NOEXLOAD: diagnostic builds without the exchange / without the
+      // read-back, wrong results, timing only; never defined by the build)
 #ifndef QG_DBG_NOEXSTORE
       {
         const __amdgpu_buffer_rsrc_t mine = ws_rsrc(slab);
