@@ -463,12 +463,15 @@ static int launch_bm(const GemmParams& p, hipStream_t st, int tn0, int tiles_n) 
   const int per_xcd = (total + 7) / 8;
   const size_t lds_bytes = 2 * LargeLds<BM>::BUF;
   auto kern = large_kernel<QG_WT, ROUTE, TG, BM>;
-  static bool attr_done = false;   // raise the dynamic LDS limit once per instantiation
-  if (!attr_done) {
+  // raise the dynamic LDS limit once per instantiation and device
+  static bool attr_done[64] = {};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return QG_EHIP;
+  if (!attr_done[dev]) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                             (int)lds_bytes) != hipSuccess)
       return QG_EHIP;
-    attr_done = true;
+    attr_done[dev] = true;
   }
   hipLaunchKernelGGL(kern, dim3((unsigned)(8 * per_xcd)), dim3(256), lds_bytes, st, p, tiles_m, tiles_n, per_xcd, tn0);
   return hipGetLastError() == hipSuccess ? QG_OK : QG_EHIP;
