@@ -76,11 +76,13 @@ typedef struct { int32_t kind, bits, ebits, mbits; } qg_wtype;
  * owns, i.e. in the matrix instruction the kernels built for them use (the paper
  * transforms the weight for the program that will read it, Section "Efficient
  * Low-Precision Weight Loading"):
- *   QG_LAYOUT_TILE128x64      lane owns 4 columns; 16x16x32 instruction.  Kernels
- *                             for every M; the choice for decode (small M).
- *   QG_LAYOUT_TILE128x64_R32  lane owns 2 columns; 32x32x16 instruction.  One
- *                             tiled kernel for every M, fastest for M >= 128;
- *                             qgemm needs M*K < 2^31 with it. */
+ *   QG_LAYOUT_TILE128x64      lane owns 4 columns; 16x16x32 instruction.  A streaming
+ *                             kernel for M <= 64 and a tiled kernel (with split-K)
+ *                             above; the default, and the faster one at every M.
+ *   QG_LAYOUT_TILE128x64_R32  lane owns 2 columns; 32x32x16 instruction.  One tiled
+ *                             kernel for every M (no split-K, no group size 32),
+ *                             about 5 % slower than the first layout's on the prefill
+ *                             shapes: the measured alternative, kept with its tests. */
 #define QG_LAYOUT_TILE128x64 0
 #define QG_LAYOUT_TILE128x64_R32 1
 #define QG_TILE_K 128
@@ -129,7 +131,7 @@ QG_API int qdequant(const void* packed_W, const void* scales, const uint8_t* zer
  * Path choice (by shape) is internal: M <= 64 streams the weights once through
  * a split-K kernel (1, 2 or 4 tiles of 16 rows per wavefront); larger M uses
  * the LDS-staged tiled kernel, which also splits K (partial sums meet in a
- * per-device workspace the library allocates on first use) when its 64- or
+ * workspace the library allocates on first use) when its 64- or
  * 128-row tiles would leave most CUs idle.  The tiled kernel needs M*K*2, the packed
  * weight and the scale array each below 4 GiB (QG_EUNSUPPORTED otherwise). */
 QG_API int qgemm(const void* A, const void* packed_W, const void* scales, const uint8_t* zeros,
