@@ -100,6 +100,18 @@ def test_config4_low_bit_floats_full(bits):
         f.check_gemm(_A_of(WL.cfg4(bits, M)), wr, f"cfg4 f{bits} M={M}")
 
 
+@pytest.mark.parametrize("bits", [4, 6])
+def test_config4_shape_at_moderate_m_full(bits):
+    # K = N = 8192 with 128 / 256 / 512 rows: the shapes on which the tiled kernel splits K
+    # (64- and 128-row tiles, 2 and 4 slabs), as the library chooses them
+    f = FullCase(WL.cfg4(bits, 1))
+    wr = f.check_weights()
+    for M in (128, 256, 512):
+        plan = f.B.qg_plan(f.wtype, f.case.group, M, f.case.N, f.case.K, act=f.B.QG_BF16, scale_dtype=f.B.QG_F16)
+        assert plan["path"] == 2 and plan["splitk"] > 1, plan
+        f.check_gemm(_A_of(WL.cfg4(bits, M)), wr, f"cfg4 f{bits} M={M}")
+
+
 @pytest.mark.parametrize("bits", [5, 6])
 def test_config5_prefill_full(bits):
     f = FullCase(WL.cfg5(bits, 1024))
