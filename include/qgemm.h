@@ -117,9 +117,8 @@ QG_API int repack(const void* canonical, qg_wtype t, int layout, int64_t K, int6
  *   group  rows of W per scale, dividing K: 32, 64, 128 * 2^s, or K itself (= one scale per
  *          output column; 0 means the same).  128 * odd (other than K) is a valid group
  *          size this build has no kernel for: QG_EUNSUPPORTED.  Group size 32 exists in
- *          qdequant (both layouts) and in qgemm on QG_LAYOUT_TILE128x64, where every M runs
- *          the streaming kernel (over blocks of 64 rows beyond M = 64); qgemm with group 32
- *          on QG_LAYOUT_TILE128x64_R32 is QG_EUNSUPPORTED.
+ *          qdequant (both layouts) and in qgemm on QG_LAYOUT_TILE128x64; qgemm with group
+ *          32 on QG_LAYOUT_TILE128x64_R32 is QG_EUNSUPPORTED.
  * QG_EINVAL on shape/group violations, QG_EUNSUPPORTED on an unsupported
  * float split or group size. */
 QG_API int qdequant(const void* packed_W, const void* scales, const uint8_t* zeros, qg_wtype t,

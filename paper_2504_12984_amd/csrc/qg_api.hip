@@ -222,11 +222,7 @@ static void plan_tiled(int64_t M, int64_t N, int64_t K, int bits, int* bm_out, i
 
 // path of the first layout: 1 = streaming kernel, 2 = tiled kernel, 3 = streaming kernel
 // over blocks of 64 rows (forced only)
-// (group size 32 has no tiled kernel: larger M run the streaming kernel over row blocks)
-static int plan_path(int64_t M, int64_t group) {
-  if (g_knob[0]) return g_knob[0];
-  return M <= 64 ? 1 : (group == 32 ? 3 : 2);
-}
+static int plan_path(int64_t M) { return g_knob[0] ? g_knob[0] : (M <= 64 ? 1 : 2); }
 
 }  // namespace qg
 
@@ -328,11 +324,11 @@ int qgemm(const void* A, const void* packed_W, const void* scales, const uint8_t
                       (uint64_t)K * (uint64_t)N / 8u * (uint64_t)t.bits < (1ull << 32) &&
                       (uint64_t)(K / group) * (uint64_t)N * 2u < (1ull << 32);
   if (layout == QG_LAYOUT_TILE128x64_R32) {      // one kernel for every M
-    if (!fits32 || group == 32) return QG_EUNSUPPORTED;      // no tiled kernel for four groups per chunk
+    if (!fits32 || group == 32) return QG_EUNSUPPORTED;      // the second layout's kernel has no variant for four groups per chunk
     return kLarge32[wt](p, route, g_knob[2], st);
   }
 
-  const int path = plan_path(M, group);
+  const int path = plan_path(M);
   if (path == 1 && M > 64) return QG_EINVAL;
 
   if (path == 1 || path == 3) {
@@ -346,7 +342,7 @@ int qgemm(const void* A, const void* packed_W, const void* scales, const uint8_t
     }
     return QG_OK;
   }
-  if (!fits32 || group == 32) return QG_EUNSUPPORTED;        // group 32: streaming kernel only (forced path 2)
+  if (!fits32) return QG_EUNSUPPORTED;
   int bm;
   plan_tiled(M, N, K, t.bits, &bm, &p.splitk, &p.chunks_per_split);
   if (p.splitk > 1) {
@@ -379,8 +375,7 @@ int qg_plan(qg_wtype t, int layout, int act, int scale_dtype, int64_t group, int
   if (M < 1 || M > (1 << 24) || !plan) return QG_EINVAL;
   plan[0] = plan[1] = plan[2] = 0; plan[3] = 1; plan[4] = (int)(K / TILE_K);
   if (layout == QG_LAYOUT_TILE128x64_R32) { plan[0] = 2; plan[2] = g_knob[2]; return group == 32 ? QG_EUNSUPPORTED : QG_OK; }
-  plan[0] = plan_path(M, group);
-  if (plan[0] == 2 && group == 32) return QG_EUNSUPPORTED;
+  plan[0] = plan_path(M);
   if (plan[0] == 1 && M > 64) return QG_EINVAL;
   if (plan[0] == 1 || plan[0] == 3) plan_streaming((int)(M < 64 ? M : 64), (int)N, (int)K, (int)group, wt, &plan[1], &plan[3], &plan[4]);
   else plan_tiled(M, N, K, t.bits, &plan[2], &plan[3], &plan[4]);

@@ -68,8 +68,10 @@ struct LargeLds {
   static constexpr int BUF = 4 * SLICE;
 };
 
-template <int WT, int ROUTE, bool TWO_GROUPS, int BM>
+template <int WT, int ROUTE, int GPC, int BM>
 __global__ __launch_bounds__(256) void large_kernel(GemmParams p, int tiles_m, int tiles_n, int per_xcd, int tn0) {
+  // GPC = groups per 128-row chunk: 1 (group size 128 or more), 2 (64) or 4 (32)
+  constexpr bool TWO_GROUPS = (GPC == 2), FOUR_GROUPS = (GPC == 4);
   typedef Decoder<WT, ROUTE> D;
   constexpr int BITS = D::BITS, RAW = D::RAW;
   constexpr int MTS = BM / 16;                 // 16-row MFMA tiles per workgroup
@@ -138,8 +140,8 @@ __global__ __launch_bounds__(256) void large_kernel(GemmParams p, int tiles_m, i
   // ---- W prefetch: raw chunk + its scales / zero-points -------------------------------
   struct WStage {
     uint32_t r[RAW];
-    uint2 s0, s1;
-    uint32_t z0, z1;
+    uint2 s0, s1, s2, s3;        // scales / zero-points of the chunk's groups (GPC of them in use)
+    uint32_t z0, z1, z2, z3;
   };
   // Through buffer resources as well (the host checks that the packed weight and the
   // scale array are below 4 GiB): lane part constant, chunk / group part scalar.
@@ -153,8 +155,8 @@ __global__ __launch_bounds__(256) void large_kernel(GemmParams p, int tiles_m, i
   const int w_strip = nc * KC * (1024 * BITS);          // byte offset of my strip (scalar)
   // The loads of one chunk are 2 (4 with two groups per chunk) + BITS separate pieces,
   // so that the main loop can issue them a few at a time in different gaps between
-  // matrix instructions.  Pieces: s0, z0, (s1, z1,) then BITS x 16 bytes of codes.
-  constexpr int WMETA = TWO_GROUPS ? 4 : 2;
+  // matrix instructions.  Pieces: s0, z0, (s1, z1, (s2, z2, s3, z3,)) then BITS x 16 bytes of codes.
+  constexpr int WMETA = 2 * GPC;
   constexpr int WPIECES = WMETA + BITS;
   auto w_piece = [&](WStage& s, int c, auto Ic) __attribute__((always_inline)) {
     constexpr int I = decltype(Ic)::value;
@@ -164,21 +166,28 @@ __global__ __launch_bounds__(256) void large_kernel(GemmParams p, int tiles_m, i
       const u4_t q = __builtin_amdgcn_raw_buffer_load_b128(w_rsrc, w_lane, w_strip + c * (1024 * BITS) + B * 1024, 0);
       s.r[4 * B + 0] = q.x; s.r[4 * B + 1] = q.y; s.r[4 * B + 2] = q.z; s.r[4 * B + 3] = q.w;
     } else {
-      const int g0 = TWO_GROUPS ? 2 * c : ((c >> p.gshift) & p.gmask);
+      const int g0 = (GPC > 1) ? GPC * c : ((c >> p.gshift) & p.gmask);
       typedef uint32_t u2_t __attribute__((ext_vector_type(2)));
       if constexpr (I == 0) { const u2_t v = __builtin_amdgcn_raw_buffer_load_b64(s_rsrc, s_lane, g0 * p.N * 2, 0); s.s0 = make_uint2(v.x, v.y); }
       if constexpr (I == 1) s.z0 = __builtin_amdgcn_raw_buffer_load_b32(z_rsrc, z_lane, g0 * p.N, 0);
       if constexpr (I == 2) { const u2_t v = __builtin_amdgcn_raw_buffer_load_b64(s_rsrc, s_lane, (g0 + 1) * p.N * 2, 0); s.s1 = make_uint2(v.x, v.y); }
       if constexpr (I == 3) s.z1 = __builtin_amdgcn_raw_buffer_load_b32(z_rsrc, z_lane, (g0 + 1) * p.N, 0);
+      if constexpr (I == 4) { const u2_t v = __builtin_amdgcn_raw_buffer_load_b64(s_rsrc, s_lane, (g0 + 2) * p.N * 2, 0); s.s2 = make_uint2(v.x, v.y); }
+      if constexpr (I == 5) s.z2 = __builtin_amdgcn_raw_buffer_load_b32(z_rsrc, z_lane, (g0 + 2) * p.N, 0);
+      if constexpr (I == 6) { const u2_t v = __builtin_amdgcn_raw_buffer_load_b64(s_rsrc, s_lane, (g0 + 3) * p.N * 2, 0); s.s3 = make_uint2(v.x, v.y); }
+      if constexpr (I == 7) s.z3 = __builtin_amdgcn_raw_buffer_load_b32(z_rsrc, z_lane, (g0 + 3) * p.N, 0);
     }
   };
   auto w_issue = [&](WStage& s, int c) __attribute__((always_inline)) {
     static_for<WPIECES>([&](auto Ic) __attribute__((always_inline)) { w_piece(s, c, Ic); });
   };
-  // constants of one column of the first (G = 0) or second (G = 1) group of a chunk
+  // constants of one column of group G (0 .. GPC-1) of a chunk
   auto consts_col = [&](typename D::Consts& g, const WStage& s, auto Gc, int nt) __attribute__((always_inline)) {
-    if constexpr (decltype(Gc)::value == 0) D::make_col(g, nt, s.s0, s.z0 & zmask, p.zbias, p.scale_bf16);
-    else                                    D::make_col(g, nt, s.s1, s.z1 & zmask, p.zbias, p.scale_bf16);
+    constexpr int G = decltype(Gc)::value;
+    if constexpr (G == 0) D::make_col(g, nt, s.s0, s.z0 & zmask, p.zbias, p.scale_bf16);
+    if constexpr (G == 1) D::make_col(g, nt, s.s1, s.z1 & zmask, p.zbias, p.scale_bf16);
+    if constexpr (G == 2) D::make_col(g, nt, s.s2, s.z2 & zmask, p.zbias, p.scale_bf16);
+    if constexpr (G == 3) D::make_col(g, nt, s.s3, s.z3 & zmask, p.zbias, p.scale_bf16);
   };
 
   // Accumulators live in the accumulation registers (AGPRs) for the whole
@@ -255,6 +264,16 @@ __global__ __launch_bounds__(256) void large_kernel(GemmParams p, int tiles_m, i
       consts_col(g1, wA, std::integral_constant<int, 1>{}, decltype(NTc)::value);
     });
   }
+  // Four groups per chunk: every k-step has its own group.  Two constant sets alternate by
+  // the parity of the k-step -- gA0 for steps 0 and 2, gB0 for steps 1 and 3, whatever the
+  // chunk -- and while the unpack of step J+1 reads one, the other is rebuilt for step J+2
+  // (groups 2 and 3 from this chunk's stage in k-steps 0 and 1, groups 0 and 1 of the next
+  // chunk from its stage in k-steps 2 and 3).
+  if constexpr (FOUR_GROUPS) {
+    static_for<4>([&](auto NTc) __attribute__((always_inline)) {
+      consts_col(gB0, wA, std::integral_constant<int, 1>{}, decltype(NTc)::value);
+    });
+  }
 
   // one chunk: weights wc (constants gc0, g1) are consumed, wn is loaded and its
   // constants gn0 built; CUR is the LDS buffer holding this chunk's A slab
@@ -276,7 +295,8 @@ __global__ __launch_bounds__(256) void large_kernel(GemmParams p, int tiles_m, i
       uint32_t nf[4][4];                 // fragment of k-step J+1 under construction
       uint32_t xe[PB];
       typename D::Mid mid[PB], mid_prev[PB];
-      const typename D::Consts& g = (J < 3) ? ((TWO_GROUPS && JN >= 2) ? g1 : gc0) : gn0;
+      const typename D::Consts& g = FOUR_GROUPS ? ((JN & 1) ? gn0 : gc0)
+                                                : (J < 3) ? ((TWO_GROUPS && JN >= 2) ? g1 : gc0) : gn0;
       const uint32_t (&rw)[RAW] = (J < 3) ? wc.r : wn.r;
       static_for<MTS>([&](auto MTc) __attribute__((always_inline)) {
         constexpr int MT = decltype(MTc)::value;
@@ -323,10 +343,17 @@ __global__ __launch_bounds__(256) void large_kernel(GemmParams p, int tiles_m, i
           });
           static_for<CPS>([&](auto Xc) __attribute__((always_inline)) {
             constexpr int X = decltype(Xc)::value;
-            if constexpr (J == 2 && IDX >= FREE_PER_STEP - CSLOTS)
+            if constexpr (!FOUR_GROUPS && J == 2 && IDX >= FREE_PER_STEP - CSLOTS)
               consts_col(gn0, wn, std::integral_constant<int, 0>{}, (IDX - (FREE_PER_STEP - CSLOTS)) * CPS + X);
             if constexpr (TWO_GROUPS && J == 3 && IDX < CSLOTS)
               consts_col(g1, wn, std::integral_constant<int, 1>{}, IDX * CPS + X);
+            if constexpr (FOUR_GROUPS && IDX >= FREE_PER_STEP - CSLOTS) {
+              constexpr int COL = (IDX - (FREE_PER_STEP - CSLOTS)) * CPS + X;
+              if constexpr (J == 0) consts_col(gc0, wc, std::integral_constant<int, 2>{}, COL);
+              if constexpr (J == 1) consts_col(gn0, wc, std::integral_constant<int, 3>{}, COL);
+              if constexpr (J == 2) consts_col(gc0, wn, std::integral_constant<int, 0>{}, COL);
+              if constexpr (J == 3) consts_col(gn0, wn, std::integral_constant<int, 1>{}, COL);
+            }
           });
         }
 #pragma unroll
@@ -349,7 +376,8 @@ __global__ __launch_bounds__(256) void large_kernel(GemmParams p, int tiles_m, i
   // shuffled the whole accumulator state around the merge).
   for (int kc = kbeg; kc < kend; kc += 2) {
     chunk(std::integral_constant<int, 0>{}, wA, wB, gA0, gB0, kc);
-    chunk(std::integral_constant<int, 1>{}, wB, wA, gB0, gA0, kc + 1);
+    if constexpr (FOUR_GROUPS) chunk(std::integral_constant<int, 1>{}, wB, wA, gA0, gB0, kc + 1);   // sets by k-step parity
+    else                       chunk(std::integral_constant<int, 1>{}, wB, wA, gB0, gA0, kc + 1);   // sets by chunk parity
   }
 
   // the matrix pipeline may still be writing the accumulators (the compiler
@@ -455,14 +483,14 @@ __global__ __launch_bounds__(256) void large_kernel(GemmParams p, int tiles_m, i
 #define QG_CAT(a, b) QG_CAT2(a, b)
 
 // One launch over the column tiles [tn0, tn0 + tiles_n) and all row tiles of height BM.
-template <int ROUTE, bool TG, int BM>
+template <int ROUTE, int GPC, int BM>
 static int launch_bm(const GemmParams& p, hipStream_t st, int tn0, int tiles_n) {
   const int tiles_m = (p.M + BM - 1) / BM;
   if (p.splitk > 1 && BM > 128) return QG_EINVAL;
   const int total = tiles_m * tiles_n * p.splitk;
   const int per_xcd = (total + 7) / 8;
   const size_t lds_bytes = 2 * LargeLds<BM>::BUF;
-  auto kern = large_kernel<QG_WT, ROUTE, TG, BM>;
+  auto kern = large_kernel<QG_WT, ROUTE, GPC, BM>;
   // raise the dynamic LDS limit once per instantiation and device
   static bool attr_done[64] = {};
   int dev = 0;
@@ -479,10 +507,13 @@ static int launch_bm(const GemmParams& p, hipStream_t st, int tn0, int tiles_n) 
 
 template <int ROUTE>
 static int launch_rows(const GemmParams& p, int bm, hipStream_t st, int tn0, int tiles_n) {
-  const bool tg = (p.group == 64);
-  if (bm == 64) return tg ? launch_bm<ROUTE, true, 64>(p, st, tn0, tiles_n) : launch_bm<ROUTE, false, 64>(p, st, tn0, tiles_n);
-  if (bm == 128) return tg ? launch_bm<ROUTE, true, 128>(p, st, tn0, tiles_n) : launch_bm<ROUTE, false, 128>(p, st, tn0, tiles_n);
-  if (bm == 256) return tg ? launch_bm<ROUTE, true, 256>(p, st, tn0, tiles_n) : launch_bm<ROUTE, false, 256>(p, st, tn0, tiles_n);
+  const int gpc = (p.group == 32) ? 4 : (p.group == 64) ? 2 : 1;       // groups per 128-row chunk
+#define QG_ROWS(BM_)                                                              \
+  if (bm == BM_)                                                                  \
+    return gpc == 4 ? launch_bm<ROUTE, 4, BM_>(p, st, tn0, tiles_n)               \
+         : gpc == 2 ? launch_bm<ROUTE, 2, BM_>(p, st, tn0, tiles_n) : launch_bm<ROUTE, 1, BM_>(p, st, tn0, tiles_n);
+  QG_ROWS(64) QG_ROWS(128) QG_ROWS(256)
+#undef QG_ROWS
   return QG_EINVAL;
 }
 

@@ -139,8 +139,8 @@ def test_empty_m_and_bad_arguments():
 @pytest.mark.parametrize("act", ["f16", "bf16"])
 @pytest.mark.parametrize("M", [1, 16, 20, 40, 64, 65, 150])
 def test_group_size_32(M, act):
-    # four groups per 128-row chunk: the streaming kernel for every M (row blocks beyond 64);
-    # the tiled kernels have no such variant and say so
+    # four groups per 128-row chunk: streaming kernel up to 64 rows, tiled kernel beyond (and
+    # forced, at every tile height); the second layout's kernel has no such variant and says so
     from paper_2504_12984_amd import binding as B
     kind, bits = (U, 4) if M % 2 == 0 else (I, 3)
     sdt = "f16" if act == "f16" else "bf16"
@@ -150,13 +150,29 @@ def test_group_size_32(M, act):
     ref = P.oracle_c()
     assert_c_close(P.gpu_c(), ref, case.name)
     plan = B.qg_plan(P.wtype, 32, M, case.N, case.K, act=B.QG_F16 if act == "f16" else B.QG_BF16)
-    assert plan["path"] == (1 if M <= 64 else 3)
+    assert plan["path"] == (1 if M <= 64 else 2)
     B.qg_set_knob(0, 2)
-    with pytest.raises(B.QgError):
-        P.gpu_c()
-    B.qg_set_knob(0, 0)
+    for bm in (64, 128, 256):
+        B.qg_set_knob(2, bm)
+        assert_c_close(P.gpu_c(), ref, f"{case.name} tiled {bm}")
+    B.qg_set_knob(0, 3)
+    assert_c_close(P.gpu_c(), ref, f"{case.name} row blocks")
+    B.qg_set_knob(0, 0); B.qg_set_knob(2, 0)
     with pytest.raises(B.QgError):
         P.gpu_c(layout=1)
+
+
+@pytest.mark.parametrize("bits", [1, 3, 5, 8])
+def test_group_size_32_tiled_path_types_and_odd_chunk_counts(bits):
+    from paper_2504_12984_amd import binding as B
+    # 7 chunks (odd: the padding chunk), several row tiles, idle wavefronts (N = 192), split-K
+    case = WL.Case(f"g32_tiled_{bits}", 300, 896, 192, U, bits, group=32, act="f16" if bits % 2 else "bf16",
+                   scale_dtype="f16", zero=(1 << bits) // 2, seed=8640 + bits)
+    P = Prepared(case)
+    ref = P.oracle_c()
+    assert_c_close(P.gpu_c(), ref, case.name)
+    B.qg_set_knob(0, 2); B.qg_set_knob(2, 64); B.qg_set_knob(1, 2)
+    assert_c_close(P.gpu_c(), ref, case.name + " split")
 
 
 def test_group_size_32_split_k_and_float_weights():

@@ -90,9 +90,9 @@ def test_knobs_force_the_plan_and_bad_arguments_are_rejected():
         B.qg_plan(U4, 96, 16, 128, 1408)                             # group does not divide K
     assert B.qg_plan(U4, 128, 300, 512, 1024, layout=B.QG_LAYOUT_TILE128x64_R32)["path"] == 2
     assert B.qg_plan(U4, 0, 16, 128, 1408) == B.qg_plan(U4, 1408, 16, 128, 1408)    # 0 = one scale per column
-    # group 32: streaming kernel only, 4-wavefront arrangements
+    # group 32: 4-wavefront arrangements of the streaming kernel, tiled kernel beyond 64 rows
     assert B.qg_plan(U4, 32, 16, 28672, 8192)["variant"] == 11
-    assert B.qg_plan(U4, 32, 300, 512, 1024)["path"] == 3
+    assert B.qg_plan(U4, 32, 300, 512, 1024)["path"] == 2
     with pytest.raises(Exception):
         B.qg_plan(U4, 32, 300, 512, 1024, layout=B.QG_LAYOUT_TILE128x64_R32)
     with pytest.raises(Exception):
