@@ -34,7 +34,10 @@
  *     process ends, so calls on different streams may overlap.  At most 32
  *     (device, stream) pairs per process (QG_EUNSUPPORTED beyond); a stream
  *     that is destroyed and whose handle value is re-used simply inherits the
- *     workspace.
+ *     workspace.  Calls may be captured into a HIP graph once the same call has
+ *     run eagerly on the capture stream (so that nothing is allocated during
+ *     the capture); every launch leaves counters and workspace ready for the
+ *     next, so a graph can be replayed any number of times.
  *
  * De-quantisation (the paper names the step but prints no formula; this is the
  * standard affine group form):

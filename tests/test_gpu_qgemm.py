@@ -336,6 +336,44 @@ def test_group_zero_means_one_scale_per_output_column():
     assert np.array_equal(bits_of(W0), bits_of(P.gpu_w(0)))
 
 
+def test_graph_capture_of_qgemm_calls_replays_to_the_eager_bits():
+    # a streaming split-K call, a tiled split-K call and a plain tiled call captured in one HIP
+    # graph; every replay (with eager work and synchronisations in between) must reproduce the
+    # eager results bit for bit -- arrival counters and workspaces are left ready by each launch.
+    # The first call on a stream allocates its workspace, so the calls run once eagerly on the
+    # capture stream before the capture.
+    from paper_2504_12984_amd import binding as B
+    cases = [WL.Case("graph_small", 16, 8192, 2048, U, 4, group=128, zero=8, seed=8970),
+             WL.Case("graph_mid", 128, 8192, 2048, U, 4, group=128, act="bf16", scale_dtype="bf16", zero=8, seed=8971),
+             WL.Case("graph_big", 300, 512, 1024, I, 5, group=64, act="bf16", scale_dtype="f16", zero=None, seed=8972)]
+    Ps = [Prepared(c) for c in cases]
+    eager = [P.gpu_c() for P in Ps]
+    for P, C in zip(Ps, eager):
+        assert_c_close(C, P.oracle_c(), P.case.name)
+    outs = [torch.empty_like(C) for C in eager]
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+
+    def enqueue():
+        for P, out in zip(Ps, outs):
+            B.qgemm(P.d_A, P.packed(0), P.d_scales, P.d_zeros, P.wtype, P.case.group, P.case.N, out=out)
+
+    with torch.cuda.stream(side):
+        enqueue()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        enqueue()
+    for rep in range(3):
+        for out in outs:
+            out.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for out, C, P in zip(outs, eager, Ps):
+            assert np.array_equal(bits_of(out), bits_of(C)), f"{P.case.name} replay {rep}"
+
+
 def test_bound_call_gives_the_same_bits_as_the_plain_call_and_checks_its_arguments():
     from paper_2504_12984_amd import binding as B
     case = WL.Case("bound", 7, 640, 192, U, 4, group=128, zero=8, seed=9100)
