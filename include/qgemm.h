@@ -131,8 +131,8 @@ QG_API int qdequant(const void* packed_W, const void* scales, const uint8_t* zer
 /* C[M,N] (row-major, `act`) = A[M,K] (row-major, `act`) . dequant(W).
  * Arguments as for qdequant; M >= 1 is arbitrary, C is overwritten.
  * Path choice (by shape) is internal: M <= 64 streams the weights once through
- * a split-K kernel (1, 2 or 4 tiles of 16 rows per wavefront); larger M uses
- * the LDS-staged tiled kernel, which also splits K (partial sums meet in a
+ * a split-K kernel (1, 2 or 4 tiles of 16 rows per wavefront); larger M -- and
+ * 33 <= M <= 64 on all but small problems -- use the LDS-staged tiled kernel, which also splits K (partial sums meet in a
  * workspace the library allocates on first use) when its 64- or
  * 128-row tiles would leave most CUs idle.  The tiled kernel needs M*K*2, the packed
  * weight and the scale array each below 4 GiB (QG_EUNSUPPORTED otherwise). */

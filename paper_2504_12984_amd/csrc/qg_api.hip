@@ -188,13 +188,34 @@ static int launch_streaming(GemmParams& p, int wt, int route, hipStream_t st) {
 // chunks per workgroup x time per chunk (1.33 at up to 4 bits, + 0.33 per bit above,
 // x 1.13 for 128 rows) + for the exchange of partial sums 5 + 0.4 per MB with 64-row
 // tiles, 11 + 0.6 per MB with 128-row tiles.
-static void plan_tiled(int64_t M, int64_t N, int64_t K, int bits, int* bm_out, int* splitk_out, int* cps_out) {
+// Up to 64 rows (one 64-row tile per column tile) a fit of its own, to K = 4096 .. 28672,
+// N = 4096 .. 28672 at 4, 6 and 8 bits: 6 + chunks per workgroup x (1.41 + 0.11 per bit
+// above 4; float codes, whose unpack is longer: 1.6 + 0.41 per bit above 4, + 0.4 without a
+// hardware convert) + 1.2 per slab (the last arriver of a tile reads the slabs back one
+// pair after the other).
+static void plan_tiled(int64_t M, int64_t N, int64_t K, qg_wtype t, int* bm_out, int* splitk_out, int* cps_out,
+                       double* cost_out = nullptr) {
+  const int bits = t.bits;
   int bm = g_knob[2], splitk = g_knob[1];
   const int KC = (int)(K / TILE_K);
   const int64_t tiles_n = (N + 255) / 256;
-  if (bm == 0 && large_prefers_64_rows(M, N)) {
+  if (bm == 0 && (M <= 64 || large_prefers_64_rows(M, N))) {
     bm = 64;
-    if (splitk <= 0) {
+    if (splitk <= 0 && M <= 64) {
+      const int over = bits > 4 ? bits - 4 : 0;
+      const bool hw_convert = (bits == 4 || bits == 6 || bits == 8);      // e2m1, e3m2, e4m3
+      const double tc = (t.kind == QG_FLOAT) ? 1.6 + 0.41 * over + (hw_convert ? 0.0 : 0.4) : 1.41 + 0.11 * over;
+      double best = 1e30;
+      for (int sk = 1; sk <= 8; sk *= 2) {
+        int cps = (KC + sk - 1) / sk;
+        if (sk > 1 && (cps & 1)) ++cps;
+        if (sk > 1 && (cps < 8 || tiles_n * sk > 256)) continue;       // short slabs do not pay for the exchange
+        const double rounds = (double)((tiles_n * sk + 255) / 256);
+        const double cost = 6.0 + rounds * cps * tc + (sk > 1 ? 1.2 * sk : 0.0);
+        if (cost < best) { best = cost; splitk = sk; }
+      }
+      if (cost_out) *cost_out = best;
+    } else if (splitk <= 0) {
       const double tc = 1.33 + 0.33 * (bits > 4 ? bits - 4 : 0);
       double best = 1e30;
       for (int cand_bm = 64; cand_bm <= 128; cand_bm *= 2)
@@ -209,6 +230,7 @@ static void plan_tiled(int64_t M, int64_t N, int64_t K, int bits, int* bm_out, i
                               (sk > 1 ? (cand_bm == 64 ? 5.0 + 0.4 * mb : 11.0 + 0.6 * mb) : 0.0);
           if (cost < best) { best = cost; bm = cand_bm; splitk = sk; }
         }
+      if (cost_out) *cost_out = best;
     }
   }
   if (splitk <= 0 || (bm != 64 && bm != 128)) splitk = 1;
@@ -222,7 +244,24 @@ static void plan_tiled(int64_t M, int64_t N, int64_t K, int bits, int* bm_out, i
 
 // path of the first layout: 1 = streaming kernel, 2 = tiled kernel, 3 = streaming kernel
 // over blocks of 64 rows (forced only)
-static int plan_path(int64_t M) { return g_knob[0] ? g_knob[0] : (M <= 64 ? 1 : 2); }
+static int plan_path(int64_t M, int64_t N, int64_t K, qg_wtype t) {
+  const int bits = t.bits;
+  if (g_knob[0]) return g_knob[0];
+  if (M > 64) return 2;
+  // 33 .. 64 rows: the streaming kernel (4 row tiles per wavefront) re-reads A from L2 for
+  // every 64-column strip -- measured 10 us + 2.2 us (+ 0.09 per bit above 4) per 1024 of K
+  // at N = 8192 -- while the tiled kernel shares A through LDS among four strips and splits K
+  // instead; it wins on all but the small problems (K = 8192, N = 28672, M = 64, 6 bits:
+  // 59 us against 75; K = N = 8192: a tie; K = 14336, N = 4096: 32 against 26).
+  if (M > 32 && (double)K * (double)N >= 16.0e6 && g_knob[1] == 0 && g_knob[2] == 0 && g_knob[3] == 0) {
+    double tiled = 1e30;
+    int bm, sk, cps;
+    plan_tiled(M, N, K, t, &bm, &sk, &cps, &tiled);
+    const double streaming = 10.0 + (2.2 + 0.09 * (bits > 4 ? bits - 4 : 0)) * ((double)K / 1024.0) * ((double)N / 8192.0);
+    if (tiled < 0.9 * streaming) return 2;          // both fits are good to about 10 %
+  }
+  return 1;
+}
 
 }  // namespace qg
 
@@ -328,7 +367,7 @@ int qgemm(const void* A, const void* packed_W, const void* scales, const uint8_t
     return kLarge32[wt](p, route, g_knob[2], st);
   }
 
-  const int path = plan_path(M);
+  const int path = plan_path(M, N, K, t);
   if (path == 1 && M > 64) return QG_EINVAL;
 
   if (path == 1 || path == 3) {
@@ -344,7 +383,7 @@ int qgemm(const void* A, const void* packed_W, const void* scales, const uint8_t
   }
   if (!fits32) return QG_EUNSUPPORTED;
   int bm;
-  plan_tiled(M, N, K, t.bits, &bm, &p.splitk, &p.chunks_per_split);
+  plan_tiled(M, N, K, t, &bm, &p.splitk, &p.chunks_per_split);
   if (p.splitk > 1) {
     const int64_t tiles = ((M + bm - 1) / bm) * ((N + 255) / 256);
     Workspace* w = nullptr;
@@ -375,10 +414,10 @@ int qg_plan(qg_wtype t, int layout, int act, int scale_dtype, int64_t group, int
   if (M < 1 || M > (1 << 24) || !plan) return QG_EINVAL;
   plan[0] = plan[1] = plan[2] = 0; plan[3] = 1; plan[4] = (int)(K / TILE_K);
   if (layout == QG_LAYOUT_TILE128x64_R32) { plan[0] = 2; plan[2] = g_knob[2]; return group == 32 ? QG_EUNSUPPORTED : QG_OK; }
-  plan[0] = plan_path(M);
+  plan[0] = plan_path(M, N, K, t);
   if (plan[0] == 1 && M > 64) return QG_EINVAL;
   if (plan[0] == 1 || plan[0] == 3) plan_streaming((int)(M < 64 ? M : 64), (int)N, (int)K, (int)group, wt, &plan[1], &plan[3], &plan[4]);
-  else plan_tiled(M, N, K, t.bits, &plan[2], &plan[3], &plan[4]);
+  else plan_tiled(M, N, K, t, &plan[2], &plan[3], &plan[4]);
   return QG_OK;
 }
 

@@ -100,6 +100,18 @@ def test_config4_low_bit_floats_full(bits):
         f.check_gemm(_A_of(WL.cfg4(bits, M)), wr, f"cfg4 f{bits} M={M}")
 
 
+@pytest.mark.parametrize("bits", [3, 8])
+def test_config3_shape_at_33_to_64_rows_full(bits):
+    # K = 8192, N = 28672 with 40 and 64 rows: the tiled kernel on 64-row tiles with K split in
+    # two, which the library prefers to the streaming kernel there
+    f = FullCase(WL.cfg3(bits))
+    wr = f.check_weights()
+    for M in (40, 64):
+        plan = f.B.qg_plan(f.wtype, f.case.group, M, f.case.N, f.case.K)
+        assert (plan["path"], plan["row_tile"]) == (2, 64), plan
+        f.check_gemm(_A_of(WL.shrink(WL.cfg3(bits), M=M, name=f"cfg3_i{bits}_M{M}")), wr, f"cfg3 int{bits} M={M}")
+
+
 @pytest.mark.parametrize("bits", [4, 6])
 def test_config4_shape_at_moderate_m_full(bits):
     # K = N = 8192 with 128 / 256 / 512 rows: the shapes on which the tiled kernel splits K

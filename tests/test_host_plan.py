@@ -20,7 +20,7 @@ def _reset_knobs():
 
 def test_small_m_streams_and_large_m_tiles():
     assert B.qg_plan(U4, 128, 1, 14336, 4096)["path"] == 1
-    assert B.qg_plan(U4, 128, 64, 14336, 4096)["path"] == 1
+    assert B.qg_plan(U4, 128, 32, 14336, 4096)["path"] == 1
     assert B.qg_plan(U4, 128, 65, 14336, 4096)["path"] == 2
     assert B.qg_plan(U4, 128, 4096, 57344, 8192) == {"path": 2, "variant": 0, "row_tile": 0, "splitk": 1,
                                                      "chunks_per_slab": 64}
@@ -61,6 +61,24 @@ def test_tiled_plan_invariants(M, N, K, bits):
         assert tiles * sk <= 256                                     # one workgroup per CU at most
     if p["row_tile"] == 0:
         assert -(-M // 128) * -(-N // 256) > 128                     # big enough to fill the chip unsplit
+
+
+def test_33_to_64_rows_take_the_tiled_kernel_on_all_but_small_problems():
+    F6 = B.WType(B.QG_FLOAT, 6, 3, 2)
+    for M in (33, 48, 64):
+        # measured: tiled split-K faster (K = 8192, N = 28672: 57 against 71 us at 4 bits)
+        for K, N, sk in ((8192, 28672, 2), (8192, 14336, 4), (28672, 8192, 8), (8192, 57344, 1), (1024, 57344, 1)):
+            p = B.qg_plan(U4, 128, M, N, K)
+            assert (p["path"], p["row_tile"], p["splitk"]) == (2, 64, sk), (M, K, N, p)
+        # measured: streaming kernel faster or equal
+        for K, N in ((8192, 8192), (4096, 4096), (14336, 4096), (2048, 8192), (128, 64)):
+            assert B.qg_plan(U4, 128, M, N, K)["path"] == 1, (M, K, N)
+        # float codes unpack more slowly in the tiled kernel: e3m2 stays on the streaming kernel
+        assert B.qg_plan(F6, 128, M, 28672, 8192, act=B.QG_BF16)["path"] == 1
+    for M in (1, 16, 32):
+        assert B.qg_plan(U4, 128, M, 28672, 8192)["path"] == 1
+    B.qg_set_knob(3, 41)                                   # a forced arrangement keeps the streaming kernel
+    assert B.qg_plan(U4, 128, 64, 28672, 8192)["path"] == 1
 
 
 def test_split_k_choices_of_the_measured_shapes():
