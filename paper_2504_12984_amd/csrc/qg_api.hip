@@ -127,9 +127,25 @@ static int check_common(qg_wtype t, int layout, int act, int scale_dtype, int64_
 static void plan_streaming(int M, int N, int K, int group, int wt, int* variant_out, int* splitk_out, int* cps_out) {
   const int KC = K / TILE_K, NCH = N / TILE_N;
   const int mt = M <= 16 ? 1 : (M <= 32 ? 2 : 4);
-  // 16 wavefronts per strip for one row tile and short K (two chunks per wavefront,
-  // every load of the strip in flight at once), 4 wavefronts otherwise
-  int variant = 10 * mt + ((mt == 1 && KC <= 32) ? 2 : 1);
+  int variant = 10 * mt + 1;                  // 4 wavefronts on one strip
+  // One row tile, short K (at most 32 chunks): as many wavefronts per strip as leaves each
+  // two chunks -- 16 (every load of the strip in flight at once) up to 4-bit codes, whose
+  // ring fits the 128 registers 16 wavefronts leave each; 8 from 16 chunks on; else 4.
+  // With enough strips for pairs of them, two strips per workgroup as for long K below
+  // (measured on K = 1024 .. 4096, N = 8192 .. 57344, 3, 4 and 8 bits: within 10 % of the
+  // best arrangement everywhere; 16 wavefronts on wide codes or one-chunk shares cost 2-3x).
+  if (mt == 1 && KC <= 32) {
+    const int bits = wt_bits(wt);
+    if (NCH % 2 == 0 && NCH / 2 >= 192) {
+      variant = 14;
+      if (bits <= 6 && group != 64 && KC >= 16) variant = 15;
+      if (variant == 15 && NCH % 4 == 0 && NCH / 4 >= 192) variant = 16;
+    } else if (KC >= 32 && bits <= 4 && NCH >= 192) {      // enough strips to occupy most CUs unsplit
+      variant = 12;
+    } else if (KC >= 16) {
+      variant = 10;
+    }
+  }
   // long K and enough strips to fill the chip with pairs of them: 8 wavefronts on 2
   // adjacent strips, 4 along K each -- wavefronts at the same K position share
   // their A rows in the vector cache (measured 2-4 % shorter at K = 8192, N = 28672;
@@ -137,10 +153,10 @@ static void plan_streaming(int M, int N, int K, int group, int wt, int* variant_
   if (KC > 32 && NCH % 2 == 0 && NCH / 2 >= 192) variant = (mt == 1) ? 14 : (mt == 2) ? 26 : 46;
   // up to 6 bits per code a wavefront needs few enough registers for 16 of them per
   // workgroup (2 strips x 8 along K): twice the wavefronts in flight, 1-6 % shorter
-  if (variant == 14 && wt_bits(wt) <= 6 && group != 64) variant = 15;
+  if (KC > 32 && variant == 14 && wt_bits(wt) <= 6 && group != 64) variant = 15;
   // and with enough strips for groups of four: 4 strips x 4 along K, half as many, twice as
   // long-lived workgroups (measured 5-9 % shorter at K = 8192, N = 57344, 2 to 6 bits)
-  if (variant == 15 && NCH % 4 == 0 && NCH / 4 >= 192) variant = 16;
+  if (KC > 32 && variant == 15 && NCH % 4 == 0 && NCH / 4 >= 192) variant = 16;
   // long K but too few strips to fill the chip (K is split over workgroups below): more
   // wavefronts per strip for narrow codes -- 16 up to 4 bits, 8 up to 6 (measured on
   // K = N = 8192: 11 % and 7 % shorter at 4 bits, no gain at 8)
@@ -149,11 +165,13 @@ static void plan_streaming(int M, int N, int K, int group, int wt, int* variant_
   if (group == 32) variant = 10 * mt + 1;          // four groups per chunk: the 4-wavefront arrangements only
   const int waves = kDecodeWaves[wt](variant);
   // Split K over workgroups only when the column strips alone cannot fill the
-  // 256 CUs, and never below 4 chunks per wavefront (2 with 16 wavefronts per strip).
+  // 256 CUs, and never below 4 chunks per wavefront (2 with 16 wavefronts per strip, or with a
+  // short K on at most 128 strips: K = 4096, N = 4096 .. 8192 is 15-25 % shorter with 8
+  // wavefronts and K in two).
   int splitk = g_knob[1];
   if (splitk <= 0) {
     splitk = 1;
-    const int min_chunks = (waves >= 16) ? 2 : 4;      // per wavefront
+    const int min_chunks = (waves >= 16 || (KC <= 32 && NCH <= 128)) ? 2 : 4;      // per wavefront
     while (NCH * splitk < 256 && KC / (splitk * 2) >= min_chunks * waves) splitk *= 2;
   }
   if (splitk > KC) splitk = KC;

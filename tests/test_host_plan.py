@@ -39,6 +39,17 @@ def test_streaming_arrangements_of_the_named_workloads():
     # K = N = 8192: 128 strips cannot fill 256 CUs -> K is split over workgroups
     p = B.qg_plan(U4, 128, 1, 8192, 8192)
     assert p["variant"] == 12 and p["splitk"] == 2 and p["chunks_per_slab"] == 32
+    # short K: wavefronts per strip so that each keeps two chunks, 16 only for narrow codes on
+    # enough strips, pairs of strips when there are many (measured: 16 wavefronts on 8-bit
+    # codes or on 8-chunk strips cost 2-3x)
+    assert B.qg_plan(U8, 128, 16, 14336, 4096)["variant"] == 10
+    assert B.qg_plan(U8, 128, 16, 28672, 4096)["variant"] == 14
+    assert B.qg_plan(U4, 128, 16, 28672, 4096)["variant"] == 15
+    assert B.qg_plan(U4, 128, 16, 57344, 1024)["variant"] == 14
+    assert B.qg_plan(U4, 128, 16, 57344, 2048)["variant"] == 16
+    assert B.qg_plan(U4, 128, 16, 14336, 1024)["variant"] == 11
+    p = B.qg_plan(U4, 128, 16, 4096, 4096)
+    assert (p["variant"], p["splitk"]) == (10, 2)
     # 17..32 and 33..64 rows: 2 and 4 row tiles per wavefront
     assert B.qg_plan(U4, 128, 32, 8192, 8192)["variant"] // 10 == 2
     assert B.qg_plan(U4, 128, 64, 8192, 8192)["variant"] // 10 == 4
