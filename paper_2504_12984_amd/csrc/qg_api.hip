@@ -160,7 +160,11 @@ static void plan_streaming(int M, int N, int K, int group, int wt, int* variant_
   // long K but too few strips to fill the chip (K is split over workgroups below): more
   // wavefronts per strip for narrow codes -- 16 up to 4 bits, 8 up to 6 (measured on
   // K = N = 8192: 11 % and 7 % shorter at 4 bits, no gain at 8)
-  if (variant == 11 && KC > 32 && NCH < 256) variant = wt_bits(wt) <= 4 ? 12 : (wt_bits(wt) <= 6 ? 10 : 11);
+  if (variant == 11 && KC > 32 && NCH <= 128) variant = wt_bits(wt) <= 4 ? 12 : (wt_bits(wt) <= 6 ? 10 : 11);
+  // between 128 and 256 strips a split in two gives more workgroups than CUs: 8-wavefront
+  // workgroups, two of which share a CU (K = 8192, N = 14336: 16.3 us against 19.3 with 16
+  // wavefronts at 3 bits; 8-bit codes: two strips x 4 wavefronts, 23.5 against 27.3)
+  if (variant == 11 && KC > 32 && NCH > 128 && NCH < 256) variant = wt_bits(wt) <= 6 ? 10 : (NCH % 2 == 0 ? 14 : 11);
   if (g_knob[3] > 0) variant = g_knob[3];
   if (group == 32) variant = 10 * mt + 1;          // four groups per chunk: the 4-wavefront arrangements only
   const int waves = kDecodeWaves[wt](variant);
@@ -173,6 +177,9 @@ static void plan_streaming(int M, int N, int K, int group, int wt, int* variant_
     splitk = 1;
     const int min_chunks = (waves >= 16 || (KC <= 32 && NCH <= 128)) ? 2 : 4;      // per wavefront
     while (NCH * splitk < 256 && KC / (splitk * 2) >= min_chunks * waves) splitk *= 2;
+    // long K and still at most half of the CUs busy: K in four, down to one chunk per wavefront
+    // (K = 14336, N = 4096: 11.0 us against 16.2 with K in two; deeper splits lose to the exchange)
+    while (KC > 32 && splitk < 4 && NCH * splitk <= 128 && KC / (splitk * 2) >= waves) splitk *= 2;
   }
   if (splitk > KC) splitk = KC;
   const int cps = (KC + splitk - 1) / splitk;

@@ -50,6 +50,14 @@ def test_streaming_arrangements_of_the_named_workloads():
     assert B.qg_plan(U4, 128, 16, 14336, 1024)["variant"] == 11
     p = B.qg_plan(U4, 128, 16, 4096, 4096)
     assert (p["variant"], p["splitk"]) == (10, 2)
+    # long K on few strips: K in four even at under two chunks per wavefront, never deeper for it;
+    # between 128 and 256 strips 8-wavefront workgroups (two share a CU) instead of 16
+    p = B.qg_plan(U4, 128, 16, 4096, 14336)
+    assert (p["variant"], p["splitk"]) == (12, 4)
+    assert B.qg_plan(U8, 128, 16, 1024, 8192)["splitk"] == 4
+    p = B.qg_plan(U4, 128, 16, 14336, 8192)
+    assert (p["variant"], p["splitk"]) == (10, 2)
+    assert B.qg_plan(U8, 128, 16, 14336, 8192)["variant"] == 14
     # 17..32 and 33..64 rows: 2 and 4 row tiles per wavefront
     assert B.qg_plan(U4, 128, 32, 8192, 8192)["variant"] // 10 == 2
     assert B.qg_plan(U4, 128, 64, 8192, 8192)["variant"] // 10 == 4
