@@ -150,7 +150,8 @@ static void plan_streaming(int M, int N, int K, int group, int wt, int* variant_
   // adjacent strips, 4 along K each -- wavefronts at the same K position share
   // their A rows in the vector cache (measured 2-4 % shorter at K = 8192, N = 28672;
   // with 2 or 4 row tiles: 2 strips x 2 wavefronts along K, 10-15 % shorter)
-  if (KC > 32 && NCH % 2 == 0 && NCH / 2 >= 192) variant = (mt == 1) ? 14 : (mt == 2) ? 26 : 46;
+  // (with several row tiles also for short K: K = 4096, N = 28672, M = 24: 20.8 us against 22.4)
+  if ((KC > 32 || mt > 1) && NCH % 2 == 0 && NCH / 2 >= 192) variant = (mt == 1) ? 14 : (mt == 2) ? 26 : 46;
   // up to 6 bits per code a wavefront needs few enough registers for 16 of them per
   // workgroup (2 strips x 8 along K): twice the wavefronts in flight, 1-6 % shorter
   if (KC > 32 && variant == 14 && wt_bits(wt) <= 6 && group != 64) variant = 15;
@@ -176,7 +177,9 @@ static void plan_streaming(int M, int N, int K, int group, int wt, int* variant_
   if (splitk <= 0) {
     splitk = 1;
     const int min_chunks = (waves >= 16 || (KC <= 32 && NCH <= 128)) ? 2 : 4;      // per wavefront
-    while (NCH * splitk < 256 && KC / (splitk * 2) >= min_chunks * waves) splitk *= 2;
+    // (several row tiles on 192 or more strips: no split -- K = 4096, N = 14336, M = 24 takes
+    // 12.1 us unsplit against 14.7 in two)
+    while (NCH * splitk < 256 && !(mt > 1 && NCH >= 192) && KC / (splitk * 2) >= min_chunks * waves) splitk *= 2;
     // long K and still at most half of the CUs busy: K in four, down to one chunk per wavefront
     // (K = 14336, N = 4096: 11.0 us against 16.2 with K in two; deeper splits lose to the exchange)
     while (KC > 32 && splitk < 4 && NCH * splitk <= 128 && KC / (splitk * 2) >= waves) splitk *= 2;

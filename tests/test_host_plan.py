@@ -58,6 +58,10 @@ def test_streaming_arrangements_of_the_named_workloads():
     p = B.qg_plan(U4, 128, 16, 14336, 8192)
     assert (p["variant"], p["splitk"]) == (10, 2)
     assert B.qg_plan(U8, 128, 16, 14336, 8192)["variant"] == 14
+    # several row tiles: pairs of strips whatever the length of K, no split on 192 strips or more
+    assert B.qg_plan(U4, 128, 24, 28672, 4096)["variant"] == 26
+    p = B.qg_plan(U4, 128, 24, 14336, 4096)
+    assert (p["variant"], p["splitk"]) == (21, 1)
     # 17..32 and 33..64 rows: 2 and 4 row tiles per wavefront
     assert B.qg_plan(U4, 128, 32, 8192, 8192)["variant"] // 10 == 2
     assert B.qg_plan(U4, 128, 64, 8192, 8192)["variant"] // 10 == 4
