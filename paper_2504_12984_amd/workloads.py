@@ -8,7 +8,8 @@ The paper benchmarks matmul shapes taken from LLM layers with dummy weights and
 inputs (Section "Performance of Low-Precision Kernels", artifact appendix "Data
 sets"); the cases below are dense i.i.d. stand-ins of those shapes.
 
-Draw order per case, from numpy Generator(PCG64(seed)):  A, codes, scales.
+Draw order per case, from numpy Generator(PCG64(seed)):  A, codes, scales, then
+(only when they are random) the zero-points.
 """
 from __future__ import annotations
 
@@ -35,7 +36,9 @@ class Case:
     group: int = 128            # rows of W per scale; == K means per output channel
     act: str = "f16"            # dtype of A, C and of the de-quantised weights
     scale_dtype: str = "f16"
-    zero: Optional[int] = None  # constant zero-point, None = no zero-point array
+    zero: Optional[object] = None   # constant zero-point; "random": one draw per (group, column),
+                                    # uniform over 0 .. zero_hi; None = no zero-point array
+    zero_hi: Optional[int] = None   # largest random zero-point (default 2^bits - 1)
     scale_lo: float = 0.005
     scale_hi: float = 0.02
     seed: int = 0
@@ -63,7 +66,8 @@ def make_inputs(case: Case):
            finite encodings (for intk: two's-complement patterns, i.e. values
            uniform over [-2^(k-1), 2^(k-1)-1])
     scales torch CPU tensor [K/group, N] of case.scale_dtype, U(lo, hi)
-    zeros  numpy uint8 [K/group, N] filled with case.zero, or None
+    zeros  numpy uint8 [K/group, N] filled with case.zero -- or, for zero == "random",
+           drawn uniformly from 0 .. zero_hi per (group, column) -- or None
     """
     rng = np.random.Generator(np.random.PCG64(case.seed))
     A = torch.from_numpy(rng.standard_normal((case.M, case.K), dtype=np.float32)).to(_TORCH[case.act])
@@ -76,7 +80,13 @@ def make_inputs(case: Case):
     G = case.K // case.group
     s = rng.uniform(case.scale_lo, case.scale_hi, size=(G, case.N)).astype(np.float32)
     scales = torch.from_numpy(s).to(_TORCH[case.scale_dtype])
-    zeros = None if case.zero is None else np.full((G, case.N), case.zero, dtype=np.uint8)
+    if case.zero is None:
+        zeros = None
+    elif case.zero == "random":
+        hi = (1 << case.bits) - 1 if case.zero_hi is None else case.zero_hi
+        zeros = rng.integers(0, hi + 1, size=(G, case.N), dtype=np.uint8)
+    else:
+        zeros = np.full((G, case.N), case.zero, dtype=np.uint8)
     return {"A": A, "codes": codes, "scales": scales, "zeros": zeros}
 
 

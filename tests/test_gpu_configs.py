@@ -9,6 +9,11 @@ The oracle cannot produce 10^8..10^9 outputs in seconds, so each case checks
     only, so a sampled column is checked exactly as in a full comparison).
 Weights of one (config, type) are drawn once and shared by its M values; A is
 drawn per M from that case's own seed.
+
+The other cut -- ALL N columns on a subset of rows (rows of C are independent, so
+a row is checked exactly as in a full comparison) -- covers every workgroup, every
+64-column strip, every L2 panel and both launches of a split tiled call: all rows
+for the decode-sized configurations, 64 seeded rows of each M for the prefill one.
 """
 import numpy as np
 import pytest
@@ -69,6 +74,69 @@ class FullCase:
         ref = O.gemm_fp64(to_f64(A), wr)
         ok = O.within_tolerance(got, ref)
         assert ok.all(), f"{tag}: {(~ok).sum()} of {ok.size} sampled outputs outside tolerance"
+
+
+    def check_gemm_all_columns(self, runs, tag: str, layouts=(0,)):
+        """runs: list of (A [M, K] torch, rows to compare); one oracle pass over all N columns
+        serves every run (their compared rows are stacked), each layout is then compared with it."""
+        c = self.case
+        stacked = np.concatenate([to_f64(A)[rows] for A, rows in runs], axis=0)
+        ref = O.qgemm_from_stream(stacked, self.stream, c.kind, c.bits, c.ebits, c.mbits, self.S64, self.inp["zeros"],
+                                  c.group, c.K, c.N, c.act)
+        for layout in layouts:
+            packed = self.d_packed if layout == self.layout else \
+                self.B.repack(torch.from_numpy(self.stream).cuda(), self.wtype, c.K, c.N, layout=layout)
+            at = 0
+            for A, rows in runs:
+                C = self.B.qgemm(A.cuda(), packed, self.d_scales, self.d_zeros, self.wtype, c.group, c.N, layout=layout)
+                got = to_f64(C[torch.from_numpy(rows).cuda()])
+                del C
+                ok = O.within_tolerance(got, ref[at:at + rows.size])
+                assert ok.all(), (f"{tag} M={A.shape[0]} layout {layout}: {(~ok).sum()} of {ok.size} outputs outside "
+                                  f"tolerance, first at row {rows[np.argwhere(~ok)[0][0]]} column {np.argwhere(~ok)[0][1]}")
+                at += rows.size
+            del packed
+
+
+def _seeded_rows(M: int, count: int, seed: int) -> np.ndarray:
+    """`count` distinct rows of 0..M-1: the first and last, the two sides of the 256-row tile
+    boundaries nearest the middle, and seeded random ones."""
+    if M <= count:
+        return np.arange(M)
+    fixed = np.array([0, 1, M - 1, M - 2, 255, 256, (M // 512) * 256 - 1, (M // 512) * 256])
+    rng = np.random.default_rng(seed)
+    rows = np.unique(np.concatenate([fixed, rng.choice(M, size=count, replace=False)]))
+    keep = np.concatenate([fixed, np.setdiff1d(rows, fixed)])[:count]
+    return np.sort(np.unique(keep))
+
+
+def test_config2_w3a16_decode_all_columns():
+    f = FullCase(WL.cfg2(1))
+    f.check_gemm_all_columns([(_A_of(WL.cfg2(M)), np.arange(M)) for M in (1, 4, 16)], "cfg2 all columns")
+
+
+@pytest.mark.parametrize("bits", [1, 3, 4, 8])
+def test_config3_signed_all_columns(bits):
+    f = FullCase(WL.cfg3(bits))
+    f.check_gemm_all_columns([(f.inp["A"], np.arange(16))], f"cfg3 int{bits} all columns")
+
+
+def test_config4_e3m2_all_columns():
+    f = FullCase(WL.cfg4(6, 1))
+    f.check_gemm_all_columns([(_A_of(WL.cfg4(6, M)), np.arange(M)) for M in (1, 16, 64)], "cfg4 e3m2 all columns")
+
+
+def test_config5_prefill_u6_all_columns_on_64_rows_both_layouts():
+    f = FullCase(WL.cfg5(6, 1024))
+    runs = [(_A_of(WL.cfg5(6, M)), _seeded_rows(M, 64, 5600 + M)) for M in (1024, 4096)]
+    assert all(r.size == 64 for _, r in runs)
+    f.check_gemm_all_columns(runs, "cfg5 u6 all columns", layouts=(0, 1))
+
+
+def test_config5_prefill_u5_all_columns_on_64_rows():
+    f = FullCase(WL.cfg5(5, 1024))
+    runs = [(_A_of(WL.cfg5(5, M)), _seeded_rows(M, 64, 5500 + M)) for M in (1024, 4096)]
+    f.check_gemm_all_columns(runs, "cfg5 u5 all columns")
 
 
 def test_config2_w3a16_decode_full():

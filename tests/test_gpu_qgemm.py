@@ -297,6 +297,33 @@ def test_tiled_path_split_into_whole_rounds_plus_remainder(layout):
     assert_c_close(got[:, torch.from_numpy(cols).cuda()], P.oracle_c(cols=cols), case.name)
 
 
+@pytest.mark.parametrize("kernel", ["streaming", "tiled64", "tiled128"])
+def test_split_k_workspace_reused_by_different_inputs_back_to_back(kernel):
+    # Calls with DIFFERENT inputs go through the same workspace slots and arrival counters
+    # one after the other on one stream with nothing in between (X, Y, Z, X, Y; X and Y have
+    # the same shape, Z another one whose tiles overlap theirs): the last arriver of a call
+    # must sum this call's partial tiles, never what an earlier call left in the workspace
+    # or in a cache.  Every result is compared with the oracle.
+    from paper_2504_12984_amd import binding as B
+    if kernel == "streaming":
+        mk = lambda tag, K, N, seed: WL.Case(f"xyx_s_{tag}", 16, K, N, U, 4, group=128, zero="random", seed=seed)
+        B.qg_set_knob(0, 1); B.qg_set_knob(1, 4)
+    else:
+        mk = lambda tag, K, N, seed: WL.Case(f"xyx_t_{tag}", 100, K, N, U, 4, group=128, act="bf16",
+                                             scale_dtype="bf16", zero="random", seed=seed)
+        B.qg_set_knob(0, 2); B.qg_set_knob(1, 4); B.qg_set_knob(2, 64 if kernel == "tiled64" else 128)
+    X, Y, Z = Prepared(mk("X", 2048, 512, 9200)), Prepared(mk("Y", 2048, 512, 9201)), Prepared(mk("Z", 1536, 320, 9202))
+    refs = {id(P): P.oracle_c() for P in (X, Y, Z)}
+    assert not np.allclose(refs[id(X)], refs[id(Y)])
+    order = [X, Y, Z, X, Y]
+    torch.cuda.synchronize()
+    outs = [P.gpu_c() for P in order]                # enqueued back to back, no synchronisation
+    torch.cuda.synchronize()
+    for i, (P, C) in enumerate(zip(order, outs)):
+        assert_c_close(C, refs[id(P)], f"{P.case.name} call {i}")
+    assert np.array_equal(bits_of(outs[0]), bits_of(outs[3])) and np.array_equal(bits_of(outs[1]), bits_of(outs[4]))
+
+
 # ------------------------------------------------------------------ binding extras
 def test_split_k_calls_on_two_streams_keep_separate_workspaces():
     # a streaming split-K matmul and a tiled split-K matmul enqueued alternately on two

@@ -1,7 +1,8 @@
 """GPU parity, part 4: seeded random shapes, types, group sizes and layouts with
 the library's automatic choices (no knobs), so that every dispatch rule -- row
 tiles, strips per workgroup, split-K, row blocks, tile heights, split launches --
-is crossed with ragged sizes.  A second family has long K (1024 .. 8192), where
+is crossed with ragged sizes; two integer cases in three carry a different zero-point per
+(group, column).  A second family has long K (1024 .. 8192), where
 the tiled kernel splits K into slabs of various lengths.  Each case is compared
 in full with the oracle, |C_gpu - C_ref| <= 1e-2 + 5e-3 |C_ref| elementwise."""
 import numpy as np
@@ -38,8 +39,12 @@ def _random_case(seed: int) -> tuple[WL.Case, int]:
     layout = int(rng.integers(0, 2))
     if layout == 0 and rng.integers(0, 4) == 0:        # group size 32 exists on the first layout only
         group = 32
+    zero_hi = None
+    if kind != WL.KIND_FLOAT and rng.integers(0, 3) > 0:      # two integer cases in three: a zero-point per (group, column)
+        zero, zero_hi = "random", int(rng.choice([(1 << bits) - 1, 255]))
     case = WL.Case(f"rand{seed}_k{kind}b{bits}_M{M}_K{K}_N{N}_g{group}_{act}_L{layout}", M, K, N, kind, bits, e, m,
-                   group=group, act=act, scale_dtype=sdt, zero=zero, scale_lo=lo, scale_hi=hi, seed=91000 + seed)
+                   group=group, act=act, scale_dtype=sdt, zero=zero, zero_hi=zero_hi, scale_lo=lo, scale_hi=hi,
+                   seed=91000 + seed)
     return case, layout
 
 
@@ -70,8 +75,11 @@ def _random_long_k_case(seed: int) -> WL.Case:
     else:
         zero = None
     lo, hi = (0.01, 0.1) if kind == WL.KIND_FLOAT else (0.005, 0.02)
+    zero_hi = None
+    if kind != WL.KIND_FLOAT and rng.integers(0, 3) > 0:      # two integer cases in three: a zero-point per (group, column)
+        zero, zero_hi = "random", int(rng.choice([(1 << bits) - 1, 255]))
     return WL.Case(f"big{seed}_k{kind}b{bits}_M{M}_K{K}_N{N}_g{group}_{act}", M, K, N, kind, bits, e, m, group=group,
-                   act=act, scale_dtype=sdt, zero=zero, scale_lo=lo, scale_hi=hi, seed=771000 + seed)
+                   act=act, scale_dtype=sdt, zero=zero, zero_hi=zero_hi, scale_lo=lo, scale_hi=hi, seed=771000 + seed)
 
 
 @pytest.mark.parametrize("seed", range(16))
