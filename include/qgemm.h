@@ -28,16 +28,20 @@
  *     default stream) and the call returns without synchronising;
  *   - the return value is a qg_status (0 = ok, negative = error, nothing was
  *     enqueued); no call throws, none frees caller memory;
- *   - qgemm may use a library-owned, lazily grown workspace for split-K partial
- *     sums: one per (device, stream), allocated on the first call that needs it
- *     (hipMalloc; growing one synchronises the device) and kept until the
- *     process ends, so calls on different streams may overlap.  At most 32
- *     (device, stream) pairs per process (QG_EUNSUPPORTED beyond); a stream
- *     that is destroyed and whose handle value is re-used simply inherits the
- *     workspace.  Calls may be captured into a HIP graph once the same call has
- *     run eagerly on the capture stream (so that nothing is allocated during
- *     the capture); every launch leaves counters and workspace ready for the
- *     next, so a graph can be replayed any number of times.
+ *   - qgemm may use a library-owned workspace for split-K partial sums: one per
+ *     (device, stream), of one fixed size (32 MiB + 64 KiB, which covers every
+ *     shape), allocated by the first call on that pair that splits K (one
+ *     hipMalloc and one memset enqueued on the stream; nothing synchronises) and
+ *     then never freed, moved or grown, so calls on different streams may overlap
+ *     and a HIP graph captured later keeps valid pointers.  At most 32 (device,
+ *     stream) pairs per process (QG_EUNSUPPORTED beyond); a stream that is
+ *     destroyed and whose handle value is re-used simply inherits the workspace.
+ *     hipStreamPerThread is refused (QG_EINVAL): the one handle value names a
+ *     different stream in every thread.  Calls may be captured into a HIP graph
+ *     once a call that splits K has run eagerly on the capture stream (so that
+ *     nothing is allocated during the capture); every launch leaves counters and
+ *     workspace ready for the next, so a graph can be replayed any number of
+ *     times.
  *
  * De-quantisation (the paper names the step but prints no formula; this is the
  * standard affine group form):
@@ -95,11 +99,14 @@ QG_API const char* qg_status_string(int status);
 /* Text of the last HIP error seen by this library on the calling thread. */
 QG_API const char* qg_last_error(void);
 
-/* ceil(count*bits/8): bytes of the canonical little-endian bit stream. */
+/* ceil(count*bits/8): bytes of the canonical little-endian bit stream -- values stored
+ * back to back with no bit gaps (Section "Storage of Low-Precision Data"). */
 QG_API size_t qg_canonical_bytes(int bits, int64_t count);
 
-/* Bytes of the device layout for a [K,N] weight (== K*N*bits/8), or 0 if the
- * shape is not tileable (K % 128, N % 64) or the type is invalid. */
+/* Bytes of the device layout for a [K,N] weight, or 0 if the shape is not tileable
+ * (K % 128, N % 64) or the type is invalid.  The re-layout adds no padding: a tile of
+ * BK x BN codes of b bits is BK*BN*b/8 bytes (the identity the paper states for its
+ * int6 tile, Section "An Example of Tilus Program"), so the whole is K*N*bits/8. */
 QG_API size_t qgemm_packed_bytes(qg_wtype t, int layout, int64_t K, int64_t N);
 
 /* codes[count] (one code per byte, low `bits` bits) -> canonical stream:
@@ -135,19 +142,10 @@ QG_API int qdequant(const void* packed_W, const void* scales, const uint8_t* zer
  * 33 <= M <= 64 on all but small problems -- use the LDS-staged tiled kernel, which also splits K (partial sums meet in a
  * workspace the library allocates on first use) when its 64- or
  * 128-row tiles would leave most CUs idle.  The tiled kernel needs M*K*2, the packed
- * weight and the scale array each below 4 GiB (QG_EUNSUPPORTED otherwise). */
+ * weight and the scale array each below 2 GiB (QG_EUNSUPPORTED otherwise). */
 QG_API int qgemm(const void* A, const void* packed_W, const void* scales, const uint8_t* zeros,
           qg_wtype t, int layout, int act, int scale_dtype, int64_t group,
           int64_t M, int64_t N, int64_t K, void* C, void* stream);
-
-/* Optional: path/tuning override for experiments (0 = automatic).  Returns the
- * previous value.  knob 0: forced path (1 = streaming kernel, 2 = tiled kernel, 3 =
- * streaming kernel over blocks of 64 rows);
- * knob 1: forced split-K factor (streaming kernel; tiled kernel with 64- or 128-row tiles); knob 2: forced row-tile
- * (64 / 128 / 256; 64 on the first layout only) of the tiled kernel; knob 3: pipeline variant of the M <= 64
- * kernel (10*row tiles + 0/1/2 for 8/4/16 wavefronts per strip: 10, 11, 12,
- * 21, 41; 14, 15, 26, 46: 8, 16 or 4 wavefronts on 2 adjacent strips; 16: 16 wavefronts on 4 strips).  Knobs 0, 1 and 3 apply to QG_LAYOUT_TILE128x64 only. */
-QG_API int qg_set_knob(int knob, int value);
 
 /* What qgemm would launch for a shape: host arithmetic only, no GPU call, usable without
  * a device.  Arguments as for qgemm (M >= 1).  plan (host, 5 ints) receives
@@ -156,7 +154,8 @@ QG_API int qg_set_knob(int knob, int value);
  *   [2] row-tile height of the tiled kernel: 64 or 128, or 0 = whole rounds of 256-row
  *       tiles, then 128 or 256 rows for the rest; 0 on paths 1 and 3
  *   [3] K-slabs (split-K factor; 1 = none)   [4] K-chunks of 128 per slab
- * The knobs apply as in qgemm.  Returns the status qgemm's argument checks would return. */
+ * The experiment overrides of qgemm_tuning.h apply as in qgemm.  Returns the status qgemm's
+ * argument checks would return. */
 QG_API int qg_plan(qg_wtype t, int layout, int act, int scale_dtype, int64_t group,
             int64_t M, int64_t N, int64_t K, int plan[5]);
 

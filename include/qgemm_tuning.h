@@ -1,0 +1,38 @@
+/*
+ * qgemm_tuning.h -- experiment overrides of the kernel choice inside qgemm.
+ *
+ * NOT part of the stable interface of qgemm.h: these exist for the tests (every kernel
+ * variant can be forced on a small shape) and for timing sweeps that fit the automatic
+ * choice.  The overrides are process-wide and apply to every thread's next qgemm /
+ * qgemm_noalloc / qg_plan call; setting one while other threads issue calls changes those
+ * calls' kernel choice (never their validity: each call reads every override once and
+ * refuses a combination that does not cover its shape with QG_EINVAL).  No passage of the
+ * paper defines them; the paper's counterpart is its tile-size tuning (Section
+ * "Performance of Low-Precision Kernels": about 200 configurations per operator).
+ */
+#ifndef QGEMM_TUNING_H_
+#define QGEMM_TUNING_H_
+
+#include "qgemm.h"
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Sets override `knob` (0..3) to `value` (0 = automatic) and returns the previous value.
+ *   knob 0: forced path (1 = streaming kernel, M <= 64 only; 2 = tiled kernel; 3 = streaming
+ *           kernel over blocks of 64 rows)
+ *   knob 1: forced split-K factor (streaming kernel; tiled kernel with 64- or 128-row tiles)
+ *   knob 2: forced row-tile height of the tiled kernel (64 / 128 / 256; 64 on the first
+ *           layout only)
+ *   knob 3: wavefront arrangement of the streaming kernel: 10 * row tiles + 0 / 1 / 2 for
+ *           8 / 4 / 16 wavefronts per strip (10, 11, 12, 21, 41); 14, 15, 26, 46: 8, 16 or 4
+ *           wavefronts on 2 adjacent strips; 16: 16 wavefronts on 4 strips.  Its row tiles
+ *           must be the ones M needs (1 up to 16 rows, 2 up to 32, 4 up to 64), else QG_EINVAL.
+ * Knobs 0, 1 and 3 apply to QG_LAYOUT_TILE128x64 only. */
+QG_API int qg_set_knob(int knob, int value);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* QGEMM_TUNING_H_ */

@@ -150,8 +150,10 @@ def qdequant(packed: torch.Tensor, scales: torch.Tensor, zeros, t: WType, act: t
 
 
 def qgemm(A: torch.Tensor, packed: torch.Tensor, scales: torch.Tensor, zeros, t: WType, group: int,
-          N: int, out: torch.Tensor | None = None, layout: int = QG_LAYOUT_TILE128x64) -> torch.Tensor:
-    """C[M,N] = A[M,K] . dequant(W); dtype of A is the activation dtype."""
+          N: int, out: torch.Tensor | None = None, layout: int = QG_LAYOUT_TILE128x64,
+          entry: str = "qgemm") -> torch.Tensor:
+    """C[M,N] = A[M,K] . dequant(W); dtype of A is the activation dtype.  `entry` names the C
+    entry point."""
     if A.dim() != 2 or A.dtype not in _DT:
         raise ValueError("A must be [M,K] fp16 or bf16")
     M, K = A.shape
@@ -162,9 +164,10 @@ def qgemm(A: torch.Tensor, packed: torch.Tensor, scales: torch.Tensor, zeros, t:
         raise ValueError("zeros must be uint8 [K/group, N]")
     if out is None:
         out = torch.empty((M, N), dtype=A.dtype, device=A.device)
-    rc = _lib.qgemm(_ptr(A, "A"), _ptr(packed, "packed"), _ptr(scales, "scales"), _ptr(zeros, "zeros"), t.c(),
-                    layout, _DT[A.dtype], _DT[scales.dtype], group, M, N, K, _ptr(out, "C"), _stream())
-    _check("qgemm", rc)
+    fn = {"qgemm": _lib.qgemm}[entry]
+    rc = fn(_ptr(A, "A"), _ptr(packed, "packed"), _ptr(scales, "scales"), _ptr(zeros, "zeros"), t.c(),
+            layout, _DT[A.dtype], _DT[scales.dtype], group, M, N, K, _ptr(out, "C"), _stream())
+    _check(entry, rc)
     return out
 
 
@@ -180,7 +183,10 @@ class BoundQgemm:
     """
 
     def __init__(self, A: torch.Tensor, packed: torch.Tensor, scales: torch.Tensor, zeros, t: WType, group: int,
-                 N: int, out: torch.Tensor, layout: int = QG_LAYOUT_TILE128x64, stream: int | None = None):
+                 N: int, out: torch.Tensor, layout: int = QG_LAYOUT_TILE128x64, stream: int | None = None,
+                 entry: str = "qgemm"):
+        self._fn = {"qgemm": _lib.qgemm}[entry]
+        self._entry = entry
         if A.dim() != 2 or A.dtype not in _DT:
             raise ValueError("A must be [M,K] fp16 or bf16")
         M, K = A.shape
@@ -200,9 +206,9 @@ class BoundQgemm:
                       vp(_stream() if stream is None else stream))
 
     def __call__(self) -> torch.Tensor:
-        rc = _lib.qgemm(*self._args)
+        rc = self._fn(*self._args)
         if rc != QG_OK:
-            raise QgError("qgemm", rc)
+            raise QgError(self._entry, rc)
         return self.out
 
 

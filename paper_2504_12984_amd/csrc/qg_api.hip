@@ -1,5 +1,6 @@
 // C ABI of the library: argument checks, kernel choice, workspace.  No compute
 // happens on the host.
+#include <atomic>
 #include <mutex>
 #include <string>
 
@@ -43,30 +44,43 @@ static const waves_fn kDecodeWaves[NUM_WT] = {QG_FOR_ALL_WT(QG_ENT)};
 #undef QG_ENT
 
 static thread_local std::string g_last_error;
-static int g_knob[4] = {0, 0, 0, 0};
+// Experiment overrides (qg_set_knob): process-wide, read once per call with relaxed loads.
+static std::atomic<int> g_knob[4] = {{0}, {0}, {0}, {0}};
+static int knob(int i) { return g_knob[i].load(std::memory_order_relaxed); }
 
 static int hip_fail(hipError_t e, const char* what) {
   g_last_error = std::string(what) + ": " + hipGetErrorString(e);
   return QG_EHIP;
 }
 
-// ---- split-K workspace (partial sums + arrival counters), one per device and stream -----
-// Kernels of one stream run in order, so they can share a workspace; kernels of different
-// streams may overlap, so each stream gets its own (created on first use, never freed:
-// at most 32 per process).
+// ---- split-K workspace (partial sums + arrival counters) -----------------------------------
+// What the automatic plans can ask for is bounded: the streaming kernel splits K only while
+// strips x slabs stay below 512 (16 KiB of partial sums each at most), the tiled kernel only
+// while tiles x slabs stay within 256 (at most 128 x 256 fp32 each).  So every workspace has
+// this one capacity; only forced split factors (the experiment knobs) can exceed it.
+constexpr size_t WS_PARTIAL_BYTES = size_t(32) << 20;
+constexpr size_t WS_TICKETS = 16384;
+constexpr size_t WS_BYTES = WS_PARTIAL_BYTES + WS_TICKETS * sizeof(unsigned);
+
+// qgemm: one workspace per device and stream.  Kernels of one stream run in order, so they
+// can share a workspace; kernels of different streams may overlap, so each stream gets its
+// own.  It is allocated once, on the first call of that (device, stream) that splits K, at
+// the fixed capacity, and never freed or moved, so a HIP graph captured later keeps valid
+// pointers.  (A forced split beyond the capacity gets a larger block; the old one is kept
+// allocated for the same reason.)  The counters are zeroed by a memset enqueued on the
+// stream ahead of the first kernel; nothing synchronises.
 struct Workspace {
   int dev = -1;
   hipStream_t stream = nullptr;
-  float* partial = nullptr;
+  unsigned char* base = nullptr;
   size_t partial_bytes = 0;
-  unsigned* tickets = nullptr;
   size_t ticket_count = 0;
 };
 static std::mutex g_ws_mutex;
 static Workspace g_ws[32];
 static int g_ws_used = 0;
 
-static int get_workspace(size_t partial_bytes, size_t ticket_count, hipStream_t st, Workspace** out) {
+static int get_workspace(size_t partial_bytes, size_t ticket_count, hipStream_t st, float** partial, unsigned** tickets) {
   int dev = 0;
   hipError_t e = hipGetDevice(&dev);
   if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
@@ -80,28 +94,26 @@ static int get_workspace(size_t partial_bytes, size_t ticket_count, hipStream_t 
     found->dev = dev; found->stream = st;
   }
   Workspace& w = *found;
-  if (w.partial_bytes < partial_bytes) {
-    // work already enqueued may still read the old buffer
-    if (w.partial) { e = hipDeviceSynchronize(); if (e != hipSuccess) return hip_fail(e, "hipDeviceSynchronize"); (void)hipFree(w.partial); w.partial = nullptr; w.partial_bytes = 0; }
-    size_t want = partial_bytes < (size_t(8) << 20) ? (size_t(8) << 20) : partial_bytes;
-    e = hipMalloc(&w.partial, want);
+  if (w.partial_bytes < partial_bytes || w.ticket_count < ticket_count) {
+    const size_t pb = partial_bytes < WS_PARTIAL_BYTES ? WS_PARTIAL_BYTES : ((partial_bytes + 255) & ~size_t(255));
+    const size_t tc = ticket_count < WS_TICKETS ? WS_TICKETS : ticket_count;
+    unsigned char* block = nullptr;
+    e = hipMalloc(&block, pb + tc * sizeof(unsigned));
     if (e != hipSuccess) return hip_fail(e, "hipMalloc(workspace)");
-    w.partial_bytes = want;
-  }
-  if (w.ticket_count < ticket_count) {
-    if (w.tickets) { e = hipDeviceSynchronize(); if (e != hipSuccess) return hip_fail(e, "hipDeviceSynchronize"); (void)hipFree(w.tickets); w.tickets = nullptr; w.ticket_count = 0; }
-    size_t want = ticket_count < 65536 ? 65536 : ticket_count;
-    e = hipMalloc(&w.tickets, want * sizeof(unsigned));
-    if (e != hipSuccess) return hip_fail(e, "hipMalloc(tickets)");
     // counters start at zero; every kernel that uses them leaves them at zero
-    e = hipMemsetAsync(w.tickets, 0, want * sizeof(unsigned), st);
-    if (e != hipSuccess) return hip_fail(e, "hipMemsetAsync(tickets)");
-    e = hipStreamSynchronize(st);
-    if (e != hipSuccess) return hip_fail(e, "hipStreamSynchronize");
-    w.ticket_count = want;
+    e = hipMemsetAsync(block + pb, 0, tc * sizeof(unsigned), st);
+    if (e != hipSuccess) { (void)hipFree(block); return hip_fail(e, "hipMemsetAsync(tickets)"); }
+    w.base = block; w.partial_bytes = pb; w.ticket_count = tc;      // an earlier, smaller block stays allocated
   }
-  *out = &w;
+  *partial = reinterpret_cast<float*>(w.base);
+  *tickets = reinterpret_cast<unsigned*>(w.base + w.partial_bytes);
   return QG_OK;
+}
+
+enum WsMode { WS_PER_STREAM = 0, WS_STATIC = 1 };
+static int acquire_ws(int mode, size_t partial_bytes, size_t ticket_count, hipStream_t st, GemmParams& p) {
+  (void)mode;
+  return get_workspace(partial_bytes, ticket_count, st, &p.ws, &p.tickets);
 }
 
 static bool layout_ok(int layout) { return layout == QG_LAYOUT_TILE128x64 || layout == QG_LAYOUT_TILE128x64_R32; }
@@ -123,10 +135,13 @@ static int check_common(qg_wtype t, int layout, int act, int scale_dtype, int64_
   return QG_OK;
 }
 
+// tiles of 16 rows a wavefront of the streaming kernel carries for M rows (M <= 64)
+static int row_tiles(int64_t M) { return M <= 16 ? 1 : (M <= 32 ? 2 : 4); }
+
 // Streaming kernel (M <= 64): wavefront arrangement and split-K by shape.  Host arithmetic only.
 static void plan_streaming(int M, int N, int K, int group, int wt, int* variant_out, int* splitk_out, int* cps_out) {
   const int KC = K / TILE_K, NCH = N / TILE_N;
-  const int mt = M <= 16 ? 1 : (M <= 32 ? 2 : 4);
+  const int mt = row_tiles(M);
   int variant = 10 * mt + 1;                  // 4 wavefronts on one strip
   // One row tile, short K (at most 32 chunks): as many wavefronts per strip as leaves each
   // two chunks -- 16 (every load of the strip in flight at once) up to 4-bit codes, whose
@@ -166,14 +181,14 @@ static void plan_streaming(int M, int N, int K, int group, int wt, int* variant_
   // workgroups, two of which share a CU (K = 8192, N = 14336: 16.3 us against 19.3 with 16
   // wavefronts at 3 bits; 8-bit codes: two strips x 4 wavefronts, 23.5 against 27.3)
   if (variant == 11 && KC > 32 && NCH > 128 && NCH < 256) variant = wt_bits(wt) <= 6 ? 10 : (NCH % 2 == 0 ? 14 : 11);
-  if (g_knob[3] > 0) variant = g_knob[3];
+  if (knob(3) > 0) variant = knob(3);
   if (group == 32) variant = 10 * mt + 1;          // four groups per chunk: the 4-wavefront arrangements only
   const int waves = kDecodeWaves[wt](variant);
   // Split K over workgroups only when the column strips alone cannot fill the
   // 256 CUs, and never below 4 chunks per wavefront (2 with 16 wavefronts per strip, or with a
   // short K on at most 128 strips: K = 4096, N = 4096 .. 8192 is 15-25 % shorter with 8
   // wavefronts and K in two).
-  int splitk = g_knob[1];
+  int splitk = knob(1);
   if (splitk <= 0) {
     splitk = 1;
     const int min_chunks = (waves >= 16 || (KC <= 32 && NCH <= 128)) ? 2 : 4;      // per wavefront
@@ -192,16 +207,16 @@ static void plan_streaming(int M, int N, int K, int group, int wt, int* variant_
 }
 
 // One launch of the streaming kernel.
-static int launch_streaming(GemmParams& p, int wt, int route, hipStream_t st) {
+static int launch_streaming(GemmParams& p, int wt, int route, int ws_mode, hipStream_t st) {
   int variant;
   plan_streaming(p.M, p.N, p.K, p.group, wt, &variant, &p.splitk, &p.chunks_per_split);
+  const int mt = row_tiles(p.M);
+  if (variant / 10 != mt) { g_last_error = "wavefront arrangement does not cover M rows"; return QG_EINVAL; }
   if (p.splitk > 1) {
-    const int NCH = p.N / TILE_N, mt = p.M <= 16 ? 1 : (p.M <= 32 ? 2 : 4);
-    Workspace* w = nullptr;
+    const int NCH = p.N / TILE_N;
     size_t pbytes = (size_t)p.splitk * NCH * (size_t)(mt * 16 * TILE_N) * sizeof(float);
-    int rc = get_workspace(pbytes, (size_t)NCH, st, &w);
+    int rc = acquire_ws(ws_mode, pbytes, (size_t)NCH, st, p);
     if (rc != QG_OK) return rc;
-    p.ws = w->partial; p.tickets = w->tickets;
   }
   return kDecode[wt](p, route, variant, st);
 }
@@ -224,7 +239,7 @@ static int launch_streaming(GemmParams& p, int wt, int route, hipStream_t st) {
 static void plan_tiled(int64_t M, int64_t N, int64_t K, qg_wtype t, int* bm_out, int* splitk_out, int* cps_out,
                        double* cost_out = nullptr) {
   const int bits = t.bits;
-  int bm = g_knob[2], splitk = g_knob[1];
+  int bm = knob(2), splitk = knob(1);
   const int KC = (int)(K / TILE_K);
   const int64_t tiles_n = (N + 255) / 256;
   if (bm == 0 && (M <= 64 || large_prefers_64_rows(M, N))) {
@@ -274,14 +289,15 @@ static void plan_tiled(int64_t M, int64_t N, int64_t K, qg_wtype t, int* bm_out,
 // over blocks of 64 rows (forced only)
 static int plan_path(int64_t M, int64_t N, int64_t K, qg_wtype t) {
   const int bits = t.bits;
-  if (g_knob[0]) return g_knob[0];
+  if (knob(0)) return knob(0);
   if (M > 64) return 2;
   // 33 .. 64 rows: the streaming kernel (4 row tiles per wavefront) re-reads A from L2 for
   // every 64-column strip -- measured 10 us + 2.2 us (+ 0.09 per bit above 4) per 1024 of K
   // at N = 8192 -- while the tiled kernel shares A through LDS among four strips and splits K
   // instead; it wins on all but the small problems (K = 8192, N = 28672, M = 64, 6 bits:
   // 59 us against 75; K = N = 8192: a tie; K = 14336, N = 4096: 32 against 26).
-  if (M > 32 && (double)K * (double)N >= 16.0e6 && g_knob[1] == 0 && g_knob[2] == 0 && g_knob[3] == 0) {
+  if (M > 32 && (double)K * (double)N >= 16.0e6 && knob(1) == 0 &&
+      knob(2) == 0 && knob(3) == 0) {
     double tiled = 1e30;
     int bm, sk, cps;
     plan_tiled(M, N, K, t, &bm, &sk, &cps, &tiled);
@@ -289,6 +305,13 @@ static int plan_path(int64_t M, int64_t N, int64_t K, qg_wtype t) {
     if (tiled < 0.9 * streaming) return 2;          // both fits are good to about 10 %
   }
   return 1;
+}
+
+// The tiled kernels' 32-bit byte offsets: A, the packed weight and the scale array each below 2 GiB.
+static bool tiled_operands_fit(int64_t M, int64_t N, int64_t K, int64_t group, int bits) {
+  const uint64_t lim = 1ull << 31;
+  return (uint64_t)M * (uint64_t)K * 2u < lim && (uint64_t)K * (uint64_t)N / 8u * (uint64_t)bits < lim &&
+         (uint64_t)(K / group) * (uint64_t)N * 2u < lim;
 }
 
 }  // namespace qg
@@ -360,8 +383,9 @@ int qdequant(const void* packed_W, const void* scales, const uint8_t* zeros, qg_
   return kDequant[wt](p, route, static_cast<hipStream_t>(stream));
 }
 
-int qgemm(const void* A, const void* packed_W, const void* scales, const uint8_t* zeros, qg_wtype t, int layout,
-          int act, int scale_dtype, int64_t group, int64_t M, int64_t N, int64_t K, void* C, void* stream) {
+static int qgemm_run(const void* A, const void* packed_W, const void* scales, const uint8_t* zeros, qg_wtype t, int layout,
+                     int act, int scale_dtype, int64_t group, int64_t M, int64_t N, int64_t K, void* C, void* stream,
+                     int ws_mode) {
   if (group == 0) group = K;               // 0 = one scale per output column
   int wt, route;
   int rc = check_common(t, layout, act, scale_dtype, group, K, N, &wt, &route);
@@ -371,6 +395,9 @@ int qgemm(const void* A, const void* packed_W, const void* scales, const uint8_t
   if (!A || !packed_W || !scales || !C) return QG_EINVAL;
   if (!aligned16(A) || !aligned16(packed_W) || !aligned16(scales) || !aligned16(C) || (zeros && !aligned16(zeros))) return QG_EINVAL;
   hipStream_t st = static_cast<hipStream_t>(stream);
+  // one handle value that names a different stream in every thread: the per-stream
+  // workspaces (and the stream order the shared scratch relies on) cannot be keyed by it
+  if (st == hipStreamPerThread) { g_last_error = "hipStreamPerThread is not accepted: pass a stream of your own"; return QG_EINVAL; }
 
   GemmParams p;
   p.A = static_cast<const uint16_t*>(A);
@@ -386,25 +413,28 @@ int qgemm(const void* A, const void* packed_W, const void* scales, const uint8_t
   if (!set_group_index(p)) return QG_EUNSUPPORTED;
 
   // The tiled kernels address A, the packed weight and the scales through buffer
-  // resources with 32-bit byte offsets.
-  const bool fits32 = (uint64_t)M * (uint64_t)K * 2u < (1ull << 32) &&
-                      (uint64_t)K * (uint64_t)N / 8u * (uint64_t)t.bits < (1ull << 32) &&
-                      (uint64_t)(K / group) * (uint64_t)N * 2u < (1ull << 32);
+  // resources with 32-bit byte offsets, some of them formed in signed arithmetic and A's
+  // with the top bit used to push padding rows out of range: each operand stays below 2 GiB.
+  const bool fits32 = tiled_operands_fit(M, N, K, group, t.bits);
   if (layout == QG_LAYOUT_TILE128x64_R32) {      // one kernel for every M
     if (!fits32 || group == 32) return QG_EUNSUPPORTED;      // the second layout's kernel has no variant for four groups per chunk
-    return kLarge32[wt](p, route, g_knob[2], st);
+    return kLarge32[wt](p, route, knob(2), st);
   }
 
   const int path = plan_path(M, N, K, t);
   if (path == 1 && M > 64) return QG_EINVAL;
 
   if (path == 1 || path == 3) {
+    // a forced arrangement must have the row tiles every block of rows needs, or rows would stay unwritten
+    if (knob(3) > 0 && group != 32)
+      for (int64_t r0 = 0; r0 < M; r0 += 64)
+        if (knob(3) / 10 != row_tiles(M - r0 < 64 ? M - r0 : 64)) { g_last_error = "forced wavefront arrangement does not cover the rows of M"; return QG_EINVAL; }
     for (int64_t r0 = 0; r0 < M; r0 += 64) {
       GemmParams q = p;
       q.A = p.A + r0 * K;
       q.C = p.C + r0 * N;
       q.M = (int)((M - r0 < 64) ? (M - r0) : 64);
-      rc = launch_streaming(q, wt, route, st);
+      rc = launch_streaming(q, wt, route, ws_mode, st);
       if (rc != QG_OK) return rc;
     }
     return QG_OK;
@@ -414,12 +444,15 @@ int qgemm(const void* A, const void* packed_W, const void* scales, const uint8_t
   plan_tiled(M, N, K, t, &bm, &p.splitk, &p.chunks_per_split);
   if (p.splitk > 1) {
     const int64_t tiles = ((M + bm - 1) / bm) * ((N + 255) / 256);
-    Workspace* w = nullptr;
-    rc = get_workspace((size_t)p.splitk * (size_t)tiles * (size_t)(bm * 256) * sizeof(float), (size_t)tiles * 4, st, &w);   // a ticket per 64-column strip
+    rc = acquire_ws(ws_mode, (size_t)p.splitk * (size_t)tiles * (size_t)(bm * 256) * sizeof(float), (size_t)tiles * 4, st, p);   // a ticket per 64-column strip
     if (rc != QG_OK) return rc;
-    p.ws = w->partial; p.tickets = w->tickets;
   }
   return kLarge[wt](p, route, bm, st);
+}
+
+int qgemm(const void* A, const void* packed_W, const void* scales, const uint8_t* zeros, qg_wtype t, int layout,
+          int act, int scale_dtype, int64_t group, int64_t M, int64_t N, int64_t K, void* C, void* stream) {
+  return qgemm_run(A, packed_W, scales, zeros, t, layout, act, scale_dtype, group, M, N, K, C, stream, WS_PER_STREAM);
 }
 
 int qg_probe_stream_read(const void* buf, size_t bytes, void* sink, void* stream) {
@@ -441,19 +474,27 @@ int qg_plan(qg_wtype t, int layout, int act, int scale_dtype, int64_t group, int
   if (rc != QG_OK) return rc;
   if (M < 1 || M > (1 << 24) || !plan) return QG_EINVAL;
   plan[0] = plan[1] = plan[2] = 0; plan[3] = 1; plan[4] = (int)(K / TILE_K);
-  if (layout == QG_LAYOUT_TILE128x64_R32) { plan[0] = 2; plan[2] = g_knob[2]; return group == 32 ? QG_EUNSUPPORTED : QG_OK; }
+  if (layout == QG_LAYOUT_TILE128x64_R32) {
+    plan[0] = 2; plan[2] = knob(2);
+    return (group == 32 || !tiled_operands_fit(M, N, K, group, t.bits)) ? QG_EUNSUPPORTED : QG_OK;
+  }
   plan[0] = plan_path(M, N, K, t);
   if (plan[0] == 1 && M > 64) return QG_EINVAL;
-  if (plan[0] == 1 || plan[0] == 3) plan_streaming((int)(M < 64 ? M : 64), (int)N, (int)K, (int)group, wt, &plan[1], &plan[3], &plan[4]);
-  else plan_tiled(M, N, K, t, &plan[2], &plan[3], &plan[4]);
+  if (plan[0] == 1 || plan[0] == 3) {
+    plan_streaming((int)(M < 64 ? M : 64), (int)N, (int)K, (int)group, wt, &plan[1], &plan[3], &plan[4]);
+    if (knob(3) > 0 && group != 32)
+      for (int64_t r0 = 0; r0 < M; r0 += 64)
+        if (knob(3) / 10 != row_tiles(M - r0 < 64 ? M - r0 : 64)) return QG_EINVAL;
+  } else {
+    if (!tiled_operands_fit(M, N, K, group, t.bits)) return QG_EUNSUPPORTED;
+    plan_tiled(M, N, K, t, &plan[2], &plan[3], &plan[4]);
+  }
   return QG_OK;
 }
 
 int qg_set_knob(int knob, int value) {
   if (knob < 0 || knob >= 4) return 0;
-  int old = g_knob[knob];
-  g_knob[knob] = value;
-  return old;
+  return g_knob[knob].exchange(value, std::memory_order_relaxed);
 }
 
 }  // extern "C"

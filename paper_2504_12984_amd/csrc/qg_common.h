@@ -4,6 +4,7 @@
 #include <stdint.h>
 
 #include "../../include/qgemm.h"
+#include "../../include/qgemm_tuning.h"
 
 namespace qg {
 

@@ -138,3 +138,36 @@ def test_knobs_force_the_plan_and_bad_arguments_are_rejected():
         B.qg_plan(U4, 32, 300, 512, 1024, layout=B.QG_LAYOUT_TILE128x64_R32)
     with pytest.raises(Exception):
         B.qg_plan(U4, 16, 16, 512, 1024)
+
+
+def test_forced_arrangement_must_cover_the_rows():
+    # an arrangement with one row tile cannot serve 64 rows (rows 16..63 would stay unwritten)
+    B.qg_set_knob(3, 11)
+    assert B.qg_plan(U4, 128, 16, 512, 1408)["variant"] == 11
+    with pytest.raises(B.QgError) as e:
+        B.qg_plan(U4, 128, 64, 512, 1408)
+    assert e.value.status == B.QG_EINVAL
+    B.qg_set_knob(3, 46)
+    assert B.qg_plan(U4, 128, 64, 512, 1408)["variant"] == 46
+    with pytest.raises(B.QgError):
+        B.qg_plan(U4, 128, 20, 512, 1408)
+    # over blocks of 64 rows every block is checked: 64 + 6 rows need 4 row tiles, then 1
+    B.qg_set_knob(0, 3)
+    with pytest.raises(B.QgError):
+        B.qg_plan(U4, 128, 70, 512, 1408)
+    assert B.qg_plan(U4, 128, 128, 512, 1408)["variant"] == 46
+
+
+def test_tiled_kernels_take_operands_below_two_gib_only():
+    # A = M x K x 2 bytes: 2^31 at M = 131072, K = 8192
+    assert B.qg_plan(U4, 128, 131071, 256, 8192)["path"] == 2
+    for layout in (0, 1):
+        with pytest.raises(B.QgError) as e:
+            B.qg_plan(U4, 128, 131072, 256, 8192, layout=layout)
+        assert e.value.status == B.QG_EUNSUPPORTED
+    # packed weight = K x N x bits / 8: 2^31 at 8 bits, K = 32768, N = 65536; 7 bits fit
+    with pytest.raises(B.QgError):
+        B.qg_plan(U8, 128, 100, 65536, 32768)
+    assert B.qg_plan(B.WType(B.QG_UINT, 7), 128, 100, 65536, 32768)["path"] == 2
+    # the streaming kernel addresses with 64-bit pointers and takes them all
+    assert B.qg_plan(U8, 128, 16, 65536, 32768)["path"] == 1

@@ -1,4 +1,4 @@
-"""The C-ABI library loads and exports every symbol include/qgemm.h declares.
+"""The C-ABI library loads and exports every symbol the headers under include/ declare.
 No compute call is made here (runs without a GPU)."""
 import ctypes
 import os
@@ -8,13 +8,14 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def _declared():
-    text = open(os.path.join(ROOT, "include", "qgemm.h")).read()
+    inc = os.path.join(ROOT, "include")
+    text = "\n".join(open(os.path.join(inc, f)).read() for f in sorted(os.listdir(inc)) if f.endswith(".h"))
     return sorted(set(re.findall(r"^QG_API\s+[\w\s\*]+?\b(\w+)\s*\(", text, flags=re.M)))
 
 
 def test_header_declares_the_expected_entry_points():
     names = _declared()
-    for must in ("qgemm", "repack", "qdequant", "qgemm_packed_bytes", "qg_pack_codes"):
+    for must in ("qgemm", "repack", "qdequant", "qgemm_packed_bytes", "qg_pack_codes", "qg_set_knob"):
         assert must in names
 
 
