@@ -41,7 +41,7 @@
  *     once a call that splits K has run eagerly on the capture stream (so that
  *     nothing is allocated during the capture); every launch leaves counters and
  *     workspace ready for the next, so a graph can be replayed any number of
- *     times.
+ *     times.  qgemm_noalloc is the same call with no allocation at all.
  *
  * De-quantisation (the paper names the step but prints no formula; this is the
  * standard affine group form):
@@ -144,6 +144,30 @@ QG_API int qdequant(const void* packed_W, const void* scales, const uint8_t* zer
  * 128-row tiles would leave most CUs idle.  The tiled kernel needs M*K*2, the packed
  * weight and the scale array each below 2 GiB (QG_EUNSUPPORTED otherwise). */
 QG_API int qgemm(const void* A, const void* packed_W, const void* scales, const uint8_t* zeros,
+          qg_wtype t, int layout, int act, int scale_dtype, int64_t group,
+          int64_t M, int64_t N, int64_t K, void* C, void* stream);
+
+/* qgemm for callers that cannot allocate device memory: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels,
+ * same plan and therefore the same bits as qgemm, but the split-K partial sums and
+ * arrival counters live in ONE fixed array in device memory that is part of the loaded
+ * library (32 MiB + 64 KiB per GPU, held until the process ends); the call allocates
+ * nothing, frees nothing and does not synchronise.
+ *   - The first call on a device with valid shapes -- M = 0 will do, all pointers may then
+ *     be NULL -- looks the array's address up on that device and keeps it (the HIP runtime
+ *     loads this library's device code at that moment if none of it has been used yet,
+ *     which is when the array comes to occupy device memory).  Make that call once before
+ *     entering a region that must not touch the allocator, e.g. before a graph capture.
+ *   - Every call on a GPU shares that GPU's array: calls that may overlap in time (on
+ *     different streams, or from different threads onto streams that are not ordered
+ *     with each other) race on it and give wrong sums.  Issue them on one stream, or
+ *     order the streams, or use qgemm (one workspace per stream) for the overlapping ones.
+ *   - Nothing needs to be cleared between calls: a call reads back only partial sums it
+ *     wrote itself, and each arrival counter is returned to zero by the kernel that used it.
+ *   - A request beyond the array (only a forced split factor, see qgemm_tuning.h, can
+ *     make one) is refused with QG_EUNSUPPORTED and qg_last_error() says how much was
+ *     asked for; nothing is enqueued.  Other errors as for qgemm. */
+QG_API int qgemm_noalloc(const void* A, const void* packed_W, const void* scales, const uint8_t* zeros,
           qg_wtype t, int layout, int act, int scale_dtype, int64_t group,
           int64_t M, int64_t N, int64_t K, void* C, void* stream);
 

@@ -25,7 +25,7 @@ QG_LAYOUT_TILE128x64_R32 = 1
 TILE_K, TILE_N = 128, 64
 
 EXPORTS = ("qg_status_string", "qg_last_error", "qg_canonical_bytes", "qgemm_packed_bytes",
-           "qg_pack_codes", "repack", "qdequant", "qgemm", "qg_set_knob", "qg_plan", "qg_probe_stream_read",
+           "qg_pack_codes", "repack", "qdequant", "qgemm", "qgemm_noalloc", "qg_set_knob", "qg_plan", "qg_probe_stream_read",
            "qg_probe_mfma")
 
 
@@ -77,6 +77,8 @@ def _load() -> ctypes.CDLL:
     lib.qdequant.argtypes = [vp, vp, vp, QgWType, i32, i32, i32, i64, i64, i64, vp, vp]
     lib.qgemm.restype = i32
     lib.qgemm.argtypes = [vp, vp, vp, vp, QgWType, i32, i32, i32, i64, i64, i64, i64, vp, vp]
+    lib.qgemm_noalloc.restype = i32
+    lib.qgemm_noalloc.argtypes = lib.qgemm.argtypes
     lib.qg_set_knob.restype = i32
     lib.qg_plan.argtypes = [QgWType, i32, i32, i32, i64, i64, i64, i64, ctypes.POINTER(ctypes.c_int32)]
     lib.qg_plan.restype = i32
@@ -153,7 +155,8 @@ def qgemm(A: torch.Tensor, packed: torch.Tensor, scales: torch.Tensor, zeros, t:
           N: int, out: torch.Tensor | None = None, layout: int = QG_LAYOUT_TILE128x64,
           entry: str = "qgemm") -> torch.Tensor:
     """C[M,N] = A[M,K] . dequant(W); dtype of A is the activation dtype.  `entry` names the C
-    entry point."""
+    entry point ("qgemm" or "qgemm_noalloc"; with the latter pass `out`, or this wrapper's
+    torch.empty allocates)."""
     if A.dim() != 2 or A.dtype not in _DT:
         raise ValueError("A must be [M,K] fp16 or bf16")
     M, K = A.shape
@@ -164,11 +167,17 @@ def qgemm(A: torch.Tensor, packed: torch.Tensor, scales: torch.Tensor, zeros, t:
         raise ValueError("zeros must be uint8 [K/group, N]")
     if out is None:
         out = torch.empty((M, N), dtype=A.dtype, device=A.device)
-    fn = {"qgemm": _lib.qgemm}[entry]
+    fn = {"qgemm": _lib.qgemm, "qgemm_noalloc": _lib.qgemm_noalloc}[entry]
     rc = fn(_ptr(A, "A"), _ptr(packed, "packed"), _ptr(scales, "scales"), _ptr(zeros, "zeros"), t.c(),
             layout, _DT[A.dtype], _DT[scales.dtype], group, M, N, K, _ptr(out, "C"), _stream())
     _check(entry, rc)
     return out
+
+
+def qgemm_noalloc(A: torch.Tensor, packed: torch.Tensor, scales: torch.Tensor, zeros, t: WType, group: int,
+                  N: int, out: torch.Tensor, layout: int = QG_LAYOUT_TILE128x64) -> torch.Tensor:
+    """qgemm through the entry point that allocates nothing (the output is the caller's)."""
+    return qgemm(A, packed, scales, zeros, t, group, N, out=out, layout=layout, entry="qgemm_noalloc")
 
 
 class BoundQgemm:
@@ -185,7 +194,7 @@ class BoundQgemm:
     def __init__(self, A: torch.Tensor, packed: torch.Tensor, scales: torch.Tensor, zeros, t: WType, group: int,
                  N: int, out: torch.Tensor, layout: int = QG_LAYOUT_TILE128x64, stream: int | None = None,
                  entry: str = "qgemm"):
-        self._fn = {"qgemm": _lib.qgemm}[entry]
+        self._fn = {"qgemm": _lib.qgemm, "qgemm_noalloc": _lib.qgemm_noalloc}[entry]
         self._entry = entry
         if A.dim() != 2 or A.dtype not in _DT:
             raise ValueError("A must be [M,K] fp16 or bf16")

@@ -110,10 +110,51 @@ static int get_workspace(size_t partial_bytes, size_t ticket_count, hipStream_t 
   return QG_OK;
 }
 
+// qgemm_noalloc: the same workspace as one fixed array in device memory, part of the code
+// object (zero when it is loaded), one copy per GPU.  Its address on a device is looked up
+// once, with that device current, and kept; host code never uses the array's name otherwise.
+// Partial sums need no clearing (a call reads back only slots it has written itself) and
+// every arrival counter is returned to zero by the last arriver of the kernel that used it.
+static __device__ __align__(256) unsigned char scratch[WS_BYTES];
+static std::mutex g_scratch_mutex;
+static unsigned char* g_scratch_ptr[64] = {};
+
+// Looks the array's address up on the current device (first call there) and keeps it.
+static int static_scratch_base(unsigned char** base) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
+  if (dev < 0 || dev >= 64) { g_last_error = "qgemm_noalloc: device index beyond 63"; return QG_EUNSUPPORTED; }
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !ptr) return hip_fail(e, "hipGetSymbolAddress(scratch)");
+    g_scratch_ptr[dev] = static_cast<unsigned char*>(ptr);
+  }
+  *base = g_scratch_ptr[dev];
+  return QG_OK;
+}
+
+static int get_static_scratch(size_t partial_bytes, size_t ticket_count, float** partial, unsigned** tickets) {
+  if (partial_bytes > WS_PARTIAL_BYTES || ticket_count > WS_TICKETS) {
+    g_last_error = "qgemm_noalloc: this call needs " + std::to_string(partial_bytes) + " bytes of split-K partial sums and " +
+                   std::to_string(ticket_count) + " arrival counters; the fixed scratch holds " +
+                   std::to_string(WS_PARTIAL_BYTES) + " bytes and " + std::to_string(WS_TICKETS) + " counters";
+    return QG_EUNSUPPORTED;
+  }
+  unsigned char* base = nullptr;
+  int rc = static_scratch_base(&base);
+  if (rc != QG_OK) return rc;
+  *partial = reinterpret_cast<float*>(base);
+  *tickets = reinterpret_cast<unsigned*>(base + WS_PARTIAL_BYTES);
+  return QG_OK;
+}
+
 enum WsMode { WS_PER_STREAM = 0, WS_STATIC = 1 };
 static int acquire_ws(int mode, size_t partial_bytes, size_t ticket_count, hipStream_t st, GemmParams& p) {
-  (void)mode;
-  return get_workspace(partial_bytes, ticket_count, st, &p.ws, &p.tickets);
+  return mode == WS_STATIC ? get_static_scratch(partial_bytes, ticket_count, &p.ws, &p.tickets)
+                           : get_workspace(partial_bytes, ticket_count, st, &p.ws, &p.tickets);
 }
 
 static bool layout_ok(int layout) { return layout == QG_LAYOUT_TILE128x64 || layout == QG_LAYOUT_TILE128x64_R32; }
@@ -391,6 +432,15 @@ static int qgemm_run(const void* A, const void* packed_W, const void* scales, co
   int rc = check_common(t, layout, act, scale_dtype, group, K, N, &wt, &route);
   if (rc != QG_OK) return rc;
   if (M < 0 || M > (1 << 24)) return QG_EINVAL;
+  if (ws_mode == WS_STATIC) {
+    // every call with valid shapes, also one with M = 0 or one that will not split K, makes sure
+    // the scratch array's address on this device is known: the first such call on a device is the
+    // set-up (the runtime loads this library's device code then, if nothing of it has run yet),
+    // which a caller that must not allocate later can do once with M = 0
+    unsigned char* base = nullptr;
+    rc = static_scratch_base(&base);
+    if (rc != QG_OK) return rc;
+  }
   if (M == 0) return QG_OK;
   if (!A || !packed_W || !scales || !C) return QG_EINVAL;
   if (!aligned16(A) || !aligned16(packed_W) || !aligned16(scales) || !aligned16(C) || (zeros && !aligned16(zeros))) return QG_EINVAL;
@@ -453,6 +503,11 @@ static int qgemm_run(const void* A, const void* packed_W, const void* scales, co
 int qgemm(const void* A, const void* packed_W, const void* scales, const uint8_t* zeros, qg_wtype t, int layout,
           int act, int scale_dtype, int64_t group, int64_t M, int64_t N, int64_t K, void* C, void* stream) {
   return qgemm_run(A, packed_W, scales, zeros, t, layout, act, scale_dtype, group, M, N, K, C, stream, WS_PER_STREAM);
+}
+
+int qgemm_noalloc(const void* A, const void* packed_W, const void* scales, const uint8_t* zeros, qg_wtype t, int layout,
+                  int act, int scale_dtype, int64_t group, int64_t M, int64_t N, int64_t K, void* C, void* stream) {
+  return qgemm_run(A, packed_W, scales, zeros, t, layout, act, scale_dtype, group, M, N, K, C, stream, WS_STATIC);
 }
 
 int qg_probe_stream_read(const void* buf, size_t bytes, void* sink, void* stream) {

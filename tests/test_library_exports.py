@@ -15,7 +15,7 @@ def _declared():
 
 def test_header_declares_the_expected_entry_points():
     names = _declared()
-    for must in ("qgemm", "repack", "qdequant", "qgemm_packed_bytes", "qg_pack_codes", "qg_set_knob"):
+    for must in ("qgemm", "qgemm_noalloc", "repack", "qdequant", "qgemm_packed_bytes", "qg_pack_codes", "qg_set_knob"):
         assert must in names
 
 
