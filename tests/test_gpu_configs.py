@@ -220,6 +220,23 @@ def test_type_sweep_shapes_full(kind, bits):
     f.check_gemm(f.inp["A"], wr, f.case.name)
 
 
+@pytest.mark.parametrize("kind,bits", [(WL.KIND_UINT, 4), (WL.KIND_FLOAT, 6)])
+def test_batch_size_axis_full(kind, bits):
+    # the paper's batch-size sweep (its figure of speedup over batch sizes: decode 1, 4, 8, 16 and
+    # prefill 4096, 8192, 12288 on K = 8192, N = 57344 with u4 and f6 weights): the sizes the five
+    # configurations do not have -- 8, 8192 and 12288 rows -- each on sampled columns for all rows
+    # and on all columns for 64 seeded rows
+    f = FullCase(WL.sweep(kind, bits))
+    wr = f.check_weights()
+    runs = []
+    for M in (8, 8192, 12288):
+        case = WL.shrink(WL.sweep(kind, bits, M), seed=WL.sweep(kind, bits).seed + M)
+        A = _A_of(case)
+        f.check_gemm(A, wr, case.name)
+        runs.append((A, _seeded_rows(M, 64, 7000 + M)))
+    f.check_gemm_all_columns(runs, f"batch sizes {f.case.wname}")
+
+
 def test_generator_draw_order_gives_A_first():
     c = WL.cfg2(4)
     assert torch.equal(_A_of(c), WL.make_inputs(WL.shrink(c, N=64))["A"])

@@ -171,3 +171,16 @@ def test_tiled_kernels_take_operands_below_two_gib_only():
     assert B.qg_plan(B.WType(B.QG_UINT, 7), 128, 100, 65536, 32768)["path"] == 2
     # the streaming kernel addresses with 64-bit pointers and takes them all
     assert B.qg_plan(U8, 128, 16, 65536, 32768)["path"] == 1
+
+
+def test_batch_size_axis_of_the_paper():
+    # K = 8192, N = 57344 (the type-sweep shape) at the paper's batch sizes
+    F6 = B.WType(B.QG_FLOAT, 6, 3, 2)
+    for t in (U4, F6):
+        for M in (1, 4, 8, 16):
+            p = B.qg_plan(t, 128, M, 57344, 8192)
+            assert (p["path"], p["variant"], p["splitk"]) == (1, 16, 1), (M, p)      # 896 strips: four per workgroup
+        for M in (4096, 8192, 12288):
+            p = B.qg_plan(t, 128, M, 57344, 8192)
+            # whole rounds of 256-row tiles, the rest in a second launch; never split
+            assert p == {"path": 2, "variant": 0, "row_tile": 0, "splitk": 1, "chunks_per_slab": 64}, (M, p)
