@@ -60,6 +60,8 @@ def parse():
     ap.add_argument("--copies", type=int, default=0, help="resident weight copies to rotate through")
     ap.add_argument("--layout", type=int, default=0, help="device layout of the packed weight (0 or 1)")
     ap.add_argument("--entry", default="qgemm", choices=["qgemm", "qgemm_noalloc"])
+    ap.add_argument("--path", type=int, default=0,
+                    help="force a path of qgemm (qgemm_tuning.h): 1 streaming, 2 tiled, 4 de-quantise first + 16-bit matmul")
     return ap.parse_args()
 
 
@@ -348,6 +350,9 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     torch.cuda.set_device(0)
 
+    if args.path:
+        from paper_2504_12984_amd import binding as B
+        B.qg_set_knob(0, args.path)
     head = Leg(args.workload, layout=args.layout, copies=args.copies, entry=args.entry)
     ms_per_step, metric, unit, value, roof, extra = head.report(args.steps, args.warmup)
     c0 = head.c0
@@ -360,6 +365,8 @@ def main():
     }
     if args.entry != "qgemm":
         out["config"]["entry"] = args.entry
+    if args.path:
+        out["config"]["forced_path"] = args.path
     if not head.small:
         out["extra"]["vendor_dense_gemm_tflops"] = head.vendor_dense_gemm_tflops()
     cpu_case = head.cases[-1]

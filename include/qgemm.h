@@ -173,10 +173,11 @@ QG_API int qgemm_noalloc(const void* A, const void* packed_W, const void* scales
 
 /* What qgemm would launch for a shape: host arithmetic only, no GPU call, usable without
  * a device.  Arguments as for qgemm (M >= 1).  plan (host, 5 ints) receives
- *   [0] path: 1 = streaming kernel, 2 = tiled kernel, 3 = streaming kernel over blocks of 64 rows
+ *   [0] path: 1 = streaming kernel, 2 = tiled kernel, 3 = streaming kernel over blocks of 64 rows,
+ *       4 = de-quantise first, then the tiled kernel on 16-bit weights (forced only)
  *   [1] wavefront arrangement of the streaming kernel (the values of knob 3), 0 on path 2
  *   [2] row-tile height of the tiled kernel: 64 or 128, or 0 = whole rounds of 256-row
- *       tiles, then 128 or 256 rows for the rest; 0 on paths 1 and 3
+ *       tiles, then 128 or 256 rows for the rest (paths 2 and 4); 0 on paths 1 and 3
  *   [3] K-slabs (split-K factor; 1 = none)   [4] K-chunks of 128 per slab
  * The experiment overrides of qgemm_tuning.h apply as in qgemm.  Returns the status qgemm's
  * argument checks would return. */

@@ -21,7 +21,15 @@ extern "C" {
 
 /* Sets override `knob` (0..3) to `value` (0 = automatic) and returns the previous value.
  *   knob 0: forced path (1 = streaming kernel, M <= 64 only; 2 = tiled kernel; 3 = streaming
- *           kernel over blocks of 64 rows)
+ *           kernel over blocks of 64 rows; 4 = the paper's prefill variant, Section "End-to-End
+ *           Performance": the whole weight is de-quantised to 16 bits first, into a
+ *           library-owned buffer of K*N*2 bytes per (device, stream) -- allocated on first
+ *           use, replaced after a stream synchronisation when a larger weight arrives, so this
+ *           path is not for graph capture and is refused by qgemm_noalloc -- then the tiled
+ *           kernel runs on those 16-bit operands with its unpack stage switched off.  Same
+ *           rounded weights, same results as path 2; K*N*2 must stay below 2 GiB.  It is
+ *           never chosen automatically: it is slower than the fused kernel at every M
+ *           measured, 64 to 12288 rows)
  *   knob 1: forced split-K factor (streaming kernel; tiled kernel with 64- or 128-row tiles)
  *   knob 2: forced row-tile height of the tiled kernel (64 / 128 / 256; 64 on the first
  *           layout only)

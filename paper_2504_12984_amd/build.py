@@ -29,6 +29,7 @@ def _jobs():
     jobs = [("qg_pack.hip", None), ("qg_probe.hip", None), ("qg_api.hip", None)]
     for src in ("qg_dequant.hip", "qg_decode_gemm.hip", "qg_large.hip", "qg_large32.hip"):
         jobs += [(src, wt) for wt in range(NUM_WT)]
+    jobs.append(("qg_large.hip", NUM_WT))      # the tiled kernel on weights already de-quantised (pass-through decoder)
     return jobs
 
 

@@ -23,6 +23,7 @@ int launch_repack(const uint8_t*, int, int, int, uint32_t, int, int, uint8_t*, h
   int large32_launch_wt##i(const GemmParams&, int, int, hipStream_t);
 QG_FOR_ALL_WT(QG_DECL)
 #undef QG_DECL
+int large_launch_wt14(const GemmParams&, int, int, hipStream_t);      // WT_DENSE16: weights already de-quantised
 
 typedef int (*dq_fn)(const DequantParams&, int, hipStream_t);
 typedef int (*gm_fn)(const GemmParams&, int, int, hipStream_t);
@@ -155,6 +156,42 @@ enum WsMode { WS_PER_STREAM = 0, WS_STATIC = 1 };
 static int acquire_ws(int mode, size_t partial_bytes, size_t ticket_count, hipStream_t st, GemmParams& p) {
   return mode == WS_STATIC ? get_static_scratch(partial_bytes, ticket_count, &p.ws, &p.tickets)
                            : get_workspace(partial_bytes, ticket_count, st, &p.ws, &p.tickets);
+}
+
+// ---- buffer of the de-quantise-first path (forced path 4) -------------------------------------
+// The whole weight in 16 bits, K*N*2 bytes, rewritten by every call: one buffer per (device,
+// stream), allocated on first use and replaced (after the stream has drained) when a larger
+// weight arrives.  Only this explicitly selected path allocates beyond the fixed workspace.
+struct DenseBuffer { int dev = -1; hipStream_t stream = nullptr; void* ptr = nullptr; size_t bytes = 0; };
+static DenseBuffer g_dense[32];
+static int g_dense_used = 0;
+
+static int get_dense_buffer(size_t bytes, hipStream_t st, void** out) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
+  std::lock_guard<std::mutex> lock(g_ws_mutex);
+  DenseBuffer* found = nullptr;
+  for (int i = 0; i < g_dense_used; ++i)
+    if (g_dense[i].dev == dev && g_dense[i].stream == st) { found = &g_dense[i]; break; }
+  if (!found) {
+    if (g_dense_used == 32) { g_last_error = "de-quantised weight buffers for more than 32 (device, stream) pairs"; return QG_EUNSUPPORTED; }
+    found = &g_dense[g_dense_used++];
+    found->dev = dev; found->stream = st;
+  }
+  if (found->bytes < bytes) {
+    if (found->ptr) {
+      e = hipStreamSynchronize(st);                    // earlier calls on the stream may still read the old buffer
+      if (e != hipSuccess) return hip_fail(e, "hipStreamSynchronize");
+      (void)hipFree(found->ptr);
+      found->ptr = nullptr; found->bytes = 0;
+    }
+    e = hipMalloc(&found->ptr, bytes);
+    if (e != hipSuccess) return hip_fail(e, "hipMalloc(de-quantised weight)");
+    found->bytes = bytes;
+  }
+  *out = found->ptr;
+  return QG_OK;
 }
 
 static bool layout_ok(int layout) { return layout == QG_LAYOUT_TILE128x64 || layout == QG_LAYOUT_TILE128x64_R32; }
@@ -421,6 +458,7 @@ int qdequant(const void* packed_W, const void* scales, const uint8_t* zeros, qg_
   p.K = (int)K; p.N = (int)N; p.group = (int)group;
   p.zbias = (t.kind == QG_INT) ? (1 << (t.bits - 1)) : 0;
   p.scale_bf16 = (scale_dtype == QG_BF16);
+  p.frag_out = 0;
   return kDequant[wt](p, route, static_cast<hipStream_t>(stream));
 }
 
@@ -473,6 +511,38 @@ static int qgemm_run(const void* A, const void* packed_W, const void* scales, co
 
   const int path = plan_path(M, N, K, t);
   if (path == 1 && M > 64) return QG_EINVAL;
+  if (path < 1 || path > 4) return QG_EINVAL;
+
+  if (path == 4) {
+    // The paper's prefill variant (Section "End-to-End Performance"): de-quantise the whole
+    // weight to 16 bits once, then a plain 16-bit matmul -- here the same tiled kernel reading
+    // ready-made operand registers instead of unpacking codes.
+    const uint64_t dense_bytes = (uint64_t)K * (uint64_t)N * 2u;
+    if (!fits32 || dense_bytes >= (1ull << 31)) return QG_EUNSUPPORTED;
+    if (ws_mode == WS_STATIC) { g_last_error = "qgemm_noalloc: the de-quantise-first path needs a K*N*2-byte buffer"; return QG_EUNSUPPORTED; }
+    void* dense = nullptr;
+    rc = get_dense_buffer((size_t)dense_bytes, st, &dense);
+    if (rc != QG_OK) return rc;
+    DequantParams d;
+    d.W = p.W; d.S = p.S; d.Z = p.Z; d.out = static_cast<uint16_t*>(dense);
+    d.layout = QG_LAYOUT_TILE128x64; d.K = p.K; d.N = p.N; d.group = p.group; d.zbias = p.zbias; d.scale_bf16 = p.scale_bf16;
+    d.frag_out = 1;
+    rc = kDequant[wt](d, route, st);
+    if (rc != QG_OK) return rc;
+    GemmParams q = p;
+    q.W = static_cast<const uint8_t*>(dense);
+    q.Z = nullptr; q.group = p.K; q.zbias = 0;
+    if (!set_group_index(q)) return QG_EINVAL;
+    qg_wtype t16 = {QG_UINT, 4, 0, 0};               // cost model of the tiled kernel: nothing to unpack, as for a narrow code
+    int bm;
+    plan_tiled(M, N, K, t16, &bm, &q.splitk, &q.chunks_per_split);
+    if (q.splitk > 1) {
+      const int64_t tiles = ((M + bm - 1) / bm) * ((N + 255) / 256);
+      rc = acquire_ws(ws_mode, (size_t)q.splitk * (size_t)tiles * (size_t)(bm * 256) * sizeof(float), (size_t)tiles * 4, st, q);
+      if (rc != QG_OK) return rc;
+    }
+    return large_launch_wt14(q, route, bm, st);
+  }
 
   if (path == 1 || path == 3) {
     // a forced arrangement must have the row tiles every block of rows needs, or rows would stay unwritten
@@ -541,8 +611,14 @@ int qg_plan(qg_wtype t, int layout, int act, int scale_dtype, int64_t group, int
       for (int64_t r0 = 0; r0 < M; r0 += 64)
         if (knob(3) / 10 != row_tiles(M - r0 < 64 ? M - r0 : 64)) return QG_EINVAL;
   } else {
+    if (plan[0] < 1 || plan[0] > 4) return QG_EINVAL;
     if (!tiled_operands_fit(M, N, K, group, t.bits)) return QG_EUNSUPPORTED;
-    plan_tiled(M, N, K, t, &plan[2], &plan[3], &plan[4]);
+    qg_wtype tt = t;
+    if (plan[0] == 4) {
+      if ((uint64_t)K * (uint64_t)N * 2u >= (1ull << 31)) return QG_EUNSUPPORTED;
+      tt = qg_wtype{QG_UINT, 4, 0, 0};
+    }
+    plan_tiled(M, N, K, tt, &plan[2], &plan[3], &plan[4]);
   }
   return QG_OK;
 }

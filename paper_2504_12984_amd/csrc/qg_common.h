@@ -106,6 +106,9 @@ struct DequantParams {
   int K, N, group;
   int zbias;        // added to every zero-point (2^(bits-1) for intk, else 0)
   int scale_bf16;   // scales are bf16 (only with ROUTE_BF16)
+  int frag_out;     // 0: out is [K,N] row-major; 1: out is in fragment order (first layout only):
+                    // 16 KiB per chunk, the four registers of (k-step j, sub-tile nt) of lane l at
+                    // byte (4*j + nt) * 1024 + 16 * l -- what the tiled kernel's pass-through reads
 };
 
 struct GemmParams {

@@ -143,6 +143,7 @@ struct Decoder<WT, ROUTE_F16, LY> {
   static constexpr int EB = wt_ebits(WT), MB = wt_mbits(WT);
   static constexpr int WN = Lay<BITS>::WN;
   static constexpr int RAW = 4 * BITS;
+  static constexpr bool HAS_META = true;           // scales / zero-points are loaded with every chunk
 
   struct Consts {
     h2_t s[NTL];
@@ -258,6 +259,7 @@ struct Decoder<WT, ROUTE_BF16, LY> {
   static constexpr int EB = wt_ebits(WT), MB = wt_mbits(WT);
   static constexpr int WN = Lay<BITS>::WN;
   static constexpr int RAW = 4 * BITS;
+  static constexpr bool HAS_META = true;           // scales / zero-points are loaded with every chunk
 
   struct Consts {
     float s[NTL];     // integers: scale; floats: scale * 2^(15-bias)
@@ -358,5 +360,39 @@ struct Decoder<WT, ROUTE_BF16, LY> {
     }
   }
 };
+
+// ================= weights already de-quantised (the paper's prefill variant) ==================
+// For prefill-sized batches the paper decodes the quantised weight to float16 once and runs a
+// standard 16-bit matmul (Section "End-to-End Performance").  Here the de-quantiser can write its
+// result in "fragment order" -- the 16-bit image of the first device layout: chunk (kc, nc) is
+// 16 pieces of 1024 bytes, piece 4*j + nt holds, for lane l at bytes [16*l, 16*l + 16), the four
+// registers the lane feeds to the matrix instruction for k-step j and sub-tile nt -- and the tiled
+// kernel then runs with this pass-through "decoder": the same kernel with the unpack removed.
+constexpr int WT_DENSE16 = NUM_WT;       // kernel-side index only, not a weight type of the interface
+
+template <int ROUTE>
+struct DenseDecoder {
+  static constexpr int NTL = 4, BITS = 16, RAW = 64;
+  static constexpr bool HAS_META = false;
+  struct Consts {};
+  struct Uniform { __device__ __forceinline__ void init() {} };
+  typedef uint32_t Mid;
+  static __device__ __forceinline__ void make_col(Consts&, int, uint2, uint32_t, int, int) {}
+  template <int T>
+  static __device__ __forceinline__ uint32_t pair_e(const uint32_t (&r)[RAW], const Uniform&) { return r[T]; }
+  template <int T>
+  static __device__ __forceinline__ Mid pair_s(uint32_t x, const Consts&, int) { return x; }
+  static __device__ __forceinline__ uint32_t pair_p(Mid m, const Consts&, int) { return m; }
+  template <int J, int NT>
+  static __device__ __forceinline__ void frag(const uint32_t (&r)[RAW], const Consts&, const Uniform&, uint32_t (&out)[4]) {
+    constexpr int T0 = LayoutOf<0>::t0(J, NT);
+    out[0] = r[T0]; out[1] = r[T0 + 1]; out[2] = r[T0 + 2]; out[3] = r[T0 + 3];
+  }
+};
+
+template <int WT, int ROUTE>
+struct DecoderFor { typedef Decoder<WT, ROUTE, 0> type; };
+template <int ROUTE>
+struct DecoderFor<WT_DENSE16, ROUTE> { typedef DenseDecoder<ROUTE> type; };
 
 }  // namespace qg

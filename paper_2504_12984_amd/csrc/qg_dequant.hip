@@ -55,6 +55,14 @@ __global__ __launch_bounds__(256) void dequant_kernel(DequantParams p) {
       constexpr int NT = decltype(NTc)::value;
       D::template frag<J, NT>(r, gc, u, o[NT]);
     });
+    if constexpr (LY == 0) {
+      if (p.frag_out) {            // the registers as they are, one 16-byte store per (k-step, sub-tile): 1 KiB per wavefront
+        uint4* dst = reinterpret_cast<uint4*>(reinterpret_cast<uint8_t*>(p.out) + chunk * 16384) + l;
+#pragma unroll
+        for (int nt = 0; nt < 4; ++nt) dst[(J * 4 + nt) * 64] = make_uint4(o[nt][0], o[nt][1], o[nt][2], o[nt][3]);
+        return;
+      }
+    }
 #pragma unroll
     for (int v = 0; v < 4; ++v) {
       const int k = TILE_K * kc + L::pair_k(l, L::t0(J, 0) + v);

@@ -72,7 +72,7 @@ template <int WT, int ROUTE, int GPC, int BM>
 __global__ __launch_bounds__(256) void large_kernel(GemmParams p, int tiles_m, int tiles_n, int per_xcd, int tn0) {
   // GPC = groups per 128-row chunk: 1 (group size 128 or more), 2 (64) or 4 (32)
   constexpr bool TWO_GROUPS = (GPC == 2), FOUR_GROUPS = (GPC == 4);
-  typedef Decoder<WT, ROUTE> D;
+  typedef typename DecoderFor<WT, ROUTE>::type D;      // WT_DENSE16: weights already de-quantised, pass-through
   constexpr int BITS = D::BITS, RAW = D::RAW;
   constexpr int MTS = BM / 16;                 // 16-row MFMA tiles per workgroup
   constexpr int PIECES = BM * 4 / 256;         // 16-byte pieces per thread per slice
@@ -156,7 +156,7 @@ __global__ __launch_bounds__(256) void large_kernel(GemmParams p, int tiles_m, i
   // The loads of one chunk are 2 (4 with two groups per chunk) + BITS separate pieces,
   // so that the main loop can issue them a few at a time in different gaps between
   // matrix instructions.  Pieces: s0, z0, (s1, z1, (s2, z2, s3, z3,)) then BITS x 16 bytes of codes.
-  constexpr int WMETA = 2 * GPC;
+  constexpr int WMETA = D::HAS_META ? 2 * GPC : 0;
   constexpr int WPIECES = WMETA + BITS;
   auto w_piece = [&](WStage& s, int c, auto Ic) __attribute__((always_inline)) {
     constexpr int I = decltype(Ic)::value;
@@ -184,6 +184,7 @@ __global__ __launch_bounds__(256) void large_kernel(GemmParams p, int tiles_m, i
   // constants of one column of group G (0 .. GPC-1) of a chunk
   auto consts_col = [&](typename D::Consts& g, const WStage& s, auto Gc, int nt) __attribute__((always_inline)) {
     constexpr int G = decltype(Gc)::value;
+    if constexpr (!D::HAS_META) return;
     if constexpr (G == 0) D::make_col(g, nt, s.s0, s.z0 & zmask, p.zbias, p.scale_bf16);
     if constexpr (G == 1) D::make_col(g, nt, s.s1, s.z1 & zmask, p.zbias, p.scale_bf16);
     if constexpr (G == 2) D::make_col(g, nt, s.s2, s.z2 & zmask, p.zbias, p.scale_bf16);
