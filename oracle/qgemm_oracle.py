@@ -29,10 +29,17 @@ What follows the paper and what is a reading of it
   activation type; the contraction then runs over the rounded weights, which
   is what feeding a cast tile to a matrix instruction means.
 
+* int8 activations (named as supported in Section "Arbitrary Data Type Support", nothing
+  more is said): integer weights only, the sum over the rows of one scale group is an exact
+  integer, the weight scale multiplies that sum, a per-row fp32 activation scale multiplies
+  the row (qgemm_int8).
+
 Parity pins (tests/test_oracle_*.py): hand-derived bit streams, numpy.packbits
 for 1-bit, nibble/byte identities for 4/8-bit, exact-rational evaluation of the
 float formats, torch's float8_e4m3fn table, numpy/torch half and bfloat16 casts,
-integer matmul for uint8 weights, one-hot rows, brute-force triple loops.
+integer matmul for uint8 weights, one-hot rows, brute-force triple loops; for the int8
+leg: numpy int64 matmul, exact-rational triple loops, agreement with the 16-bit-activation
+contraction wherever that one is exact, the row-sum form of the zero-point.
 The paper prints no numeric tensor example, so beyond those pins parity with
 the paper's own implementation is unpinned.
 """
@@ -238,6 +245,70 @@ def qgemm_from_stream(A, stream, kind, bits, ebits, mbits, scales, zeros, group,
         z = None if zeros is None else np.asarray(zeros)[:, cb]
         wr, _ = dequant_rounded(codes, kind, bits, ebits, mbits, scales[:, cb], z, group, act)
         out[:, s:s + cb.size] = gemm_fp64(A, wr)
+    return out
+
+
+# --------------------------------------------------------------------------
+# int8 activations (Section "Arbitrary Data Type Support": operand A may be an
+# 8-bit type; the paper names int8 beside float16 and bfloat16)
+# --------------------------------------------------------------------------
+def int_weights(codes, kind, bits, zeros, group):
+    """value(code) - z as exact integers (int64) [K, N]; integer weight kinds only."""
+    if kind not in (KIND_UINT, KIND_INT):
+        raise ValueError("int8 activations multiply integer weights (uintk / intk) only")
+    codes = np.asarray(codes)
+    K, N = codes.shape
+    assert K % group == 0
+    v = code_values(kind, bits)[codes].astype(np.int64)
+    if zeros is not None:
+        v = v - np.asarray(zeros).astype(np.int64)[np.arange(K) // group]
+    return v
+
+
+def qgemm_int8(A8, a_scale, codes, kind, bits, scales, zeros, group):
+    """C[m,n] = a_scale[m] * sum_g s[g,n] * ( sum_{k in group g} A8[m,k] * (value(code[k,n]) - z[g,n]) ).
+
+    The paper says that int8 is a supported activation type and gives nothing more; this is
+    the reading used here.  An integer matrix instruction can only multiply integers, so the
+    inner sum over the rows of one scale group is an exact integer, the group's weight scale
+    (a 16-bit float widened exactly) multiplies that sum, the groups are added, and a
+    per-row activation scale (fp32, the usual per-token quantisation of activations; None =
+    1) multiplies the row.  Evaluated here in fp64 after the exact integer part; the result
+    is NOT rounded to the output type (the comparison tolerance covers that rounding).
+
+    The integer inner sums are formed with a float64 matrix product of integer-valued
+    operands: every product is below 2^15 and every sum below 2^15 * K, far below 2^53,
+    so each float64 operation is exact whatever order the library adds in.
+
+    A8 [M, K] int8; a_scale [M] or None; codes [K, N] uint8 patterns; scales [K/group, N]
+    fp64; zeros [K/group, N] integers or None.  Returns fp64 [M, N].
+    """
+    A8 = np.asarray(A8)
+    assert A8.dtype == np.int8
+    w = int_weights(codes, kind, bits, zeros, group)
+    K, N = w.shape
+    Af, wf = A8.astype(np.float64), w.astype(np.float64)
+    s = np.asarray(scales, dtype=np.float64)
+    C = np.zeros((A8.shape[0], N), dtype=np.float64)
+    for g in range(K // group):
+        rows = slice(g * group, (g + 1) * group)
+        C += (Af[:, rows] @ wf[rows]) * s[g][None, :]
+    if a_scale is not None:
+        C *= np.asarray(a_scale, dtype=np.float64)[:, None]
+    return C
+
+
+def qgemm_int8_from_stream(A8, a_scale, stream, kind, bits, scales, zeros, group, K, N, cols=None, col_block=1024):
+    """qgemm_int8 from the canonical byte stream, optionally on a subset of output columns."""
+    cols = np.arange(N, dtype=np.int64) if cols is None else np.asarray(cols, dtype=np.int64)
+    scales = np.asarray(scales, dtype=np.float64)
+    out = np.empty((np.asarray(A8).shape[0], cols.size), dtype=np.float64)
+    rows = np.arange(K, dtype=np.int64)[:, None] * N
+    for s0 in range(0, cols.size, col_block):
+        cb = cols[s0:s0 + col_block]
+        codes = unpack_elements(stream, bits, rows + cb[None, :])
+        z = None if zeros is None else np.asarray(zeros)[:, cb]
+        out[:, s0:s0 + cb.size] = qgemm_int8(A8, a_scale, codes, kind, bits, scales[:, cb], z, group)
     return out
 
 
