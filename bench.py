@@ -88,6 +88,10 @@ def cases_for(name):
     if name.startswith("cfg5_u"):
         bits, m = name[6:].split("_M")
         return [WL.cfg5(int(bits), int(m))]
+    if name.startswith("a8_i"):                          # int8 activations on the signed sweep's recipe: a8_i4, a8_i4_M64
+        rest = name[4:]
+        bits, m = rest.split("_M") if "_M" in rest else (rest, "16")
+        return [WL.shrink(WL.cfg3(int(bits)), M=int(m), a8=True, name=name)]
     if name.startswith("sweep_"):                        # sweep_u4, sweep_i7, sweep_f6 (M = 16), sweep_u4_M8192
         kind = {"u": WL.KIND_UINT, "i": WL.KIND_INT, "f": WL.KIND_FLOAT}[name[6]]
         rest = name[7:]
@@ -104,7 +108,8 @@ def algorithmic_bytes(c):
     G = c.K // c.group
     S = G * c.N * 2
     Z = G * c.N if c.zero is not None else 0
-    return P, P + S + Z + c.M * c.K * 2 + c.M * c.N * 2
+    a_bytes = c.M * c.K + c.M * 4 if c.a8 else c.M * c.K * 2            # int8 rows + one fp32 scale per row
+    return P, P + S + Z + a_bytes + c.M * c.N * 2
 
 
 def decode_lane_ops_per_element(c):
@@ -115,6 +120,10 @@ def decode_lane_ops_per_element(c):
     one packed convert = 4 per pair; floats with a hardware convert save the middle step
     (2 / 3 per pair)."""
     from paper_2504_12984_amd import workloads as WL
+    if c.a8:
+        # int8 activations: a shift and a mask per register of four codes, + 3 per accumulator
+        # and scale group for the zero-point / convert / scale step (16 accumulators per 64 x 128)
+        return 2 / 4.0 + 3 * 16 / (64.0 * min(c.group, 128))
     hw = c.kind == WL.KIND_FLOAT and (c.ebits, c.mbits) in ((2, 1), (3, 2), (4, 3))
     per_pair = (2 if hw else 3) if c.act == "f16" else (3 if hw else 4)
     return per_pair / 2.0
@@ -163,6 +172,8 @@ class Leg:
         dev = "cuda:0"
         inp0 = WL.make_inputs(c0)
         codes = torch.from_numpy(inp0["codes"]).to(dev)
+        if c0.a8:
+            layout = self.layout = B.QG_LAYOUT_TILE128x64_I8
         packed0 = B.repack(B.qg_pack_codes(codes, c0.bits), self.wt, c0.K, c0.N, layout=layout)
         del codes
         self.copies = copies or int(min(64, max(3, -(-(3 << 29) // self.P))))     # ~1.5 GB of packed weights
@@ -170,14 +181,21 @@ class Leg:
         self.scales = [inp0["scales"].to(dev).clone() for _ in range(self.copies)]
         self.zeros = [None if inp0["zeros"] is None else torch.from_numpy(inp0["zeros"]).to(dev).clone()
                       for _ in range(self.copies)]
-        self.As = [WL.make_inputs(c)["A"].to(dev) if i else inp0["A"].to(dev) for i, c in enumerate(self.cases)]
-        del inp0
-        self.Cs = [torch.empty((c.M, c.N), dtype=a.dtype, device=dev) for c, a in zip(self.cases, self.As)]
+        inps = [WL.make_inputs(c) if i else inp0 for i, c in enumerate(self.cases)]
+        self.As = [x["A"].to(dev) for x in inps]
+        self.a_scales = [x["a_scale"].to(dev) if c.a8 else None for x, c in zip(inps, self.cases)]
+        del inp0, inps
+        out_dt = {"f16": torch.float16, "bf16": torch.bfloat16}
+        self.Cs = [torch.empty((c.M, c.N), dtype=out_dt[c.act], device=dev) for c in self.cases]
         torch.cuda.synchronize()
         # arguments marshalled once per (case, weight copy): the timed loop is foreign calls only
-        self.calls = [[B.BoundQgemm(A, self.packed[i], self.scales[i], self.zeros[i], self.wt, c.group, c.N, C,
-                                    layout=layout, entry=entry)
-                       for i in range(self.copies)] for c, A, C in zip(self.cases, self.As, self.Cs)]
+        if c0.a8:
+            self.calls = [[B.BoundQgemmA8(A, a_s, self.packed[i], self.scales[i], self.zeros[i], self.wt, c.group, c.N, C)
+                           for i in range(self.copies)] for c, A, a_s, C in zip(self.cases, self.As, self.a_scales, self.Cs)]
+        else:
+            self.calls = [[B.BoundQgemm(A, self.packed[i], self.scales[i], self.zeros[i], self.wt, c.group, c.N, C,
+                                        layout=layout, entry=entry)
+                           for i in range(self.copies)] for c, A, C in zip(self.cases, self.As, self.Cs)]
         self.rot = 0
         self.small = all(c.M <= 64 for c in self.cases)
 
@@ -286,7 +304,7 @@ class Leg:
                     "traffic": traffic[0] if traffic else None,
                     "traffic_source": (f"carried over from {traffic[1]} (counter run of this command), "
                                        "not measured in this run") if traffic else None,
-                    "kernel": "qg::decode_kernel", "avg_launch_us": round(launch_ms * 1e3, 3),
+                    "kernel": "qg::a8_kernel" if self.c0.a8 else "qg::decode_kernel", "avg_launch_us": round(launch_ms * 1e3, 3),
                     "median_launch_us_per_case": med_us,
                     "algorithmic_bytes_per_launch": int(alg_bytes),
                     "secondary": {"bound": "valu", "lane_ops": int(lane_ops), "achieved": round(valu, 2),
@@ -360,7 +378,7 @@ def main():
         "metric": metric, "value": round(value, 2), "unit": unit, "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16" if c0.act == "bf16" else "f16", "data": "synthetic",
+        "dtype": "i8" if c0.a8 else ("bf16" if c0.act == "bf16" else "f16"), "data": "synthetic",
         "config": head.config(), "roofline": roof, "extra": extra,
     }
     if args.entry != "qgemm":

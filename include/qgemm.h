@@ -74,7 +74,7 @@ typedef enum { QG_F16 = 0, QG_BF16 = 1 } qg_dtype;      /* activation / scale dt
  * e1m1, e2m1, e2m2, e3m2, e3m3, e4m3 (Section "Arbitrary Data Type Support"). */
 typedef struct { int32_t kind, bits, ebits, mbits; } qg_wtype;
 
-/* Device layouts.  In both, W is cut into tiles of 128 (K) x 64 (N) codes; a tile
+/* Device layouts.  In all of them W is cut into tiles of 128 (K) x 64 (N) codes; a tile
  * is 1024*bits bytes, read by one 64-lane wavefront as `bits` 16-byte loads per
  * lane, and the lane's 16*bits bytes hold exactly the 128 codes that lane feeds to
  * the matrix instruction (no exchange between lanes, no staging through LDS).
@@ -89,9 +89,14 @@ typedef struct { int32_t kind, bits, ebits, mbits; } qg_wtype;
  *   QG_LAYOUT_TILE128x64_R32  lane owns 2 columns; 32x32x16 instruction.  One tiled
  *                             kernel for every M (no split-K, no group size 32),
  *                             about 5 % slower than the first layout's on the prefill
- *                             shapes: the measured alternative, kept with its tests. */
+ *                             shapes: the measured alternative, kept with its tests.
+ *   QG_LAYOUT_TILE128x64_I8   for int8 activations (qgemm_a8): lane owns 4 columns, its bytes
+ *                             are four parallel byte streams that unpack straight into the
+ *                             int8 operands of the 16x16x64 integer instruction.  Integer
+ *                             weight types only; qdequant and qgemm do not read it. */
 #define QG_LAYOUT_TILE128x64 0
 #define QG_LAYOUT_TILE128x64_R32 1
+#define QG_LAYOUT_TILE128x64_I8 2
 #define QG_TILE_K 128
 #define QG_TILE_N 64
 
@@ -170,6 +175,25 @@ QG_API int qgemm(const void* A, const void* packed_W, const void* scales, const 
 QG_API int qgemm_noalloc(const void* A, const void* packed_W, const void* scales, const uint8_t* zeros,
           qg_wtype t, int layout, int act, int scale_dtype, int64_t group,
           int64_t M, int64_t N, int64_t K, void* C, void* stream);
+
+/* Matmul with int8 activations (Section "Arbitrary Data Type Support" names int8 as a supported
+ * activation type and gives no formula; this is the library's reading, the standard W-k-bit /
+ * A-8-bit form):
+ *     C[m,n] = rne_out( a_scale[m] * sum_g s[g,n] * ( sum_{k in group g} A8[m,k] * (value(code[k,n]) - z[g,n]) ) )
+ * The inner sum over the rows of one scale group is an exact integer (integer matrix
+ * instruction, int32), the group's weight scale multiplies it and the groups are added in fp32,
+ * the row's activation scale multiplies the total, one rounding to `out_dtype`.
+ *   A8        [M, K] row-major int8, device, 16-byte aligned
+ *   a_scale   [M] fp32, device, or NULL for 1
+ *   packed_W  repack(..., QG_LAYOUT_TILE128x64_I8, ...) of a uintk or intk weight (floats: QG_EUNSUPPORTED)
+ *   scales / zeros / scale_dtype / K, N as for qgemm; group 64, 128 * 2^s, K (or 0 = K);
+ *   group 32 is QG_EUNSUPPORTED (the instruction sums 64 values of k)
+ *   out_dtype QG_F16 or QG_BF16: dtype of C [M, N]
+ * M >= 1 is arbitrary (rows are served in blocks of 64; there is no separate prefill kernel
+ * yet).  Workspace, stream and error conventions as for qgemm. */
+QG_API int qgemm_a8(const int8_t* A8, const float* a_scale, const void* packed_W, const void* scales,
+             const uint8_t* zeros, qg_wtype t, int out_dtype, int scale_dtype, int64_t group,
+             int64_t M, int64_t N, int64_t K, void* C, void* stream);
 
 /* What qgemm would launch for a shape: host arithmetic only, no GPU call, usable without
  * a device.  Arguments as for qgemm (M >= 1).  plan (host, 5 ints) receives

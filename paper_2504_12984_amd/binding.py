@@ -22,10 +22,11 @@ QG_UINT, QG_INT, QG_FLOAT = 0, 1, 2
 QG_F16, QG_BF16 = 0, 1
 QG_LAYOUT_TILE128x64 = 0
 QG_LAYOUT_TILE128x64_R32 = 1
+QG_LAYOUT_TILE128x64_I8 = 2
 TILE_K, TILE_N = 128, 64
 
 EXPORTS = ("qg_status_string", "qg_last_error", "qg_canonical_bytes", "qgemm_packed_bytes",
-           "qg_pack_codes", "repack", "qdequant", "qgemm", "qgemm_noalloc", "qg_set_knob", "qg_plan", "qg_probe_stream_read",
+           "qg_pack_codes", "repack", "qdequant", "qgemm", "qgemm_noalloc", "qgemm_a8", "qg_set_knob", "qg_plan", "qg_probe_stream_read",
            "qg_probe_mfma")
 
 
@@ -79,6 +80,8 @@ def _load() -> ctypes.CDLL:
     lib.qgemm.argtypes = [vp, vp, vp, vp, QgWType, i32, i32, i32, i64, i64, i64, i64, vp, vp]
     lib.qgemm_noalloc.restype = i32
     lib.qgemm_noalloc.argtypes = lib.qgemm.argtypes
+    lib.qgemm_a8.restype = i32
+    lib.qgemm_a8.argtypes = [vp, vp, vp, vp, vp, QgWType, i32, i32, i64, i64, i64, i64, vp, vp]
     lib.qg_set_knob.restype = i32
     lib.qg_plan.argtypes = [QgWType, i32, i32, i32, i64, i64, i64, i64, ctypes.POINTER(ctypes.c_int32)]
     lib.qg_plan.restype = i32
@@ -180,6 +183,29 @@ def qgemm_noalloc(A: torch.Tensor, packed: torch.Tensor, scales: torch.Tensor, z
     return qgemm(A, packed, scales, zeros, t, group, N, out=out, layout=layout, entry="qgemm_noalloc")
 
 
+def qgemm_a8(A8: torch.Tensor, a_scale, packed: torch.Tensor, scales: torch.Tensor, zeros, t: WType, group: int,
+             N: int, out_dtype: torch.dtype = torch.float16, out: torch.Tensor | None = None) -> torch.Tensor:
+    """C[M,N] = a_scale[m] * sum_g s[g,n] * (A8 . (codes - z))_g; A8 int8 [M,K], a_scale fp32 [M] or None,
+    `packed` in QG_LAYOUT_TILE128x64_I8."""
+    if A8.dim() != 2 or A8.dtype != torch.int8:
+        raise ValueError("A8 must be [M,K] int8")
+    M, K = A8.shape
+    rows = K // group if group > 0 else 1
+    if scales.dtype not in _DT or tuple(scales.shape) != (rows, N):
+        raise ValueError("scales must be [K/group, N] fp16 or bf16")
+    if zeros is not None and (zeros.dtype != torch.uint8 or tuple(zeros.shape) != (rows, N)):
+        raise ValueError("zeros must be uint8 [K/group, N]")
+    if a_scale is not None and (a_scale.dtype != torch.float32 or tuple(a_scale.shape) != (M,)):
+        raise ValueError("a_scale must be fp32 [M]")
+    if out is None:
+        out = torch.empty((M, N), dtype=out_dtype, device=A8.device)
+    rc = _lib.qgemm_a8(_ptr(A8, "A8"), _ptr(a_scale, "a_scale"), _ptr(packed, "packed"), _ptr(scales, "scales"),
+                       _ptr(zeros, "zeros"), t.c(), _DT[out.dtype], _DT[scales.dtype], group, M, N, K, _ptr(out, "C"),
+                       _stream())
+    _check("qgemm_a8", rc)
+    return out
+
+
 class BoundQgemm:
     """One qgemm call with its arguments checked and marshalled once.
 
@@ -218,6 +244,38 @@ class BoundQgemm:
         rc = self._fn(*self._args)
         if rc != QG_OK:
             raise QgError(self._entry, rc)
+        return self.out
+
+
+class BoundQgemmA8:
+    """One qgemm_a8 call with its arguments checked and marshalled once (see BoundQgemm)."""
+
+    def __init__(self, A8: torch.Tensor, a_scale, packed: torch.Tensor, scales: torch.Tensor, zeros, t: WType,
+                 group: int, N: int, out: torch.Tensor, stream: int | None = None):
+        if A8.dim() != 2 or A8.dtype != torch.int8:
+            raise ValueError("A8 must be [M,K] int8")
+        M, K = A8.shape
+        rows = K // group if group > 0 else 1
+        if scales.dtype not in _DT or tuple(scales.shape) != (rows, N):
+            raise ValueError("scales must be [K/group, N] fp16 or bf16")
+        if zeros is not None and (zeros.dtype != torch.uint8 or tuple(zeros.shape) != (rows, N)):
+            raise ValueError("zeros must be uint8 [K/group, N]")
+        if a_scale is not None and (a_scale.dtype != torch.float32 or tuple(a_scale.shape) != (M,)):
+            raise ValueError("a_scale must be fp32 [M]")
+        if tuple(out.shape) != (M, N) or out.dtype not in _DT:
+            raise ValueError("out must be [M,N] fp16 or bf16")
+        vp, i32, i64 = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64
+        self._keep = (A8, a_scale, packed, scales, zeros, out)
+        self.out = out
+        self._args = (vp(_ptr(A8, "A8")), vp(_ptr(a_scale, "a_scale")), vp(_ptr(packed, "packed")),
+                      vp(_ptr(scales, "scales")), vp(_ptr(zeros, "zeros")), t.c(), i32(_DT[out.dtype]),
+                      i32(_DT[scales.dtype]), i64(group), i64(M), i64(N), i64(K), vp(_ptr(out, "C")),
+                      vp(_stream() if stream is None else stream))
+
+    def __call__(self) -> torch.Tensor:
+        rc = _lib.qgemm_a8(*self._args)
+        if rc != QG_OK:
+            raise QgError("qgemm_a8", rc)
         return self.out
 
 

@@ -29,6 +29,7 @@ def _jobs():
     jobs = [("qg_pack.hip", None), ("qg_probe.hip", None), ("qg_api.hip", None)]
     for src in ("qg_dequant.hip", "qg_decode_gemm.hip", "qg_large.hip", "qg_large32.hip"):
         jobs += [(src, wt) for wt in range(NUM_WT)]
+    jobs += [("qg_a8_gemm.hip", -bits) for bits in range(1, 9)]      # int8 activations: once per code width
     jobs.append(("qg_large.hip", NUM_WT))      # the tiled kernel on weights already de-quantised (pass-through decoder)
     return jobs
 
@@ -58,13 +59,19 @@ def _check_scratch(stem, src, remarks):
                                    f"(limit {limit}); its accumulators are not safe to spill")
 
 
+def _stem(job):
+    """Object name of a job: (source, None), (source, weight-type index) or (source, -code width)."""
+    src, wt = job
+    return src[:-4] + ("" if wt is None else f"_wt{wt}" if wt >= 0 else f"_bits{-wt}")
+
+
 def _compile(job):
     src, wt = job
-    stem = src[:-4] + ("" if wt is None else f"_wt{wt}")
+    stem = _stem(job)
     obj = os.path.join(OBJ, stem + ".o")
     cmd = [HIPCC, *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
     if wt is not None:
-        cmd.insert(-4, f"-DQG_WT={wt}")
+        cmd.insert(-4, f"-DQG_WT={wt}" if wt >= 0 else f"-DQG_BITS={-wt}")
     if src in SPILL_CHECKED:
         cmd.insert(-4, "-Rpass-analysis=kernel-resource-usage")
     r = subprocess.run(cmd, capture_output=True, text=True)

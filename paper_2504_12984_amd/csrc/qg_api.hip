@@ -23,7 +23,13 @@ int launch_repack(const uint8_t*, int, int, int, uint32_t, int, int, uint8_t*, h
   int large32_launch_wt##i(const GemmParams&, int, int, hipStream_t);
 QG_FOR_ALL_WT(QG_DECL)
 #undef QG_DECL
-int large_launch_wt14(const GemmParams&, int, int, hipStream_t);      // WT_DENSE16: weights already de-quantised
+int large_launch_wt14(const GemmParams&, int, int, hipStream_t);
+#define QG_DECL_A8(b) int a8_launch_bits##b(const A8Params&, int, int, hipStream_t);
+QG_DECL_A8(1) QG_DECL_A8(2) QG_DECL_A8(3) QG_DECL_A8(4) QG_DECL_A8(5) QG_DECL_A8(6) QG_DECL_A8(7) QG_DECL_A8(8)
+#undef QG_DECL_A8
+typedef int (*a8_fn)(const A8Params&, int, int, hipStream_t);
+static const a8_fn kA8[8] = {a8_launch_bits1, a8_launch_bits2, a8_launch_bits3, a8_launch_bits4,
+                             a8_launch_bits5, a8_launch_bits6, a8_launch_bits7, a8_launch_bits8};      // WT_DENSE16: weights already de-quantised
 
 typedef int (*dq_fn)(const DequantParams&, int, hipStream_t);
 typedef int (*gm_fn)(const GemmParams&, int, int, hipStream_t);
@@ -195,6 +201,7 @@ static int get_dense_buffer(size_t bytes, hipStream_t st, void** out) {
 }
 
 static bool layout_ok(int layout) { return layout == QG_LAYOUT_TILE128x64 || layout == QG_LAYOUT_TILE128x64_R32; }
+static bool pack_layout_ok(int layout) { return layout_ok(layout) || layout == QG_LAYOUT_TILE128x64_I8; }
 static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 static int check_common(qg_wtype t, int layout, int act, int scale_dtype, int64_t group, int64_t K, int64_t N,
@@ -416,7 +423,8 @@ size_t qg_canonical_bytes(int bits, int64_t count) {
 }
 
 size_t qgemm_packed_bytes(qg_wtype t, int layout, int64_t K, int64_t N) {
-  if (!layout_ok(layout) || wt_index(t) == -1) return 0;
+  if (!pack_layout_ok(layout) || wt_index(t) == -1) return 0;
+  if (layout == QG_LAYOUT_TILE128x64_I8 && t.kind == QG_FLOAT) return 0;
   if (K <= 0 || N <= 0 || K % TILE_K || N % TILE_N) return 0;
   return (size_t)(K * N * t.bits / 8);
 }
@@ -429,14 +437,15 @@ int qg_pack_codes(const uint8_t* codes, int bits, int64_t count, uint8_t* stream
 }
 
 int repack(const void* canonical, qg_wtype t, int layout, int64_t K, int64_t N, void* packed_out, void* stream) {
-  if (!layout_ok(layout)) return QG_EINVAL;
+  if (!pack_layout_ok(layout)) return QG_EINVAL;
   int wt = wt_index(t);
   if (wt == -1) return QG_EINVAL;   // any float split can be re-laid out; only the type must be well formed
+  if (layout == QG_LAYOUT_TILE128x64_I8 && t.kind == QG_FLOAT) return QG_EUNSUPPORTED;   // integer weights only
   if (!canonical || !packed_out || canonical == packed_out) return QG_EINVAL;
   if (K <= 0 || N <= 0 || K % TILE_K || N % TILE_N || K > (1 << 24) || N > (1 << 24)) return QG_EINVAL;
   if (!aligned16(packed_out)) return QG_EINVAL;
   uint32_t flip = (t.kind == QG_INT) ? (1u << (t.bits - 1)) : 0u;
-  const int natural = (wt >= 0 && wt_natural(wt)) ? 1 : 0;   // types decoded by the hardware converts
+  const int natural = (wt >= 0 && wt_natural(wt) && layout != QG_LAYOUT_TILE128x64_I8) ? 1 : 0;   // types decoded by the hardware converts
   return launch_repack(static_cast<const uint8_t*>(canonical), t.bits, (int)K, (int)N, flip, natural, layout,
                        static_cast<uint8_t*>(packed_out), static_cast<hipStream_t>(stream));
 }
@@ -578,6 +587,78 @@ int qgemm(const void* A, const void* packed_W, const void* scales, const uint8_t
 int qgemm_noalloc(const void* A, const void* packed_W, const void* scales, const uint8_t* zeros, qg_wtype t, int layout,
                   int act, int scale_dtype, int64_t group, int64_t M, int64_t N, int64_t K, void* C, void* stream) {
   return qgemm_run(A, packed_W, scales, zeros, t, layout, act, scale_dtype, group, M, N, K, C, stream, WS_STATIC);
+}
+
+// int8 activations: wavefronts per strip, row tiles and split-K of one block of at most 64 rows
+static void plan_a8(int M, int N, int K, int* waves_out, int* splitk_out, int* cps_out) {
+  const int KC = K / TILE_K, NCH = N / TILE_N;
+  // eight wavefronts per strip on long K; four with four row tiles (their accumulators and
+  // the ring do not fit the registers eight wavefronts leave each) and on short K
+  int waves = (KC >= 16 && row_tiles(M) < 4) ? 8 : 4;
+  int splitk = knob(1);
+  if (splitk <= 0) {
+    splitk = 1;
+    // K over workgroups while the strips alone leave CUs idle and every wavefront keeps two chunks
+    while (NCH * splitk < 256 && KC / (splitk * 2) >= 2 * waves) splitk *= 2;
+  }
+  if (splitk > KC) splitk = KC;
+  const int cps = (KC + splitk - 1) / splitk;
+  *waves_out = waves; *splitk_out = (KC + cps - 1) / cps; *cps_out = cps;
+}
+
+int qgemm_a8(const int8_t* A8, const float* a_scale, const void* packed_W, const void* scales, const uint8_t* zeros,
+             qg_wtype t, int out_dtype, int scale_dtype, int64_t group, int64_t M, int64_t N, int64_t K, void* C,
+             void* stream) {
+  if (group == 0) group = K;
+  int wt = wt_index(t);
+  if (wt == -1) return QG_EINVAL;
+  if (t.kind == QG_FLOAT) return QG_EUNSUPPORTED;                 // the integer instruction multiplies integers
+  if (K <= 0 || N <= 0 || K % TILE_K || N % TILE_N || K > (1 << 24) || N > (1 << 24)) return QG_EINVAL;
+  if (group <= 0 || K % group) return QG_EINVAL;
+  if (group == 32) return QG_EUNSUPPORTED;                         // the instruction sums 64 values of k
+  if (!((group % TILE_K) == 0 || group == 64)) return QG_EINVAL;
+  if ((out_dtype != QG_F16 && out_dtype != QG_BF16) || (scale_dtype != QG_F16 && scale_dtype != QG_BF16)) return QG_EINVAL;
+  if (M < 0 || M > (1 << 24)) return QG_EINVAL;
+  if (M == 0) return QG_OK;
+  if (!A8 || !packed_W || !scales || !C) return QG_EINVAL;
+  if (!aligned16(A8) || !aligned16(packed_W) || !aligned16(scales) || !aligned16(C) || (zeros && !aligned16(zeros)) ||
+      (a_scale && (reinterpret_cast<uintptr_t>(a_scale) & 3u))) return QG_EINVAL;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (st == hipStreamPerThread) { g_last_error = "hipStreamPerThread is not accepted: pass a stream of your own"; return QG_EINVAL; }
+
+  A8Params p;
+  p.A = A8; p.a_scale = a_scale;
+  p.W = static_cast<const uint8_t*>(packed_W);
+  p.S = static_cast<const uint16_t*>(scales);
+  p.Z = zeros;
+  p.C = static_cast<uint16_t*>(C);
+  p.ws = nullptr; p.tickets = nullptr;
+  p.N = (int)N; p.K = (int)K; p.group = (int)group;
+  p.zbias = (t.kind == QG_INT) ? (1 << (t.bits - 1)) : 0;
+  p.scale_bf16 = (scale_dtype == QG_BF16);
+  p.out_bf16 = (out_dtype == QG_BF16);
+  p.M = 0;
+  if (!set_group_index(p)) return QG_EUNSUPPORTED;
+  for (int64_t r0 = 0; r0 < M; r0 += 64) {
+    A8Params q = p;
+    q.A = p.A + r0 * K;
+    q.a_scale = a_scale ? a_scale + r0 : nullptr;
+    q.C = p.C + r0 * N;
+    q.M = (int)((M - r0 < 64) ? (M - r0) : 64);
+    int waves;
+    plan_a8(q.M, q.N, q.K, &waves, &q.splitk, &q.chunks_per_split);
+    const int mt = row_tiles(q.M);
+    if (q.splitk > 1) {
+      const int NCH = q.N / TILE_N;
+      float* ws = nullptr; unsigned* tk = nullptr;
+      int rc = get_workspace((size_t)q.splitk * NCH * (size_t)(mt * 16 * TILE_N) * sizeof(float), (size_t)NCH, st, &ws, &tk);
+      if (rc != QG_OK) return rc;
+      q.ws = ws; q.tickets = tk;
+    }
+    int rc = kA8[t.bits - 1](q, waves, mt, st);
+    if (rc != QG_OK) return rc;
+  }
+  return QG_OK;
 }
 
 int qg_probe_stream_read(const void* buf, size_t bytes, void* sink, void* stream) {

@@ -37,10 +37,21 @@ namespace qg {
 // This is the paper's "reinterpret each tile as the bytes each thread loads and
 // store the tile contiguously" (Section "Efficient Low-Precision Weight
 // Loading"), with T = 64 lanes and n = 16*BITS bytes per lane, so n1 = 16.
+// A third layout (QG_LAYOUT_TILE128x64_I8) serves the integer matrix instruction
+// v_mfma_i32_16x16x64_i8, whose lane l = 16*b + i feeds row i with 16 consecutive k values
+// as the 16 bytes of four registers.  Same chunks and byte offsets, but the lane's 4*BITS
+// registers are FOUR parallel byte streams (byte lane e = bits [8e, 8e+8) of every register):
+// quad t occupies bits [t*BITS, (t+1)*BITS) of each byte stream, so one shift and one mask
+// turn a register into four int8 operands at once.
+//     t = (j*4 + nt)*4 + v,   j in 0..1 (k-step of 64), nt in 0..3, v in 0..3 (operand register)
+//     byte lane e of quad t:  k = 128*kc + 64*j + 16*b + 4*v + e,   n = 64*nc + 4*i + nt
 constexpr int TILE_K = QG_TILE_K;
 constexpr int TILE_N = QG_TILE_N;
 constexpr int PAIRS = 64;
-constexpr int NUM_LAYOUT = 2;
+constexpr int NUM_LAYOUT = 3;
+constexpr int QUADS = 32;
+__host__ __device__ constexpr int quad_k(int l, int t) { return 64 * (t / 16) + 16 * (l / 16) + 4 * (t & 3); }
+__host__ __device__ constexpr int quad_n(int l, int t) { return 4 * (l % 16) + ((t >> 2) & 3); }
 
 // Per-layout shape: columns per lane (NT), k extent of one matrix instruction
 // (K_STEP), steps per chunk, and the element (k of the lo code, n) offsets inside
@@ -129,8 +140,25 @@ struct GemmParams {
   int gshift, gmask;
 };
 
+// Matmul with int8 activations (third layout, integer matrix instruction).
+struct A8Params {
+  const int8_t* A;        // [M, K] row-major
+  const float* a_scale;   // [M] or null (= 1)
+  const uint8_t* W;
+  const uint16_t* S;
+  const uint8_t* Z;
+  uint16_t* C;
+  float* ws;
+  unsigned* tickets;
+  int M, N, K, group;
+  int zbias, scale_bf16, out_bf16;
+  int splitk, chunks_per_split;
+  int gshift, gmask;      // as in GemmParams
+};
+
 // Fills gshift/gmask; false if the group size has no shift form (128 * odd, != K).
-inline bool set_group_index(GemmParams& p) {
+template <class P>
+inline bool set_group_index(P& p) {
   p.gshift = 0; p.gmask = ~0;
   if (p.group == 64 || p.group == 32) return true;
   if (p.group == p.K) { p.gmask = 0; return true; }

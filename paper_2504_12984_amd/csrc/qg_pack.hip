@@ -50,6 +50,26 @@ __global__ __launch_bounds__(256) void repack_kernel(const uint8_t* __restrict__
   const int l = (int)(gid & 63);
   const int nc = (int)(chunk / KC), kc = (int)(chunk % KC);
   uint32_t* dst = out + chunk * (256 * bits);
+  if (layout == QG_LAYOUT_TILE128x64_I8) {
+    // four parallel byte streams: quad t at bits [t*bits, (t+1)*bits) of byte lane e of the registers
+    for (int d = 0; d < 4 * bits; ++d) {
+      uint32_t word = 0;
+      int t0 = (8 * d) / bits, t1 = (8 * d + 7) / bits;
+      if (t1 > QUADS - 1) t1 = QUADS - 1;
+      for (int t = t0; t <= t1; ++t) {
+        const int n = TILE_N * nc + quad_n(l, t);
+        const int sh = t * bits - 8 * d;
+        for (int e = 0; e < 4; ++e) {
+          const int k = TILE_K * kc + quad_k(l, t) + e;
+          const uint32_t code = fetch_code(canon, canon_bytes, (int64_t)k * N + n, bits) ^ flip;
+          const uint32_t part = ((sh >= 0) ? (code << sh) : (code >> (-sh))) & 0xffu;
+          word |= part << (8 * e);
+        }
+      }
+      dst[(d >> 2) * 256 + l * 4 + (d & 3)] = word;
+    }
+    return;
+  }
   if (natural) {
     // plain order: code c = 2t + {0 lo, 1 hi} of the lane at bits [c*bits, (c+1)*bits)
     for (int d = 0; d < 4 * bits; ++d) {

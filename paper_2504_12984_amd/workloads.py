@@ -9,7 +9,7 @@ inputs (Section "Performance of Low-Precision Kernels", artifact appendix "Data
 sets"); the cases below are dense i.i.d. stand-ins of those shapes.
 
 Draw order per case, from numpy Generator(PCG64(seed)):  A, codes, scales, then
-(only when they are random) the zero-points.
+(only when they are random) the zero-points, then (int8 activations only) the row scales.
 """
 from __future__ import annotations
 
@@ -39,6 +39,7 @@ class Case:
     zero: Optional[object] = None   # constant zero-point; "random": one draw per (group, column),
                                     # uniform over 0 .. zero_hi; None = no zero-point array
     zero_hi: Optional[int] = None   # largest random zero-point (default 2^bits - 1)
+    a8: bool = False                # int8 activations: A is int8 with one fp32 scale per row; `act` is C's dtype
     scale_lo: float = 0.005
     scale_hi: float = 0.02
     seed: int = 0
@@ -70,7 +71,11 @@ def make_inputs(case: Case):
            drawn uniformly from 0 .. zero_hi per (group, column) -- or None
     """
     rng = np.random.Generator(np.random.PCG64(case.seed))
-    A = torch.from_numpy(rng.standard_normal((case.M, case.K), dtype=np.float32)).to(_TORCH[case.act])
+    A = torch.from_numpy(rng.standard_normal((case.M, case.K), dtype=np.float32))
+    if case.a8:      # the same N(0,1) draw quantised to int8 at about 1/40 per step (saturating)
+        A = torch.clamp(torch.round(A * 40.0), -127, 127).to(torch.int8)
+    else:
+        A = A.to(_TORCH[case.act])
     bad = _nonfinite_codes(case)
     if bad:
         ok = np.array([c for c in range(1 << case.bits) if c not in bad], dtype=np.uint8)
@@ -87,7 +92,10 @@ def make_inputs(case: Case):
         zeros = rng.integers(0, hi + 1, size=(G, case.N), dtype=np.uint8)
     else:
         zeros = np.full((G, case.N), case.zero, dtype=np.uint8)
-    return {"A": A, "codes": codes, "scales": scales, "zeros": zeros}
+    out = {"A": A, "codes": codes, "scales": scales, "zeros": zeros}
+    if case.a8:
+        out["a_scale"] = torch.from_numpy(rng.uniform(0.02, 0.03, size=case.M).astype(np.float32))
+    return out
 
 
 # ---- the five named configurations -----------------------------------------
