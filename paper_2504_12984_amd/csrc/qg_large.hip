@@ -14,6 +14,8 @@
 // Workgroup ids are remapped so that the workgroups resident on one XCD (ids
 // congruent mod 8) form 4 x 8 panels of tiles that share A and W in that XCD's L2.
 // Compiled once per weight type (QG_WT).
+// QG_DBG_NOBARRIER / NOAFRAG / NOSTAGE (never defined by the build) each cut one stage out for
+// timing experiments -- results are wrong with them.
 #include "qg_decode.h"
 #include "qg_static_for.h"
 
@@ -126,7 +128,15 @@ __global__ __launch_bounds__(256) void large_kernel(GemmParams p, int tiles_m, i
     return __builtin_amdgcn_raw_buffer_load_b128(a_rsrc, (int)(a_off0 + (uint32_t)i * a_step + past),
                                                  min(kstep, 4 * KC - 1) * 64, 0);
   };
-  u4_t stage[2][PIECES];
+  // Staging registers: SETS sets of PIECES pieces; a piece is loaded SETS k-steps before it is
+  // stored to LDS (2: half a chunk ahead; 4: a whole chunk ahead -- measured on the prefill
+  // shapes: no difference, the loads are not late; 2 is the build's value).
+#ifndef QG_STAGE_SETS
+#define QG_STAGE_SETS 2
+#endif
+  constexpr int SETS = QG_STAGE_SETS;
+  static_assert(SETS == 2 || SETS == 4, "staging distance");
+  u4_t stage[SETS][PIECES];
   auto a_issue = [&](int set, int kstep) __attribute__((always_inline)) {
 #pragma unroll
     for (int i = 0; i < PIECES; ++i) stage[set][i] = a_load(i, kstep);
@@ -207,11 +217,19 @@ __global__ __launch_bounds__(256) void large_kernel(GemmParams p, int tiles_m, i
   WStage wA, wB;
   w_issue(wA, kbeg);
   const int ks0 = 4 * kbeg;
-  a_issue(0, ks0); a_issue(1, ks0 + 1);
-  a_commit(0, 0, 0); a_issue(0, ks0 + 2);
-  a_commit(1, 0, 1); a_issue(1, ks0 + 3);
-  a_commit(0, 0, 2); a_issue(0, ks0 + 4);     // slice 0 of the second chunk
-  a_commit(1, 0, 3); a_issue(1, ks0 + 5);     // slice 1 of the second chunk
+  if constexpr (SETS == 2) {
+    a_issue(0, ks0); a_issue(1, ks0 + 1);
+    a_commit(0, 0, 0); a_issue(0, ks0 + 2);
+    a_commit(1, 0, 1); a_issue(1, ks0 + 3);
+    a_commit(0, 0, 2); a_issue(0, ks0 + 4);     // slice 0 of the second chunk
+    a_commit(1, 0, 3); a_issue(1, ks0 + 5);     // slice 1 of the second chunk
+  } else {
+    a_issue(0, ks0); a_issue(1, ks0 + 1); a_issue(2, ks0 + 2); a_issue(3, ks0 + 3);
+    a_commit(0, 0, 0); a_issue(0, ks0 + 4);     // the four slices of the second chunk
+    a_commit(1, 0, 1); a_issue(1, ks0 + 5);
+    a_commit(2, 0, 2); a_issue(2, ks0 + 6);
+    a_commit(3, 0, 3); a_issue(3, ks0 + 7);
+  }
 
   // my A fragment of row-tile mt, k-step slice j: piece b of row mt*16 + i16
   const int a_rd = i16 * 64 + 16 * (b ^ lds_swizzle(i16));
@@ -246,8 +264,8 @@ __global__ __launch_bounds__(256) void large_kernel(GemmParams p, int tiles_m, i
   __syncthreads();
 
   // Extra-item table, gap 3 of row tile MT in k-step J:
-  //   MT % 4 == 0   store the A staging piece MT/4 loaded two k-steps ago
-  //   MT % 4 == 2   start the load of that piece for two k-steps from now
+  //   MT % 4 == 0   store the A staging piece MT/4 loaded SETS k-steps ago
+  //   MT % 4 == 2   start the load of that piece for SETS k-steps from now
   //   odd MT        (index MT/2 within the step) k-steps 0 and 1: WPS loads of the next
   //                 chunk's weights; last CSLOTS of k-step 2: the next chunk's first-group
   //                 constants, CPS columns each; first CSLOTS of k-step 3 (two groups per
@@ -285,7 +303,11 @@ __global__ __launch_bounds__(256) void large_kernel(GemmParams p, int tiles_m, i
     // A fragments: flat index f = J*MTS + MT over the chunk, read two tiles ahead
     const uint8_t* abase = lds + CUR * L::BUF + a_rd;
     auto a_read = [&](int f) __attribute__((always_inline)) {
+#ifdef QG_DBG_NOAFRAG
+      return (u4_t){0x3c003c00u + (uint32_t)f, 0x3c003c00u, 0x3c003c00u, (uint32_t)(uintptr_t)abase};
+#else
       return *reinterpret_cast<const u4_t*>(abase + (f / MTS) * L::SLICE + (f % MTS) * (16 * 64));
+#endif
     };
     u4_t ar[3];
     ar[0] = a_read(0);
@@ -330,11 +352,15 @@ __global__ __launch_bounds__(256) void large_kernel(GemmParams p, int tiles_m, i
         __builtin_amdgcn_sched_barrier(0);
         // ---- the one extra item of this tile --------------------------------------------
         if constexpr (MT % 4 == 0) {
+#ifndef QG_DBG_NOSTAGE
           constexpr int I = MT / 4;
-          *reinterpret_cast<u4_t*>(lds + NXT * L::BUF + J * L::SLICE + a_dst0 + 4096 * I) = stage[J & 1][I];
+          *reinterpret_cast<u4_t*>(lds + NXT * L::BUF + J * L::SLICE + a_dst0 + 4096 * I) = stage[J % SETS][I];
+#endif
         } else if constexpr (MT % 4 == 2) {
+#ifndef QG_DBG_NOSTAGE
           constexpr int I = MT / 4;
-          stage[J & 1][I] = a_load(I, 4 * (kc + 1) + J + 2);
+          stage[J % SETS][I] = a_load(I, 4 * (kc + 1) + J + SETS);     // SETS k-steps from now
+#endif
         } else {
           constexpr int IDX = MT / 2;                  // 0 .. FREE_PER_STEP-1
           constexpr int FS = J * FREE_PER_STEP + IDX;
@@ -368,7 +394,9 @@ __global__ __launch_bounds__(256) void large_kernel(GemmParams p, int tiles_m, i
 #pragma unroll
       for (int nt = 0; nt < 4; ++nt) wf[JN & 1][nt] = (u4_t){nf[nt][0], nf[nt][1], nf[nt][2], nf[nt][3]};
     });
+#ifndef QG_DBG_NOBARRIER
     __syncthreads();
+#endif
   };
 
   // Chunks go in pairs (buffers, weight stages and constants alternate); an odd chunk
