@@ -14,7 +14,7 @@
 // Workgroup ids are remapped so that the workgroups resident on one XCD (ids
 // congruent mod 8) form 4 x 8 panels of tiles that share A and W in that XCD's L2.
 // Compiled once per weight type (QG_WT).
-// QG_DBG_NOBARRIER / NOAFRAG / NOSTAGE (never defined by the build) each cut one stage out for
+// QG_DBG_NOBARRIER / NOAFRAG / NOSTAGE / NOWLOAD (never defined by the build) each cut one stage out for
 // timing experiments -- results are wrong with them.
 #include "qg_decode.h"
 #include "qg_static_for.h"
@@ -364,10 +364,12 @@ __global__ __launch_bounds__(256) void large_kernel(GemmParams p, int tiles_m, i
         } else {
           constexpr int IDX = MT / 2;                  // 0 .. FREE_PER_STEP-1
           constexpr int FS = J * FREE_PER_STEP + IDX;
+#ifndef QG_DBG_NOWLOAD
           static_for<WPS>([&](auto Xc) __attribute__((always_inline)) {
             constexpr int I = FS * WPS + decltype(Xc)::value;
             if constexpr (I < WPIECES) w_piece(wn, kc + 1, std::integral_constant<int, I>{});
           });
+#endif
           static_for<CPS>([&](auto Xc) __attribute__((always_inline)) {
             constexpr int X = decltype(Xc)::value;
             if constexpr (!FOUR_GROUPS && J == 2 && IDX >= FREE_PER_STEP - CSLOTS)
