@@ -196,6 +196,23 @@ def from_bits(u: np.ndarray, fmt: str) -> np.ndarray:
 
 
 # --------------------------------------------------------------------------
+# Power-of-two block scales (microscaling; the paper's closing remark that
+# microscaling types are "a more fine-grained quantization" it could support)
+# --------------------------------------------------------------------------
+def e8m0_values(e: np.ndarray) -> np.ndarray:
+    """fp64 value of 8-bit exponent-only scales: 2^(e - 127); the code 255 is NaN.
+
+    This is the shared-scale format of the OCP microscaling types (one scale per
+    block of 32 elements).  With such scales the de-quantised weight
+    value(code) * 2^(e - 127) needs no rounding while it stays inside the target
+    format's range, so the rest of the oracle (dequant_exact, round_rne) applies
+    unchanged with these values as `scales`.
+    """
+    e = np.asarray(e, dtype=np.uint8).astype(np.int64)
+    return np.where(e == 255, np.nan, np.ldexp(1.0, e - 127))
+
+
+# --------------------------------------------------------------------------
 # De-quantise and contract
 # --------------------------------------------------------------------------
 def dequant_exact(codes, kind, bits, ebits, mbits, scales, zeros, group):

@@ -208,3 +208,19 @@ def test_every_pattern_round_trips():
         u, v = _all_finite(fmt)
         assert np.array_equal(O.round_rne(v, fmt), v)
         assert np.array_equal(O.to_bits(v, fmt), u)
+
+
+def test_e8m0_block_scales_are_powers_of_two_and_match_torch():
+    import torch
+    e = np.arange(256, dtype=np.uint8)
+    v = O.e8m0_values(e)
+    assert v[127] == 1.0 and v[128] == 2.0 and v[126] == 0.5 and v[0] == 2.0 ** -127 and v[254] == 2.0 ** 127
+    assert np.isnan(v[255]) and np.all(v[1:255] == 2.0 * v[0:254])
+    if hasattr(torch, "float8_e8m0fnu"):                       # the library's table of the same format
+        t = torch.from_numpy(e.copy()).view(torch.float8_e8m0fnu).to(torch.float32).numpy().astype(np.float64)
+        assert np.array_equal(t[:255], v[:255]) and np.isnan(t[255])
+    # with such scales the rounded weight is the exact product while it stays in range
+    codes = np.arange(16, dtype=np.uint8).reshape(16, 1)
+    s = O.e8m0_values(np.array([[120]], dtype=np.uint8))
+    wr, bits = O.dequant_rounded(codes, O.KIND_FLOAT, 4, 2, 1, s, None, 16, "f16")
+    assert np.array_equal(wr, O.code_values(O.KIND_FLOAT, 4, 2, 1)[codes] * 2.0 ** -7)
