@@ -92,6 +92,12 @@ def cases_for(name):
         rest = name[4:]
         bits, m = rest.split("_M") if "_M" in rest else (rest, "16")
         return [WL.shrink(WL.cfg3(int(bits)), M=int(m), a8=True, name=name)]
+    if name.startswith("mx_f") or name.startswith("mxsweep_f"):     # block-scaled e2m1 / e4m3: mx_f4_M1 (K = N = 8192), mxsweep_f8_M16 (N = 57344)
+        big = name.startswith("mxsweep")
+        bits, m = name.split("_f")[1].split("_M")
+        e, mm = {4: (2, 1), 8: (4, 3)}[int(bits)]
+        return [WL.Case(name, int(m), 8192, 57344 if big else 8192, WL.KIND_FLOAT, int(bits), e, mm, group=32,
+                        act="bf16", scale_dtype="e8m0", zero=None, seed=700 + int(bits))]
     if name.startswith("sweep_"):                        # sweep_u4, sweep_i7, sweep_f6 (M = 16), sweep_u4_M8192
         kind = {"u": WL.KIND_UINT, "i": WL.KIND_INT, "f": WL.KIND_FLOAT}[name[6]]
         rest = name[7:]
@@ -106,7 +112,7 @@ def algorithmic_bytes(c):
     """Bytes one call must move: packed W once, scales, zero-points, A, C."""
     P = c.K * c.N * c.bits // 8
     G = c.K // c.group
-    S = G * c.N * 2
+    S = G * c.N * (1 if c.scale_dtype == "e8m0" else 2)
     Z = G * c.N if c.zero is not None else 0
     a_bytes = c.M * c.K + c.M * 4 if c.a8 else c.M * c.K * 2            # int8 rows + one fp32 scale per row
     return P, P + S + Z + a_bytes + c.M * c.N * 2
@@ -124,6 +130,8 @@ def decode_lane_ops_per_element(c):
         # int8 activations: a shift and a mask per register of four codes, + 3 per accumulator
         # and scale group for the zero-point / convert / scale step (16 accumulators per 64 x 128)
         return 2 / 4.0 + 3 * 16 / (64.0 * min(c.group, 128))
+    if c.scale_dtype == "e8m0":
+        return 1 / 2.0            # one scaled hardware convert per pair of codes
     hw = c.kind == WL.KIND_FLOAT and (c.ebits, c.mbits) in ((2, 1), (3, 2), (4, 3))
     per_pair = (2 if hw else 3) if c.act == "f16" else (3 if hw else 4)
     return per_pair / 2.0

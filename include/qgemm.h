@@ -67,7 +67,7 @@ extern "C" {
 
 typedef enum { QG_OK = 0, QG_EINVAL = -1, QG_EUNSUPPORTED = -2, QG_EHIP = -3 } qg_status;
 typedef enum { QG_UINT = 0, QG_INT = 1, QG_FLOAT = 2 } qg_kind;
-typedef enum { QG_F16 = 0, QG_BF16 = 1 } qg_dtype;      /* activation / scale dtype */
+typedef enum { QG_F16 = 0, QG_BF16 = 1, QG_E8M0 = 2 } qg_dtype;   /* activation / scale dtype; QG_E8M0: scales only */
 
 /* Weight type.  uint/int: bits in 1..8, ebits = mbits = 0.  float: 1 + ebits +
  * mbits == bits; supported splits are the paper's representative set
@@ -127,7 +127,15 @@ QG_API int repack(const void* canonical, qg_wtype t, int layout, int64_t K, int6
            void* packed_out, void* stream);
 
 /* W_out[K,N] (row-major, `act` dtype) = rounded de-quantised weights.
- *   scales [K/group, N] row-major, dtype `scale_dtype`
+ *   scales [K/group, N] row-major, dtype `scale_dtype` (QG_F16 or QG_BF16), or -- microscaling
+ *          block scales, which the paper's closing section names as a finer-grained
+ *          quantisation it could support -- QG_E8M0: one BYTE e per 32 rows and column, the
+ *          scale is 2^(e - 127), e in 1 .. 254.  Block scales go with group == 32, no
+ *          zero-points, the float types e2m1 and e4m3 (the 4- and 8-bit microscaling element
+ *          types) and QG_LAYOUT_TILE128x64; anything else with QG_E8M0 is QG_EUNSUPPORTED.
+ *          The hardware's scaled converts apply the scale, so a de-quantised pair of codes
+ *          costs one instruction; qgemm runs such weights through the streaming kernel (rows
+ *          beyond 64 in blocks of 64: there is no tiled kernel for them yet)
  *   zeros  [K/group, N] row-major uint8, or NULL for zero-point 0
  *   group  rows of W per scale, dividing K: 32, 64, 128 * 2^s, or K itself (= one scale per
  *          output column; 0 means the same).  128 * odd (other than K) is a valid group

@@ -19,7 +19,7 @@ LIB_PATH = os.environ.get("QGEMM_LIB") or os.path.join(_HERE, "libqgemm.so")
 
 QG_OK, QG_EINVAL, QG_EUNSUPPORTED, QG_EHIP = 0, -1, -2, -3
 QG_UINT, QG_INT, QG_FLOAT = 0, 1, 2
-QG_F16, QG_BF16 = 0, 1
+QG_F16, QG_BF16, QG_E8M0 = 0, 1, 2
 QG_LAYOUT_TILE128x64 = 0
 QG_LAYOUT_TILE128x64_R32 = 1
 QG_LAYOUT_TILE128x64_I8 = 2
@@ -96,6 +96,8 @@ def _load() -> ctypes.CDLL:
 _lib = _load()
 
 _DT = {torch.float16: QG_F16, torch.bfloat16: QG_BF16}
+# scale tensors may also be uint8: 8-bit exponents, one per 32 rows (microscaling block scales)
+_SDT = {torch.float16: QG_F16, torch.bfloat16: QG_BF16, torch.uint8: QG_E8M0}
 
 
 def _stream() -> int:
@@ -149,7 +151,7 @@ def qdequant(packed: torch.Tensor, scales: torch.Tensor, zeros, t: WType, act: t
              group: int, K: int, N: int, layout: int = QG_LAYOUT_TILE128x64) -> torch.Tensor:
     out = torch.empty((K, N), dtype=act, device=packed.device)
     rc = _lib.qdequant(_ptr(packed, "packed"), _ptr(scales, "scales"), _ptr(zeros, "zeros"), t.c(), layout,
-                       _DT[act], _DT[scales.dtype], group, K, N, _ptr(out, "out"), _stream())
+                       _DT[act], _SDT[scales.dtype], group, K, N, _ptr(out, "out"), _stream())
     _check("qdequant", rc)
     return out
 
@@ -164,15 +166,15 @@ def qgemm(A: torch.Tensor, packed: torch.Tensor, scales: torch.Tensor, zeros, t:
         raise ValueError("A must be [M,K] fp16 or bf16")
     M, K = A.shape
     rows = K // group if group > 0 else 1                    # group 0 = one scale per output column
-    if scales.dtype not in _DT or tuple(scales.shape) != (rows, N):
-        raise ValueError("scales must be [K/group, N] fp16 or bf16")
+    if scales.dtype not in _SDT or tuple(scales.shape) != (rows, N):
+        raise ValueError("scales must be [K/group, N] fp16 or bf16 (or uint8 exponents for block scales)")
     if zeros is not None and (zeros.dtype != torch.uint8 or tuple(zeros.shape) != (rows, N)):
         raise ValueError("zeros must be uint8 [K/group, N]")
     if out is None:
         out = torch.empty((M, N), dtype=A.dtype, device=A.device)
     fn = {"qgemm": _lib.qgemm, "qgemm_noalloc": _lib.qgemm_noalloc}[entry]
     rc = fn(_ptr(A, "A"), _ptr(packed, "packed"), _ptr(scales, "scales"), _ptr(zeros, "zeros"), t.c(),
-            layout, _DT[A.dtype], _DT[scales.dtype], group, M, N, K, _ptr(out, "C"), _stream())
+            layout, _DT[A.dtype], _SDT[scales.dtype], group, M, N, K, _ptr(out, "C"), _stream())
     _check(entry, rc)
     return out
 
@@ -192,7 +194,7 @@ def qgemm_a8(A8: torch.Tensor, a_scale, packed: torch.Tensor, scales: torch.Tens
     M, K = A8.shape
     rows = K // group if group > 0 else 1
     if scales.dtype not in _DT or tuple(scales.shape) != (rows, N):
-        raise ValueError("scales must be [K/group, N] fp16 or bf16")
+        raise ValueError("scales must be [K/group, N] fp16 or bf16 (or uint8 exponents for block scales)")
     if zeros is not None and (zeros.dtype != torch.uint8 or tuple(zeros.shape) != (rows, N)):
         raise ValueError("zeros must be uint8 [K/group, N]")
     if a_scale is not None and (a_scale.dtype != torch.float32 or tuple(a_scale.shape) != (M,)):
@@ -226,8 +228,8 @@ class BoundQgemm:
             raise ValueError("A must be [M,K] fp16 or bf16")
         M, K = A.shape
         rows = K // group if group > 0 else 1                    # group 0 = one scale per output column
-        if scales.dtype not in _DT or tuple(scales.shape) != (rows, N):
-            raise ValueError("scales must be [K/group, N] fp16 or bf16")
+        if scales.dtype not in _SDT or tuple(scales.shape) != (rows, N):
+            raise ValueError("scales must be [K/group, N] fp16 or bf16 (or uint8 exponents for block scales)")
         if zeros is not None and (zeros.dtype != torch.uint8 or tuple(zeros.shape) != (rows, N)):
             raise ValueError("zeros must be uint8 [K/group, N]")
         if tuple(out.shape) != (M, N) or out.dtype != A.dtype:
@@ -236,7 +238,7 @@ class BoundQgemm:
         self._keep = (A, packed, scales, zeros, out)
         self.out = out
         self._args = (vp(_ptr(A, "A")), vp(_ptr(packed, "packed")), vp(_ptr(scales, "scales")),
-                      vp(_ptr(zeros, "zeros")), t.c(), i32(layout), i32(_DT[A.dtype]), i32(_DT[scales.dtype]),
+                      vp(_ptr(zeros, "zeros")), t.c(), i32(layout), i32(_DT[A.dtype]), i32(_SDT[scales.dtype]),
                       i64(group), i64(M), i64(N), i64(K), vp(_ptr(out, "C")),
                       vp(_stream() if stream is None else stream))
 
@@ -257,7 +259,7 @@ class BoundQgemmA8:
         M, K = A8.shape
         rows = K // group if group > 0 else 1
         if scales.dtype not in _DT or tuple(scales.shape) != (rows, N):
-            raise ValueError("scales must be [K/group, N] fp16 or bf16")
+            raise ValueError("scales must be [K/group, N] fp16 or bf16 (or uint8 exponents for block scales)")
         if zeros is not None and (zeros.dtype != torch.uint8 or tuple(zeros.shape) != (rows, N)):
             raise ValueError("zeros must be uint8 [K/group, N]")
         if a_scale is not None and (a_scale.dtype != torch.float32 or tuple(a_scale.shape) != (M,)):

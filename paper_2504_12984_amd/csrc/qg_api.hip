@@ -213,8 +213,10 @@ static int check_common(qg_wtype t, int layout, int act, int scale_dtype, int64_
   if (K <= 0 || N <= 0 || K % TILE_K || N % TILE_N || K > (1 << 24) || N > (1 << 24)) return QG_EINVAL;
   if (group <= 0 || K % group) return QG_EINVAL;
   if (!((group % TILE_K) == 0 || group == 64 || group == 32)) return QG_EINVAL;
-  if ((act != QG_F16 && act != QG_BF16) || (scale_dtype != QG_F16 && scale_dtype != QG_BF16)) return QG_EINVAL;
+  if ((act != QG_F16 && act != QG_BF16) || (scale_dtype != QG_F16 && scale_dtype != QG_BF16 && scale_dtype != QG_E8M0)) return QG_EINVAL;
   if (act == QG_F16 && scale_dtype == QG_BF16) return QG_EUNSUPPORTED;
+  // power-of-two block scales: 32 rows per scale, e2m1 / e4m3 codes (the scaled hardware converts), first layout
+  if (scale_dtype == QG_E8M0 && (group != 32 || !(wt == 9 || wt == 13) || layout != QG_LAYOUT_TILE128x64)) return QG_EUNSUPPORTED;
   *wt_out = wt;
   *route_out = (act == QG_F16) ? ROUTE_F16 : ROUTE_BF16;
   return QG_OK;
@@ -224,7 +226,10 @@ static int check_common(qg_wtype t, int layout, int act, int scale_dtype, int64_
 static int row_tiles(int64_t M) { return M <= 16 ? 1 : (M <= 32 ? 2 : 4); }
 
 // Streaming kernel (M <= 64): wavefront arrangement and split-K by shape.  Host arithmetic only.
-static void plan_streaming(int M, int N, int K, int group, int wt, int* variant_out, int* splitk_out, int* cps_out) {
+// (mx: block-scaled weights -- group 32, but only four scale bytes per block and lane, so every
+// arrangement has the registers for them)
+static void plan_streaming(int M, int N, int K, int group, int wt, int* variant_out, int* splitk_out, int* cps_out,
+                           bool mx = false) {
   const int KC = K / TILE_K, NCH = N / TILE_N;
   const int mt = row_tiles(M);
   int variant = 10 * mt + 1;                  // 4 wavefronts on one strip
@@ -267,7 +272,7 @@ static void plan_streaming(int M, int N, int K, int group, int wt, int* variant_
   // wavefronts at 3 bits; 8-bit codes: two strips x 4 wavefronts, 23.5 against 27.3)
   if (variant == 11 && KC > 32 && NCH > 128 && NCH < 256) variant = wt_bits(wt) <= 6 ? 10 : (NCH % 2 == 0 ? 14 : 11);
   if (knob(3) > 0) variant = knob(3);
-  if (group == 32) variant = 10 * mt + 1;          // four groups per chunk: the 4-wavefront arrangements only
+  if (group == 32 && !mx) variant = 10 * mt + 1;   // four groups per chunk: the 4-wavefront arrangements only
   const int waves = kDecodeWaves[wt](variant);
   // Split K over workgroups only when the column strips alone cannot fill the
   // 256 CUs, and never below 4 chunks per wavefront (2 with 16 wavefronts per strip, or with a
@@ -294,7 +299,7 @@ static void plan_streaming(int M, int N, int K, int group, int wt, int* variant_
 // One launch of the streaming kernel.
 static int launch_streaming(GemmParams& p, int wt, int route, int ws_mode, hipStream_t st) {
   int variant;
-  plan_streaming(p.M, p.N, p.K, p.group, wt, &variant, &p.splitk, &p.chunks_per_split);
+  plan_streaming(p.M, p.N, p.K, p.group, wt, &variant, &p.splitk, &p.chunks_per_split, p.scale_e8m0 != 0);
   const int mt = row_tiles(p.M);
   if (variant / 10 != mt) { g_last_error = "wavefront arrangement does not cover M rows"; return QG_EINVAL; }
   if (p.splitk > 1) {
@@ -467,6 +472,8 @@ int qdequant(const void* packed_W, const void* scales, const uint8_t* zeros, qg_
   p.K = (int)K; p.N = (int)N; p.group = (int)group;
   p.zbias = (t.kind == QG_INT) ? (1 << (t.bits - 1)) : 0;
   p.scale_bf16 = (scale_dtype == QG_BF16);
+  p.scale_e8m0 = (scale_dtype == QG_E8M0);
+  if (p.scale_e8m0 && zeros) return QG_EINVAL;       // block scales come without zero-points
   p.frag_out = 0;
   return kDequant[wt](p, route, static_cast<hipStream_t>(stream));
 }
@@ -506,6 +513,8 @@ static int qgemm_run(const void* A, const void* packed_W, const void* scales, co
   p.M = (int)M; p.N = (int)N; p.K = (int)K; p.group = (int)group;
   p.zbias = (t.kind == QG_INT) ? (1 << (t.bits - 1)) : 0;
   p.scale_bf16 = (scale_dtype == QG_BF16);
+  p.scale_e8m0 = (scale_dtype == QG_E8M0);
+  if (p.scale_e8m0 && zeros) return QG_EINVAL;       // block scales come without zero-points
   p.splitk = 1; p.chunks_per_split = (int)(K / TILE_K);
   if (!set_group_index(p)) return QG_EUNSUPPORTED;
 
@@ -518,7 +527,10 @@ static int qgemm_run(const void* A, const void* packed_W, const void* scales, co
     return kLarge32[wt](p, route, knob(2), st);
   }
 
-  const int path = plan_path(M, N, K, t);
+  int path = plan_path(M, N, K, t);
+  if (p.scale_e8m0) {                                // block-scaled weights: the streaming kernel, rows in blocks of 64
+    if (path == 2 || path == 4) { if (knob(0)) return QG_EUNSUPPORTED; path = (M > 64) ? 3 : 1; }
+  }
   if (path == 1 && M > 64) return QG_EINVAL;
   if (path < 1 || path > 4) return QG_EINVAL;
 
@@ -535,6 +547,7 @@ static int qgemm_run(const void* A, const void* packed_W, const void* scales, co
     DequantParams d;
     d.W = p.W; d.S = p.S; d.Z = p.Z; d.out = static_cast<uint16_t*>(dense);
     d.layout = QG_LAYOUT_TILE128x64; d.K = p.K; d.N = p.N; d.group = p.group; d.zbias = p.zbias; d.scale_bf16 = p.scale_bf16;
+    d.scale_e8m0 = 0;
     d.frag_out = 1;
     rc = kDequant[wt](d, route, st);
     if (rc != QG_OK) return rc;
@@ -555,7 +568,7 @@ static int qgemm_run(const void* A, const void* packed_W, const void* scales, co
 
   if (path == 1 || path == 3) {
     // a forced arrangement must have the row tiles every block of rows needs, or rows would stay unwritten
-    if (knob(3) > 0 && group != 32)
+    if (knob(3) > 0 && (group != 32 || p.scale_e8m0))
       for (int64_t r0 = 0; r0 < M; r0 += 64)
         if (knob(3) / 10 != row_tiles(M - r0 < 64 ? M - r0 : 64)) { g_last_error = "forced wavefront arrangement does not cover the rows of M"; return QG_EINVAL; }
     for (int64_t r0 = 0; r0 < M; r0 += 64) {
@@ -685,10 +698,14 @@ int qg_plan(qg_wtype t, int layout, int act, int scale_dtype, int64_t group, int
     return (group == 32 || !tiled_operands_fit(M, N, K, group, t.bits)) ? QG_EUNSUPPORTED : QG_OK;
   }
   plan[0] = plan_path(M, N, K, t);
+  if (scale_dtype == QG_E8M0 && (plan[0] == 2 || plan[0] == 4)) {      // block-scaled weights: the streaming kernel only
+    if (knob(0)) return QG_EUNSUPPORTED;
+    plan[0] = (M > 64) ? 3 : 1;
+  }
   if (plan[0] == 1 && M > 64) return QG_EINVAL;
   if (plan[0] == 1 || plan[0] == 3) {
-    plan_streaming((int)(M < 64 ? M : 64), (int)N, (int)K, (int)group, wt, &plan[1], &plan[3], &plan[4]);
-    if (knob(3) > 0 && group != 32)
+    plan_streaming((int)(M < 64 ? M : 64), (int)N, (int)K, (int)group, wt, &plan[1], &plan[3], &plan[4], scale_dtype == QG_E8M0);
+    if (knob(3) > 0 && (group != 32 || scale_dtype == QG_E8M0))
       for (int64_t r0 = 0; r0 < M; r0 += 64)
         if (knob(3) / 10 != row_tiles(M - r0 < 64 ? M - r0 : 64)) return QG_EINVAL;
   } else {

@@ -117,6 +117,7 @@ struct DequantParams {
   int K, N, group;
   int zbias;        // added to every zero-point (2^(bits-1) for intk, else 0)
   int scale_bf16;   // scales are bf16 (only with ROUTE_BF16)
+  int scale_e8m0;   // scales are 8-bit exponents, one per 32 rows (e2m1 / e4m3 weights, group 32, first layout)
   int frag_out;     // 0: out is [K,N] row-major; 1: out is in fragment order (first layout only):
                     // 16 KiB per chunk, the four registers of (k-step j, sub-tile nt) of lane l at
                     // byte (4*j + nt) * 1024 + 16 * l -- what the tiled kernel's pass-through reads
@@ -132,6 +133,7 @@ struct GemmParams {
   unsigned* tickets;    // one arrival counter per output tile, zero between calls
   int M, N, K, group;
   int zbias, scale_bf16;
+  int scale_e8m0;       // scales are 8-bit exponents (streaming kernel only; e2m1 / e4m3, group 32)
   int splitk;           // number of K-slabs (grid.y)
   int chunks_per_split; // K-chunks per slab (last slab may be shorter)
   // group index of K-chunk c without a division: group 64 -> 2c (two groups per

@@ -127,6 +127,42 @@ __device__ __forceinline__ h2_t natural_pair(const uint32_t (&r)[4 * wt_bits(WT)
   }
 }
 
+// The same converts with a power-of-two block scale (an 8-bit exponent, the shared scale of the
+// microscaling types): the hardware multiplies by 2^(exponent of `scale`) while it converts, so
+// the de-quantised pair is ONE instruction.  OUT_BF16 picks the 16-bit type of the result.
+// Only the two-values-per-instruction converts exist per (scale, pair): e2m1 and e4m3 (the
+// 6-bit convert takes one scale for 32 values, which here belong to four columns).
+template <int WT, int T, int OUT_BF16>
+__device__ __forceinline__ uint32_t natural_pair_mx(const uint32_t (&r)[4 * wt_bits(WT)], float scale) {
+  static_assert(WT == 13 || WT == 9, "block-scaled converts exist for e4m3 and e2m1");
+  if constexpr (WT == 13) {
+    if constexpr (OUT_BF16) return __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(r[T / 2], scale, (T % 2) == 1));
+    else                    return __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(r[T / 2], scale, (T % 2) == 1));
+  } else {
+    if constexpr (OUT_BF16) return __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(r[T / 4], scale, T % 4));
+    else                    return __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(r[T / 4], scale, T % 4));
+  }
+}
+
+// One k-step of 32 rows is one scale block: the lane's four columns have one scale byte each
+// (s4, low byte = first column).  2^(e - 127) as fp32 is the byte moved into the exponent field
+// (e in 1 .. 254).
+struct MxConsts {
+  float s[4];
+  __device__ __forceinline__ void make(uint32_t s4) {
+#pragma unroll
+    for (int nt = 0; nt < 4; ++nt) s[nt] = __builtin_bit_cast(float, ((s4 >> (8 * nt)) & 0xffu) << 23);
+  }
+};
+template <int WT, int OUT_BF16, int J, int NT>
+__device__ __forceinline__ void frag_mx(const uint32_t (&r)[4 * wt_bits(WT)], const MxConsts& gc, uint32_t (&out)[4]) {
+  constexpr int T0 = LayoutOf<0>::t0(J, NT);
+  out[0] = natural_pair_mx<WT, T0 + 0, OUT_BF16>(r, gc.s[NT]);
+  out[1] = natural_pair_mx<WT, T0 + 1, OUT_BF16>(r, gc.s[NT]);
+  out[2] = natural_pair_mx<WT, T0 + 2, OUT_BF16>(r, gc.s[NT]);
+  out[3] = natural_pair_mx<WT, T0 + 3, OUT_BF16>(r, gc.s[NT]);
+}
+
 // ============================ per-group constants ================================
 // sraw: the lane's 16-bit scales (its NTL adjacent columns, low bits first), zraw:
 // its zero-point bytes.  Built once per (chunk, group), used by 8 or 16 pairs each.

@@ -59,7 +59,9 @@ __device__ __forceinline__ uint32_t pack_out(float lo, float hi) {
   else return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, b2_t));
 }
 
-template <int WT, int ROUTE, int GPC, int NW, int DEPTH, int MT, int NS = 1>
+// MX: the scales are 8-bit exponents, one per 32 rows and column (GPC = 4), applied by the
+// hardware converts of the e2m1 / e4m3 types; there are no zero-points.
+template <int WT, int ROUTE, int GPC, int NW, int DEPTH, int MT, int NS = 1, bool MX = false>
 __global__ __launch_bounds__(NW * 64) void decode_kernel(GemmParams p) {
   // NS adjacent strips per workgroup, NK wavefronts along K for each: wavefront w
   // works on strip w % NS and takes every NK-th chunk of the slab starting at
@@ -122,6 +124,13 @@ __global__ __launch_bounds__(NW * 64) void decode_kernel(GemmParams p) {
     return;
 #endif
     const int g0 = (GPC > 1) ? GPC * c : ((c >> p.gshift) & p.gmask);
+    if constexpr (MX) {          // four scale bytes (the lane's columns) per block of 32 rows, kept in the zero-point slot
+#pragma unroll
+      for (int g = 0; g < GPC; ++g)
+        s.z[g] = *reinterpret_cast<const uint32_t*>(reinterpret_cast<const uint8_t*>(p.S) + (int64_t)(g0 + g) * p.N + n0);
+      __builtin_amdgcn_sched_barrier(0);
+      return;
+    }
 #ifdef QG_SZ_BCAST
     if (b == 0) {
 #endif
@@ -154,6 +163,23 @@ __global__ __launch_bounds__(NW * 64) void decode_kernel(GemmParams p) {
   auto compute = [&](auto Sc) __attribute__((always_inline)) {
     constexpr int S = decltype(Sc)::value;
     Stage& s = st[S];
+    if constexpr (MX) {
+      static_assert(GPC == 4, "one scale block per k-step");
+      static_for<4>([&](auto Jc) __attribute__((always_inline)) {
+        constexpr int J = decltype(Jc)::value;
+        MxConsts mx;
+        mx.make(s.z[J]);
+        static_for<4>([&](auto NTc) __attribute__((always_inline)) {
+          constexpr int NT = decltype(NTc)::value;
+          uint32_t o[4];
+          frag_mx<WT, ROUTE == ROUTE_BF16, J, NT>(s.r, mx, o);
+          const u4_t wf = {o[0], o[1], o[2], o[3]};
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt) acc[mt][NT] = mfma16<ROUTE>(wf, s.a[mt][J], acc[mt][NT]);
+        });
+      });
+      return;
+    }
     typename D::Consts gc[GPC];
 #ifdef QG_SZ_BCAST
     {
@@ -317,10 +343,10 @@ __global__ __launch_bounds__(NW * 64) void decode_kernel(GemmParams p) {
 #define QG_CAT2(a, b) a##b
 #define QG_CAT(a, b) QG_CAT2(a, b)
 
-template <int ROUTE, int GPC, int NW, int DEPTH, int MT, int NS = 1>
+template <int ROUTE, int GPC, int NW, int DEPTH, int MT, int NS = 1, bool MX = false>
 static int launch_cfg(const GemmParams& p, hipStream_t st) {
   if ((p.N / TILE_N) % NS) return QG_EINVAL;
-  auto kern = decode_kernel<QG_WT, ROUTE, GPC, NW, DEPTH, MT, NS>;
+  auto kern = decode_kernel<QG_WT, ROUTE, GPC, NW, DEPTH, MT, NS, MX>;
   dim3 grid((unsigned)(p.N / TILE_N / NS), (unsigned)p.splitk), block(NW * 64);
   hipLaunchKernelGGL(kern, grid, block, 0, st, p);
   return hipGetLastError() == hipSuccess ? QG_OK : QG_EHIP;
@@ -329,6 +355,24 @@ static int launch_cfg(const GemmParams& p, hipStream_t st) {
 // variant = 10 * (row tiles: 1, 2, 4) + (0: 8 wavefronts per strip, 1: 4 wavefronts, 2: 16 wavefronts)
 template <int ROUTE, int GPC>
 static int launch_variant(const GemmParams& p, int variant, hipStream_t st) {
+  if constexpr (GPC == 4 && (QG_WT == 9 || QG_WT == 13)) {
+    if (p.scale_e8m0) {              // block-scaled e2m1 / e4m3: every arrangement, scaled converts
+      switch (variant) {
+        case 10: return launch_cfg<ROUTE, 4, 8, 2, 1, 1, true>(p, st);
+        case 11: return launch_cfg<ROUTE, 4, 4, 2, 1, 1, true>(p, st);
+        case 12: return launch_cfg<ROUTE, 4, 16, 2, 1, 1, true>(p, st);
+        case 14: return launch_cfg<ROUTE, 4, 8, 2, 1, 2, true>(p, st);
+        case 15: return launch_cfg<ROUTE, 4, 16, 2, 1, 2, true>(p, st);
+        case 16: return launch_cfg<ROUTE, 4, 16, 2, 1, 4, true>(p, st);
+        case 21: return launch_cfg<ROUTE, 4, 4, 2, 2, 1, true>(p, st);
+        case 26: return launch_cfg<ROUTE, 4, 4, 2, 2, 2, true>(p, st);
+        case 46: return launch_cfg<ROUTE, 4, 4, 2, 4, 2, true>(p, st);
+        case 41: return launch_cfg<ROUTE, 4, 4, 2, 4, 1, true>(p, st);
+        default: return QG_EINVAL;
+      }
+    }
+  }
+  if (p.scale_e8m0) return QG_EUNSUPPORTED;
   if constexpr (GPC == 4) {          // group size 32: the 4-wavefront arrangements only
     switch (variant) {
       case 11: return launch_cfg<ROUTE, 4, 4, 2, 1>(p, st);

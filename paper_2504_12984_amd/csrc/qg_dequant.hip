@@ -11,7 +11,9 @@
 
 namespace qg {
 
-template <int WT, int ROUTE, int LY>
+// MX: 8-bit exponent scales, one per 32 rows and column, applied by the scaled hardware converts
+// (e2m1 / e4m3 weights on the first layout).
+template <int WT, int ROUTE, int LY, bool MX = false>
 __global__ __launch_bounds__(256) void dequant_kernel(DequantParams p) {
   typedef Decoder<WT, ROUTE, LY> D;
   typedef LayoutOf<LY> L;
@@ -36,25 +38,35 @@ __global__ __launch_bounds__(256) void dequant_kernel(DequantParams p) {
   static_for<L::STEPS>([&](auto Jc) __attribute__((always_inline)) {
     constexpr int J = decltype(Jc)::value;
     const int g = (TILE_K * kc + L::K_STEP * J) / p.group;
-    uint2 sraw;
+    uint2 sraw = make_uint2(0u, 0u);
     uint32_t zraw = 0u;
-    if constexpr (L::NT == 4) {
+    if constexpr (MX) {
+    } else if constexpr (L::NT == 4) {
       sraw = *reinterpret_cast<const uint2*>(p.S + (int64_t)g * p.N + n0);
       if (p.Z) zraw = *reinterpret_cast<const uint32_t*>(p.Z + (int64_t)g * p.N + n0);
     } else {
       sraw = make_uint2(*reinterpret_cast<const uint32_t*>(p.S + (int64_t)g * p.N + n0), 0u);
       if (p.Z) zraw = *reinterpret_cast<const uint16_t*>(p.Z + (int64_t)g * p.N + n0);
     }
-    typename D::Consts gc;
-    D::make_consts(gc, sraw, zraw, p.zbias, p.scale_bf16);
     // all of the lane's columns for this k-step, then one store per row: the lane's
     // NT adjacent columns are 2*NT contiguous bytes, and the 16 (32) lanes of a k-block
     // together write 128 contiguous bytes of the row
     uint32_t o[L::NT][4];
-    static_for<L::NT>([&](auto NTc) __attribute__((always_inline)) {
-      constexpr int NT = decltype(NTc)::value;
-      D::template frag<J, NT>(r, gc, u, o[NT]);
-    });
+    if constexpr (MX) {
+      MxConsts mx;
+      mx.make(*reinterpret_cast<const uint32_t*>(reinterpret_cast<const uint8_t*>(p.S) + (int64_t)(4 * kc + J) * p.N + n0));
+      static_for<4>([&](auto NTc) __attribute__((always_inline)) {
+        constexpr int NT = decltype(NTc)::value;
+        frag_mx<WT, ROUTE == ROUTE_BF16, J, NT>(r, mx, o[NT]);
+      });
+    } else {
+      typename D::Consts gc;
+      D::make_consts(gc, sraw, zraw, p.zbias, p.scale_bf16);
+      static_for<L::NT>([&](auto NTc) __attribute__((always_inline)) {
+        constexpr int NT = decltype(NTc)::value;
+        D::template frag<J, NT>(r, gc, u, o[NT]);
+      });
+    }
     if constexpr (LY == 0) {
       if (p.frag_out) {            // the registers as they are, one 16-byte store per (k-step, sub-tile): 1 KiB per wavefront
         uint4* dst = reinterpret_cast<uint4*>(reinterpret_cast<uint8_t*>(p.out) + chunk * 16384) + l;
@@ -91,6 +103,16 @@ static void launch_ly(const DequantParams& p, int route, dim3 grid, dim3 block, 
 int QG_CAT(dequant_launch_wt, QG_WT)(const DequantParams& p, int route, hipStream_t st) {
   int64_t nchunks = (int64_t)(p.K / TILE_K) * (p.N / TILE_N);
   dim3 grid((unsigned)((nchunks + 3) / 4)), block(256);
+  if (p.scale_e8m0) {
+#if QG_WT == 9 || QG_WT == 13
+    if (p.layout != 0 || p.group != 32) return QG_EUNSUPPORTED;
+    if (route == ROUTE_F16) hipLaunchKernelGGL((dequant_kernel<QG_WT, ROUTE_F16, 0, true>), grid, block, 0, st, p);
+    else                    hipLaunchKernelGGL((dequant_kernel<QG_WT, ROUTE_BF16, 0, true>), grid, block, 0, st, p);
+    return hipGetLastError() == hipSuccess ? QG_OK : QG_EHIP;
+#else
+    return QG_EUNSUPPORTED;
+#endif
+  }
   if (p.layout == 0) launch_ly<0>(p, route, grid, block, st);
   else               launch_ly<1>(p, route, grid, block, st);
   return hipGetLastError() == hipSuccess ? QG_OK : QG_EHIP;

@@ -21,6 +21,7 @@ import torch
 
 KIND_UINT, KIND_INT, KIND_FLOAT = 0, 1, 2
 _TORCH = {"f16": torch.float16, "bf16": torch.bfloat16}
+E8M0_LO, E8M0_HI = 119, 130      # block-scale exponents drawn for "e8m0" scales: 2^-8 .. 2^3
 
 
 @dataclass(frozen=True)
@@ -66,7 +67,8 @@ def make_inputs(case: Case):
     codes  numpy uint8 [K, N], the raw `bits`-bit patterns, uniform over the
            finite encodings (for intk: two's-complement patterns, i.e. values
            uniform over [-2^(k-1), 2^(k-1)-1])
-    scales torch CPU tensor [K/group, N] of case.scale_dtype, U(lo, hi)
+    scales torch CPU tensor [K/group, N] of case.scale_dtype, U(lo, hi) -- for scale_dtype "e8m0"
+           a uint8 tensor of exponents (the scale is 2^(e - 127))
     zeros  numpy uint8 [K/group, N] filled with case.zero -- or, for zero == "random",
            drawn uniformly from 0 .. zero_hi per (group, column) -- or None
     """
@@ -83,8 +85,11 @@ def make_inputs(case: Case):
     else:
         codes = rng.integers(0, 1 << case.bits, size=(case.K, case.N), dtype=np.uint8)
     G = case.K // case.group
-    s = rng.uniform(case.scale_lo, case.scale_hi, size=(G, case.N)).astype(np.float32)
-    scales = torch.from_numpy(s).to(_TORCH[case.scale_dtype])
+    if case.scale_dtype == "e8m0":      # 8-bit exponents e (scale 2^(e - 127)), uniform over E8M0_LO .. E8M0_HI
+        scales = torch.from_numpy(rng.integers(E8M0_LO, E8M0_HI + 1, size=(G, case.N), dtype=np.uint8))
+    else:
+        s = rng.uniform(case.scale_lo, case.scale_hi, size=(G, case.N)).astype(np.float32)
+        scales = torch.from_numpy(s).to(_TORCH[case.scale_dtype])
     if case.zero is None:
         zeros = None
     elif case.zero == "random":
