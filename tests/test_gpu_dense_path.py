@@ -87,6 +87,23 @@ def test_dense_path_one_hot_rows_bit_exact(act):
     assert np.array_equal(bits_of(P.gpu_c()), wbits)
 
 
+def test_dense_path_prefill_configuration_full_size():
+    # cfg5 u6 at M = 1024 (whole rounds of 256-row tiles + the second launch): sampled columns for all rows
+    import torch as _t
+    from oracle import qgemm_oracle as O
+    from paper_2504_12984_amd import binding as B
+    from gpu_util import to_f64
+    case = WL.cfg5(6, 1024)
+    P = Prepared(case)
+    cols = np.unique(np.concatenate([np.arange(4), np.arange(case.N - 4, case.N),
+                                     np.random.default_rng(3).integers(0, case.N, size=64)]))
+    B.qg_set_knob(0, 4)
+    C = P.gpu_c()
+    assert_c_close(C[:, _t.from_numpy(cols).cuda()], P.oracle_c(cols=cols), case.name + " de-quantise first")
+    B.qg_set_knob(0, 0)
+    assert np.array_equal(bits_of(C), bits_of(P.gpu_c())), "same tiles, same rounded weights: same bits as the fused kernel"
+
+
 def test_dense_path_buffer_grows_and_is_reused_across_weights_of_different_size():
     # small weight, larger weight (the buffer is replaced), small again; different inputs each time
     from paper_2504_12984_amd import binding as B
