@@ -129,6 +129,20 @@ def test_signed_sweep_shape_full_size(bits):
     assert_c_close(C, P.ref(), case.name + " all columns")
 
 
+@pytest.mark.parametrize("act,sdt", [("f16", "bf16"), ("bf16", "f16"), ("f16", "f16"), ("bf16", "bf16")])
+@pytest.mark.parametrize("M,K,N", [(1, 128, 64), (64, 128, 64), (3, 256, 128), (0, 128, 64)])
+def test_smallest_shapes_and_every_output_scale_type_pair(M, K, N, act, sdt):
+    # one chunk, one strip; the output type and the scale type are independent of each other
+    case = _case(f"a8_tiny_{M}_{K}_{N}_{act}_{sdt}", max(M, 1), K, N, U, 4, 64, act=act, sdt=sdt, seed=40600 + K + N)
+    P = A8Case(case)
+    if M == 0:
+        A0 = torch.empty((0, K), dtype=torch.int8, device="cuda")
+        out = P.B.qgemm_a8(A0, None, P.d_packed, P.d_scales, P.d_zeros, P.wtype, 64, N, out_dtype=ACT[act])
+        assert out.shape == (0, N)
+        return
+    assert_c_close(P.gpu(), P.ref(), case.name)
+
+
 def test_argument_errors():
     from paper_2504_12984_amd import binding as B
     P = A8Case(_case("a8_err", 4, 128, 64, U, 4, 128, seed=40500))

@@ -148,6 +148,15 @@ def test_block_scaled_decode_shape_full_size(bits, e, m):
     assert_c_close(C, P.oracle_c(), case.name + " all columns")
 
 
+@pytest.mark.parametrize("M,K,N", [(1, 128, 64), (64, 128, 64), (7, 256, 128)])
+def test_block_scaled_smallest_shapes(M, K, N):
+    case = _case(f"mx_tiny_{M}_{K}_{N}", M, K, N, 4, 2, 1, "f16", 50600 + K + N)
+    P = MxCase(case)
+    _, wbits = P.oracle_w()
+    assert np.array_equal(bits_of(P.gpu_w()), wbits)
+    assert_c_close(P.gpu_c(), P.oracle_c(), case.name)
+
+
 def test_block_scales_argument_errors():
     from paper_2504_12984_amd import binding as B
     P = MxCase(_case("mx_err", 4, 128, 64, 4, 2, 1, "f16", 50500))
