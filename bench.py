@@ -92,7 +92,7 @@ def cases_for(name):
         rest = name[4:]
         bits, m = rest.split("_M") if "_M" in rest else (rest, "16")
         return [WL.shrink(WL.cfg3(int(bits)), M=int(m), a8=True, name=name)]
-    if name.startswith("mx_f") or name.startswith("mxsweep_f"):     # block-scaled e2m1 / e4m3: mx_f4_M1 (K = N = 8192), mxsweep_f8_M16 (N = 57344)
+    if name.startswith("mx_f") or name.startswith("mxsweep_f"):     # block-scaled e2m1 / e4m3: mx_f4_M1 (K = N = 8192), mxsweep_f8_M16 / _M4096 (N = 57344)
         big = name.startswith("mxsweep")
         bits, m = name.split("_f")[1].split("_M")
         e, mm = {4: (2, 1), 8: (4, 3)}[int(bits)]

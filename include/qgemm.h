@@ -134,8 +134,9 @@ QG_API int repack(const void* canonical, qg_wtype t, int layout, int64_t K, int6
  *          zero-points, the float types e2m1 and e4m3 (the 4- and 8-bit microscaling element
  *          types) and QG_LAYOUT_TILE128x64; anything else with QG_E8M0 is QG_EUNSUPPORTED.
  *          The hardware's scaled converts apply the scale, so a de-quantised pair of codes
- *          costs one instruction; qgemm runs such weights through the streaming kernel (rows
- *          beyond 64 in blocks of 64: there is no tiled kernel for them yet)
+ *          costs one instruction; qgemm runs such weights through the streaming and the tiled
+ *          kernel of that layout like any other (only the de-quantise-first experiment path has
+ *          no variant for them)
  *   zeros  [K/group, N] row-major uint8, or NULL for zero-point 0
  *   group  rows of W per scale, dividing K: 32, 64, 128 * 2^s, or K itself (= one scale per
  *          output column; 0 means the same).  128 * odd (other than K) is a valid group

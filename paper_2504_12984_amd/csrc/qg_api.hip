@@ -527,10 +527,8 @@ static int qgemm_run(const void* A, const void* packed_W, const void* scales, co
     return kLarge32[wt](p, route, knob(2), st);
   }
 
-  int path = plan_path(M, N, K, t);
-  if (p.scale_e8m0) {                                // block-scaled weights: the streaming kernel, rows in blocks of 64
-    if (path == 2 || path == 4) { if (knob(0)) return QG_EUNSUPPORTED; path = (M > 64) ? 3 : 1; }
-  }
+  const int path = plan_path(M, N, K, t);
+  if (p.scale_e8m0 && path == 4) return QG_EUNSUPPORTED;      // the de-quantise-first path has no block-scaled variant
   if (path == 1 && M > 64) return QG_EINVAL;
   if (path < 1 || path > 4) return QG_EINVAL;
 
@@ -698,10 +696,7 @@ int qg_plan(qg_wtype t, int layout, int act, int scale_dtype, int64_t group, int
     return (group == 32 || !tiled_operands_fit(M, N, K, group, t.bits)) ? QG_EUNSUPPORTED : QG_OK;
   }
   plan[0] = plan_path(M, N, K, t);
-  if (scale_dtype == QG_E8M0 && (plan[0] == 2 || plan[0] == 4)) {      // block-scaled weights: the streaming kernel only
-    if (knob(0)) return QG_EUNSUPPORTED;
-    plan[0] = (M > 64) ? 3 : 1;
-  }
+  if (scale_dtype == QG_E8M0 && plan[0] == 4) return QG_EUNSUPPORTED;   // the de-quantise-first path has no block-scaled variant
   if (plan[0] == 1 && M > 64) return QG_EINVAL;
   if (plan[0] == 1 || plan[0] == 3) {
     plan_streaming((int)(M < 64 ? M : 64), (int)N, (int)K, (int)group, wt, &plan[1], &plan[3], &plan[4], scale_dtype == QG_E8M0);

@@ -180,6 +180,7 @@ struct Decoder<WT, ROUTE_F16, LY> {
   static constexpr int WN = Lay<BITS>::WN;
   static constexpr int RAW = 4 * BITS;
   static constexpr bool HAS_META = true;           // scales / zero-points are loaded with every chunk
+  static constexpr bool IS_MX = false;
 
   struct Consts {
     h2_t s[NTL];
@@ -296,6 +297,7 @@ struct Decoder<WT, ROUTE_BF16, LY> {
   static constexpr int WN = Lay<BITS>::WN;
   static constexpr int RAW = 4 * BITS;
   static constexpr bool HAS_META = true;           // scales / zero-points are loaded with every chunk
+  static constexpr bool IS_MX = false;
 
   struct Consts {
     float s[NTL];     // integers: scale; floats: scale * 2^(15-bias)
@@ -410,6 +412,7 @@ template <int ROUTE>
 struct DenseDecoder {
   static constexpr int NTL = 4, BITS = 16, RAW = 64;
   static constexpr bool HAS_META = false;
+  static constexpr bool IS_MX = false;
   struct Consts {};
   struct Uniform { __device__ __forceinline__ void init() {} };
   typedef uint32_t Mid;
@@ -426,9 +429,53 @@ struct DenseDecoder {
   }
 };
 
+// Block-scaled e2m1 / e4m3 in the three-phase form the tiled kernel deals out over its gaps:
+// "extract" picks the register that holds the pair, "centre" is the one scaled hardware convert,
+// "round" has nothing left to do.  The lane's four scale bytes of a 32-row block travel in the
+// zero-point slot of the weight stage.
 template <int WT, int ROUTE>
+struct MxDecoder {
+  static constexpr int NTL = 4, BITS = wt_bits(WT), RAW = 4 * BITS;
+  static constexpr bool HAS_META = true;
+  static constexpr bool IS_MX = true;
+  static_assert(WT == 9 || WT == 13, "block-scaled converts exist for e2m1 and e4m3");
+  struct Consts { float s[4]; };
+  struct Uniform { __device__ __forceinline__ void init() {} };
+  typedef uint32_t Mid;
+  static __device__ __forceinline__ void make_col(Consts& gc, int nt, uint2, uint32_t s4, int, int) {
+    gc.s[nt] = __builtin_bit_cast(float, ((s4 >> (8 * nt)) & 0xffu) << 23);
+  }
+  template <int T>
+  static __device__ __forceinline__ uint32_t pair_e(const uint32_t (&r)[RAW], const Uniform&) { return r[WT == 13 ? T / 2 : T / 4]; }
+  template <int T>
+  static __device__ __forceinline__ Mid pair_s(uint32_t x, const Consts& gc, int nt) {
+    constexpr int OUT_BF16 = (ROUTE == ROUTE_BF16);
+    if constexpr (WT == 13) {
+      if constexpr (OUT_BF16) return __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(x, gc.s[nt], (T % 2) == 1));
+      else                    return __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(x, gc.s[nt], (T % 2) == 1));
+    } else {
+      if constexpr (OUT_BF16) return __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(x, gc.s[nt], T % 4));
+      else                    return __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(x, gc.s[nt], T % 4));
+    }
+  }
+  static __device__ __forceinline__ uint32_t pair_p(Mid m, const Consts&, int) { return m; }
+  template <int J, int NT>
+  static __device__ __forceinline__ void frag(const uint32_t (&r)[RAW], const Consts& gc, const Uniform& u, uint32_t (&out)[4]) {
+    constexpr int T0 = LayoutOf<0>::t0(J, NT);
+    out[0] = pair_s<T0 + 0>(pair_e<T0 + 0>(r, u), gc, NT);
+    out[1] = pair_s<T0 + 1>(pair_e<T0 + 1>(r, u), gc, NT);
+    out[2] = pair_s<T0 + 2>(pair_e<T0 + 2>(r, u), gc, NT);
+    out[3] = pair_s<T0 + 3>(pair_e<T0 + 3>(r, u), gc, NT);
+  }
+};
+
+template <int WT, int ROUTE, bool MX = false>
 struct DecoderFor { typedef Decoder<WT, ROUTE, 0> type; };
 template <int ROUTE>
-struct DecoderFor<WT_DENSE16, ROUTE> { typedef DenseDecoder<ROUTE> type; };
+struct DecoderFor<WT_DENSE16, ROUTE, false> { typedef DenseDecoder<ROUTE> type; };
+template <int ROUTE>
+struct DecoderFor<9, ROUTE, true> { typedef MxDecoder<9, ROUTE> type; };
+template <int ROUTE>
+struct DecoderFor<13, ROUTE, true> { typedef MxDecoder<13, ROUTE> type; };
 
 }  // namespace qg

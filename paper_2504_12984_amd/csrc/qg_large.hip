@@ -70,11 +70,13 @@ struct LargeLds {
   static constexpr int BUF = 4 * SLICE;
 };
 
-template <int WT, int ROUTE, int GPC, int BM>
+template <int WT, int ROUTE, int GPC, int BM, bool MX = false>
 __global__ __launch_bounds__(256) void large_kernel(GemmParams p, int tiles_m, int tiles_n, int per_xcd, int tn0) {
   // GPC = groups per 128-row chunk: 1 (group size 128 or more), 2 (64) or 4 (32)
+  // MX: power-of-two block scales (8-bit exponents, one per 32 rows: GPC = 4) on e2m1 / e4m3 codes
   constexpr bool TWO_GROUPS = (GPC == 2), FOUR_GROUPS = (GPC == 4);
-  typedef typename DecoderFor<WT, ROUTE>::type D;      // WT_DENSE16: weights already de-quantised, pass-through
+  static_assert(!MX || GPC == 4, "block scales: one per 32 rows");
+  typedef typename DecoderFor<WT, ROUTE, MX>::type D;  // WT_DENSE16: weights already de-quantised, pass-through
   constexpr int BITS = D::BITS, RAW = D::RAW;
   constexpr int MTS = BM / 16;                 // 16-row MFMA tiles per workgroup
   constexpr int PIECES = BM * 4 / 256;         // 16-byte pieces per thread per slice
@@ -158,7 +160,7 @@ __global__ __launch_bounds__(256) void large_kernel(GemmParams p, int tiles_m, i
   const __amdgpu_buffer_rsrc_t w_rsrc = __builtin_amdgcn_make_buffer_rsrc(
       const_cast<uint8_t*>(p.W), 0, (int)(uint32_t)((int64_t)p.K * p.N / 8 * BITS), 0x00020000);
   const __amdgpu_buffer_rsrc_t s_rsrc = __builtin_amdgcn_make_buffer_rsrc(
-      const_cast<uint16_t*>(p.S), 0, (int)(uint32_t)((int64_t)(p.K / p.group) * p.N * 2), 0x00020000);
+      const_cast<uint16_t*>(p.S), 0, (int)(uint32_t)((int64_t)(p.K / p.group) * p.N * (D::IS_MX ? 1 : 2)), 0x00020000);
   const __amdgpu_buffer_rsrc_t z_rsrc = __builtin_amdgcn_make_buffer_rsrc(
       const_cast<uint8_t*>(zbase), 0, (int)(uint32_t)((int64_t)(p.K / p.group) * p.N), 0x00020000);
   const int w_lane = 16 * l, s_lane = 2 * n0, z_lane = n0;
@@ -166,7 +168,7 @@ __global__ __launch_bounds__(256) void large_kernel(GemmParams p, int tiles_m, i
   // The loads of one chunk are 2 (4 with two groups per chunk) + BITS separate pieces,
   // so that the main loop can issue them a few at a time in different gaps between
   // matrix instructions.  Pieces: s0, z0, (s1, z1, (s2, z2, s3, z3,)) then BITS x 16 bytes of codes.
-  constexpr int WMETA = D::HAS_META ? 2 * GPC : 0;
+  constexpr int WMETA = !D::HAS_META ? 0 : (D::IS_MX ? GPC : 2 * GPC);      // block scales: one 4-byte load per group
   constexpr int WPIECES = WMETA + BITS;
   auto w_piece = [&](WStage& s, int c, auto Ic) __attribute__((always_inline)) {
     constexpr int I = decltype(Ic)::value;
@@ -178,14 +180,22 @@ __global__ __launch_bounds__(256) void large_kernel(GemmParams p, int tiles_m, i
     } else {
       const int g0 = (GPC > 1) ? GPC * c : ((c >> p.gshift) & p.gmask);
       typedef uint32_t u2_t __attribute__((ext_vector_type(2)));
-      if constexpr (I == 0) { const u2_t v = __builtin_amdgcn_raw_buffer_load_b64(s_rsrc, s_lane, g0 * p.N * 2, 0); s.s0 = make_uint2(v.x, v.y); }
-      if constexpr (I == 1) s.z0 = __builtin_amdgcn_raw_buffer_load_b32(z_rsrc, z_lane, g0 * p.N, 0);
-      if constexpr (I == 2) { const u2_t v = __builtin_amdgcn_raw_buffer_load_b64(s_rsrc, s_lane, (g0 + 1) * p.N * 2, 0); s.s1 = make_uint2(v.x, v.y); }
-      if constexpr (I == 3) s.z1 = __builtin_amdgcn_raw_buffer_load_b32(z_rsrc, z_lane, (g0 + 1) * p.N, 0);
-      if constexpr (I == 4) { const u2_t v = __builtin_amdgcn_raw_buffer_load_b64(s_rsrc, s_lane, (g0 + 2) * p.N * 2, 0); s.s2 = make_uint2(v.x, v.y); }
-      if constexpr (I == 5) s.z2 = __builtin_amdgcn_raw_buffer_load_b32(z_rsrc, z_lane, (g0 + 2) * p.N, 0);
-      if constexpr (I == 6) { const u2_t v = __builtin_amdgcn_raw_buffer_load_b64(s_rsrc, s_lane, (g0 + 3) * p.N * 2, 0); s.s3 = make_uint2(v.x, v.y); }
-      if constexpr (I == 7) s.z3 = __builtin_amdgcn_raw_buffer_load_b32(z_rsrc, z_lane, (g0 + 3) * p.N, 0);
+      if constexpr (D::IS_MX) {        // the lane's four scale bytes of group I, kept in the zero-point slot
+        const uint32_t v = __builtin_amdgcn_raw_buffer_load_b32(s_rsrc, z_lane, (g0 + I) * p.N, 0);
+        if constexpr (I == 0) s.z0 = v;
+        if constexpr (I == 1) s.z1 = v;
+        if constexpr (I == 2) s.z2 = v;
+        if constexpr (I == 3) s.z3 = v;
+      } else {
+        if constexpr (I == 0) { const u2_t v = __builtin_amdgcn_raw_buffer_load_b64(s_rsrc, s_lane, g0 * p.N * 2, 0); s.s0 = make_uint2(v.x, v.y); }
+        if constexpr (I == 1) s.z0 = __builtin_amdgcn_raw_buffer_load_b32(z_rsrc, z_lane, g0 * p.N, 0);
+        if constexpr (I == 2) { const u2_t v = __builtin_amdgcn_raw_buffer_load_b64(s_rsrc, s_lane, (g0 + 1) * p.N * 2, 0); s.s1 = make_uint2(v.x, v.y); }
+        if constexpr (I == 3) s.z1 = __builtin_amdgcn_raw_buffer_load_b32(z_rsrc, z_lane, (g0 + 1) * p.N, 0);
+        if constexpr (I == 4) { const u2_t v = __builtin_amdgcn_raw_buffer_load_b64(s_rsrc, s_lane, (g0 + 2) * p.N * 2, 0); s.s2 = make_uint2(v.x, v.y); }
+        if constexpr (I == 5) s.z2 = __builtin_amdgcn_raw_buffer_load_b32(z_rsrc, z_lane, (g0 + 2) * p.N, 0);
+        if constexpr (I == 6) { const u2_t v = __builtin_amdgcn_raw_buffer_load_b64(s_rsrc, s_lane, (g0 + 3) * p.N * 2, 0); s.s3 = make_uint2(v.x, v.y); }
+        if constexpr (I == 7) s.z3 = __builtin_amdgcn_raw_buffer_load_b32(z_rsrc, z_lane, (g0 + 3) * p.N, 0);
+      }
     }
   };
   auto w_issue = [&](WStage& s, int c) __attribute__((always_inline)) {
@@ -195,10 +205,11 @@ __global__ __launch_bounds__(256) void large_kernel(GemmParams p, int tiles_m, i
   auto consts_col = [&](typename D::Consts& g, const WStage& s, auto Gc, int nt) __attribute__((always_inline)) {
     constexpr int G = decltype(Gc)::value;
     if constexpr (!D::HAS_META) return;
-    if constexpr (G == 0) D::make_col(g, nt, s.s0, s.z0 & zmask, p.zbias, p.scale_bf16);
-    if constexpr (G == 1) D::make_col(g, nt, s.s1, s.z1 & zmask, p.zbias, p.scale_bf16);
-    if constexpr (G == 2) D::make_col(g, nt, s.s2, s.z2 & zmask, p.zbias, p.scale_bf16);
-    if constexpr (G == 3) D::make_col(g, nt, s.s3, s.z3 & zmask, p.zbias, p.scale_bf16);
+    const uint32_t zm = D::IS_MX ? 0xffffffffu : zmask;          // block scales travel in the zero-point slot: never masked
+    if constexpr (G == 0) D::make_col(g, nt, s.s0, s.z0 & zm, p.zbias, p.scale_bf16);
+    if constexpr (G == 1) D::make_col(g, nt, s.s1, s.z1 & zm, p.zbias, p.scale_bf16);
+    if constexpr (G == 2) D::make_col(g, nt, s.s2, s.z2 & zm, p.zbias, p.scale_bf16);
+    if constexpr (G == 3) D::make_col(g, nt, s.s3, s.z3 & zm, p.zbias, p.scale_bf16);
   };
 
   // Accumulators live in the accumulation registers (AGPRs) for the whole
@@ -514,14 +525,14 @@ __global__ __launch_bounds__(256) void large_kernel(GemmParams p, int tiles_m, i
 #define QG_CAT(a, b) QG_CAT2(a, b)
 
 // One launch over the column tiles [tn0, tn0 + tiles_n) and all row tiles of height BM.
-template <int ROUTE, int GPC, int BM>
+template <int ROUTE, int GPC, int BM, bool MX = false>
 static int launch_bm(const GemmParams& p, hipStream_t st, int tn0, int tiles_n) {
   const int tiles_m = (p.M + BM - 1) / BM;
   if (p.splitk > 1 && BM > 128) return QG_EINVAL;
   const int total = tiles_m * tiles_n * p.splitk;
   const int per_xcd = (total + 7) / 8;
   const size_t lds_bytes = 2 * LargeLds<BM>::BUF;
-  auto kern = large_kernel<QG_WT, ROUTE, GPC, BM>;
+  auto kern = large_kernel<QG_WT, ROUTE, GPC, BM, MX>;
   // raise the dynamic LDS limit once per instantiation and device
   static bool attr_done[64] = {};
   int dev = 0;
@@ -539,6 +550,17 @@ static int launch_bm(const GemmParams& p, hipStream_t st, int tn0, int tiles_n) 
 template <int ROUTE>
 static int launch_rows(const GemmParams& p, int bm, hipStream_t st, int tn0, int tiles_n) {
   const int gpc = (p.group == 32) ? 4 : (p.group == 64) ? 2 : 1;       // groups per 128-row chunk
+  if (p.scale_e8m0) {
+#if QG_WT == 9 || QG_WT == 13
+    if (gpc != 4) return QG_EUNSUPPORTED;
+    if (bm == 64) return launch_bm<ROUTE, 4, 64, true>(p, st, tn0, tiles_n);
+    if (bm == 128) return launch_bm<ROUTE, 4, 128, true>(p, st, tn0, tiles_n);
+    if (bm == 256) return launch_bm<ROUTE, 4, 256, true>(p, st, tn0, tiles_n);
+    return QG_EINVAL;
+#else
+    return QG_EUNSUPPORTED;
+#endif
+  }
 #define QG_ROWS(BM_)                                                              \
   if (bm == BM_)                                                                  \
     return gpc == 4 ? launch_bm<ROUTE, 4, BM_>(p, st, tn0, tiles_n)               \

@@ -87,8 +87,16 @@ def test_block_scaled_matmul_every_row_count(bits, e, m, M):
     case = _case(f"mx_c_{bits}_{M}", M, 1408, 320, bits, e, m, "bf16" if M % 2 else "f16", 50100 + bits + M)
     P = MxCase(case)
     plan = P.B.qg_plan(P.wtype, 32, M, case.N, case.K, act=P.B.QG_F16, scale_dtype=P.B.QG_E8M0)
-    assert plan["path"] == (1 if M <= 64 else 3), plan
-    assert_c_close(P.gpu_c(), P.oracle_c(), case.name)
+    assert plan["path"] == (1 if M <= 64 else 2), plan
+    ref = P.oracle_c()
+    assert_c_close(P.gpu_c(), ref, case.name)
+    P.B.qg_set_knob(0, 2)                          # the tiled kernel at every tile height, also below its usual range
+    for bm in (64, 128, 256):
+        P.B.qg_set_knob(2, bm)
+        assert_c_close(P.gpu_c(), ref, f"{case.name} tiled {bm}")
+    P.B.qg_set_knob(2, 0)
+    P.B.qg_set_knob(0, 3)                          # and the streaming kernel over blocks of 64 rows
+    assert_c_close(P.gpu_c(), ref, case.name + " row blocks")
 
 
 @pytest.mark.parametrize("variant", [10, 11, 12, 14, 15, 16])
@@ -157,6 +165,41 @@ def test_block_scaled_smallest_shapes(M, K, N):
     assert_c_close(P.gpu_c(), P.oracle_c(), case.name)
 
 
+@pytest.mark.parametrize("act", ["f16", "bf16"])
+@pytest.mark.parametrize("bits,e,m", TYPES)
+def test_block_scaled_tiled_kernel_ragged_shapes_split_k_and_one_hot(bits, e, m, act):
+    from paper_2504_12984_amd import binding as B
+    # 7 chunks (odd: the padding chunk), 3 strips (an idle wavefront), rows past M; then K in two slabs
+    case = _case(f"mx_tiled_{bits}_{act}", 300, 896, 192, bits, e, m, act, 50700 + bits)
+    P = MxCase(case)
+    ref = P.oracle_c()
+    assert_c_close(P.gpu_c(), ref, case.name)
+    B.qg_set_knob(0, 2); B.qg_set_knob(2, 64); B.qg_set_knob(1, 2)
+    assert_c_close(P.gpu_c(), ref, case.name + " split")
+    B.qg_set_knob(1, 0); B.qg_set_knob(2, 0)
+    # one-hot rows through the tiled kernel: the de-quantised weight itself (a lone -0 sums to +0)
+    K, N = 256, 128
+    c2 = _case(f"mx_tiled_onehot_{bits}_{act}", K, K, N, bits, e, m, act, 50710 + bits)
+    inp = WL.make_inputs(c2)
+    A = torch.zeros((K, K), dtype=inp["A"].dtype)
+    A[torch.arange(K), torch.arange(K)] = 1.0
+    inp["A"] = A
+    P2 = MxCase(c2, inp)
+    _, wbits = P2.oracle_w()
+    want = wbits.copy()
+    want[want == 0x8000] = 0
+    assert np.array_equal(bits_of(P2.gpu_c()), want)
+
+
+def test_block_scaled_prefill_shape_full_size():
+    # K = 8192, N = 57344 (the prefill shape), e2m1 with block scales, M = 1024: sampled columns for all rows
+    case = _case("mx_prefill_f4", 1024, 8192, 57344, 4, 2, 1, "bf16", 50800)
+    P = MxCase(case)
+    C = P.gpu_c()
+    cols = np.unique(np.concatenate([np.arange(4), np.arange(57340, 57344), np.random.default_rng(4).integers(0, 57344, 64)]))
+    assert_c_close(C[:, torch.from_numpy(cols).cuda()], P.oracle_c(cols=cols), case.name)
+
+
 def test_block_scales_argument_errors():
     from paper_2504_12984_amd import binding as B
     P = MxCase(_case("mx_err", 4, 128, 64, 4, 2, 1, "f16", 50500))
@@ -173,7 +216,7 @@ def test_block_scales_argument_errors():
     with pytest.raises(B.QgError) as err:          # no zero-points with block scales
         B.qgemm(P.d_A, P.d_packed, s, torch.zeros((4, 64), dtype=torch.uint8, device="cuda"), P.wtype, 32, 64)
     assert err.value.status == B.QG_EINVAL
-    B.qg_set_knob(0, 2)                            # the tiled kernel has no block-scaled variant
+    B.qg_set_knob(0, 4)                            # the de-quantise-first path has no block-scaled variant
     with pytest.raises(B.QgError) as err:
         P.gpu_c()
     assert err.value.status == B.QG_EUNSUPPORTED

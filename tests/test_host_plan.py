@@ -189,17 +189,17 @@ def test_batch_size_axis_of_the_paper():
 def test_block_scaled_weights_plan_and_refusals():
     F4, F8, F6 = B.WType(B.QG_FLOAT, 4, 2, 1), B.WType(B.QG_FLOAT, 8, 4, 3), B.WType(B.QG_FLOAT, 6, 3, 2)
     E8 = B.QG_E8M0
-    # streaming kernel at every M: up to 64 rows in one launch, beyond in blocks of 64; every arrangement is open to them
+    # streaming kernel (every arrangement is open to them) and tiled kernel like any other weight
     assert B.qg_plan(F4, 32, 1, 57344, 8192, act=B.QG_BF16, scale_dtype=E8)["variant"] == 16
     assert B.qg_plan(F8, 32, 16, 8192, 8192, act=B.QG_F16, scale_dtype=E8)["path"] == 1
-    assert B.qg_plan(F8, 32, 4096, 8192, 8192, act=B.QG_BF16, scale_dtype=E8)["path"] == 3
+    assert B.qg_plan(F8, 32, 4096, 8192, 8192, act=B.QG_BF16, scale_dtype=E8)["path"] == 2
     # the same weights with 16-bit scales and group 32 keep to the four-wavefront arrangements
     assert B.qg_plan(F4, 32, 1, 57344, 8192, act=B.QG_BF16, scale_dtype=B.QG_F16)["variant"] == 11
     for t, group, layout in ((F6, 32, 0), (U4, 32, 0), (F4, 128, 0), (F4, 32, 1)):
         with pytest.raises(B.QgError) as e:
             B.qg_plan(t, group, 16, 8192, 8192, act=B.QG_BF16, scale_dtype=E8, layout=layout)
         assert e.value.status == B.QG_EUNSUPPORTED, (t, group, layout)
-    B.qg_set_knob(0, 2)
+    B.qg_set_knob(0, 4)
     with pytest.raises(B.QgError) as e:
         B.qg_plan(F4, 32, 16, 8192, 8192, act=B.QG_BF16, scale_dtype=E8)
     assert e.value.status == B.QG_EUNSUPPORTED
