@@ -34,12 +34,19 @@ What follows the paper and what is a reading of it
   integer, the weight scale multiplies that sum, a per-row fp32 activation scale multiplies
   the row (qgemm_int8).
 
+* Codebook quantisation (named in the closing section as something a lookup instruction
+  would add, with no formula): the reading used here is one table of 2^k half-precision
+  levels per weight matrix, w = table[code] * s[k // g, n], rounded once to the activation
+  type; no zero-point (codebook_exact, qgemm_codebook_from_stream).
+
 Parity pins (tests/test_oracle_*.py): hand-derived bit streams, numpy.packbits
 for 1-bit, nibble/byte identities for 4/8-bit, exact-rational evaluation of the
 float formats, torch's float8_e4m3fn table, numpy/torch half and bfloat16 casts,
 integer matmul for uint8 weights, one-hot rows, brute-force triple loops; for the int8
 leg: numpy int64 matmul, exact-rational triple loops, agreement with the 16-bit-activation
-contraction wherever that one is exact, the row-sum form of the zero-point.
+contraction wherever that one is exact, the row-sum form of the zero-point; for the codebook
+leg: tables that reproduce the integer and float types (value tables of uintk - z, e2m1,
+e4m3), exact-rational loops, one-hot rows, permuted tables.
 The paper prints no numeric tensor example, so beyond those pins parity with
 the paper's own implementation is unpinned.
 """
@@ -326,6 +333,55 @@ def qgemm_int8_from_stream(A8, a_scale, stream, kind, bits, scales, zeros, group
         codes = unpack_elements(stream, bits, rows + cb[None, :])
         z = None if zeros is None else np.asarray(zeros)[:, cb]
         out[:, s0:s0 + cb.size] = qgemm_int8(A8, a_scale, codes, kind, bits, scales[:, cb], z, group)
+    return out
+
+
+# --------------------------------------------------------------------------
+# Codebook quantisation (the paper's closing section: codebook schemes such as
+# LCQ would be served by adding a lookup instruction)
+# --------------------------------------------------------------------------
+def codebook_exact(codes, table, scales, group):
+    """w = table[code] * s in fp64, unrounded.
+
+    The paper says only that a lookup instruction would accommodate codebook quantisation;
+    this is the reading used here.  A k-bit code is an index into ONE table of 2^k levels
+    per weight matrix (LCQ learns one companding function, hence one set of levels, per
+    layer); the levels are half-precision numbers whatever the activation type; the
+    group scale multiplies the level as it multiplies value(code) - z in the affine form;
+    there is no zero-point (a table can hold any offset).
+
+    codes  [K, N]  uint8 indices below len(table)
+    table  [2^k]   fp64 (half-precision levels widened exactly)
+    scales [K/group, N] fp64
+    """
+    codes = np.asarray(codes)
+    table = np.asarray(table, dtype=np.float64)
+    K, N = codes.shape
+    assert K % group == 0 and table.ndim == 1
+    assert int(codes.max(initial=0)) < table.size
+    gi = np.arange(K) // group
+    return table[codes] * np.asarray(scales, dtype=np.float64)[gi]
+
+
+def codebook_rounded(codes, table, scales, group, act):
+    """The rounded weights rne_act(table[code] * s) as fp64, plus their bit patterns."""
+    wr = round_rne(codebook_exact(codes, table, scales, group), act)
+    return wr, to_bits(wr, act)
+
+
+def qgemm_codebook_from_stream(A, stream, bits, table, scales, group, K, N, act, cols=None, col_block=1024):
+    """C = A . rne_act(table[code] * s) from the canonical byte stream, optionally on a
+    subset of output columns.  Returns fp64 [M, len(cols)]."""
+    A = np.asarray(A, dtype=np.float64)
+    cols = np.arange(N, dtype=np.int64) if cols is None else np.asarray(cols, dtype=np.int64)
+    scales = np.asarray(scales, dtype=np.float64)
+    out = np.empty((A.shape[0], cols.size), dtype=np.float64)
+    rows = np.arange(K, dtype=np.int64)[:, None] * N
+    for s0 in range(0, cols.size, col_block):
+        cb = cols[s0:s0 + col_block]
+        codes = unpack_elements(stream, bits, rows + cb[None, :])
+        wr, _ = codebook_rounded(codes, table, scales[:, cb], group, act)
+        out[:, s0:s0 + cb.size] = gemm_fp64(A, wr)
     return out
 
 
