@@ -66,12 +66,15 @@ extern "C" {
 #endif
 
 typedef enum { QG_OK = 0, QG_EINVAL = -1, QG_EUNSUPPORTED = -2, QG_EHIP = -3 } qg_status;
-typedef enum { QG_UINT = 0, QG_INT = 1, QG_FLOAT = 2 } qg_kind;
+typedef enum { QG_UINT = 0, QG_INT = 1, QG_FLOAT = 2, QG_CODEBOOK = 3 } qg_kind;
 typedef enum { QG_F16 = 0, QG_BF16 = 1, QG_E8M0 = 2 } qg_dtype;   /* activation / scale dtype; QG_E8M0: scales only */
 
 /* Weight type.  uint/int: bits in 1..8, ebits = mbits = 0.  float: 1 + ebits +
  * mbits == bits; supported splits are the paper's representative set
- * e1m1, e2m1, e2m2, e3m2, e3m3, e4m3 (Section "Arbitrary Data Type Support"). */
+ * e1m1, e2m1, e2m2, e3m2, e3m3, e4m3 (Section "Arbitrary Data Type Support").
+ * codebook: bits in 1..8, ebits = mbits = 0; a code is an index into a table of 2^bits levels
+ * that the *_codebook calls take (repack and qgemm_packed_bytes accept the kind, qdequant /
+ * qgemm / qgemm_a8 answer QG_EINVAL: they have no table). */
 typedef struct { int32_t kind, bits, ebits, mbits; } qg_wtype;
 
 /* Device layouts.  In all of them W is cut into tiles of 128 (K) x 64 (N) codes; a tile
@@ -204,6 +207,27 @@ QG_API int qgemm_a8(const int8_t* A8, const float* a_scale, const void* packed_W
              const uint8_t* zeros, qg_wtype t, int out_dtype, int scale_dtype, int64_t group,
              int64_t M, int64_t N, int64_t K, void* C, void* stream);
 
+/* Codebook quantisation.  The paper's related-work section says a lookup instruction would
+ * accommodate codebook schemes such as LCQ and gives no formula; this is the library's reading:
+ *     w[k,n] = rne_act( codebook[code[k,n]] * s[k/g, n] )
+ * one table of 2^bits levels per weight matrix, the group scale as in the affine form, no
+ * zero-point (a table holds any offset), one rounding to the activation type.
+ *   packed_W  repack(..., {QG_CODEBOOK, bits, 0, 0}, QG_LAYOUT_TILE128x64, ...) of the canonical
+ *             stream of codes, bits in 1..8
+ *   codebook  2^bits fp16 values (whatever `act` is), device, 2-byte aligned, read by every
+ *             workgroup at kernel start
+ *   scales / scale_dtype (QG_F16, or QG_BF16 with bf16 activations) / group / K, N / act as for
+ *   qdequant and qgemm
+ * The lookup is an LDS read from a table replicated over the 32 banks (up to 4 bits: one read
+ * returns the two levels of a pair of codes; above: one read per code).  qgemm_codebook serves
+ * any M >= 1 with the streaming kernel (rows in blocks of 64; no tiled kernel yet); workspace,
+ * stream and error conventions as for qgemm.  QG_EINVAL on a null table, bits outside 1..8 and
+ * on the shape / group violations of qgemm. */
+QG_API int qdequant_codebook(const void* packed_W, const void* codebook, const void* scales, int bits,
+                      int act, int scale_dtype, int64_t group, int64_t K, int64_t N, void* W_out, void* stream);
+QG_API int qgemm_codebook(const void* A, const void* packed_W, const void* codebook, const void* scales, int bits,
+                   int act, int scale_dtype, int64_t group, int64_t M, int64_t N, int64_t K, void* C, void* stream);
+
 /* What qgemm would launch for a shape: host arithmetic only, no GPU call, usable without
  * a device.  Arguments as for qgemm (M >= 1).  plan (host, 5 ints) receives
  *   [0] path: 1 = streaming kernel, 2 = tiled kernel, 3 = streaming kernel over blocks of 64 rows,
@@ -213,7 +237,7 @@ QG_API int qgemm_a8(const int8_t* A8, const float* a_scale, const void* packed_W
  *       tiles, then 128 or 256 rows for the rest (paths 2 and 4); 0 on paths 1 and 3
  *   [3] K-slabs (split-K factor; 1 = none)   [4] K-chunks of 128 per slab
  * The experiment overrides of qgemm_tuning.h apply as in qgemm.  Returns the status qgemm's
- * argument checks would return. */
+ * argument checks would return.  With t.kind == QG_CODEBOOK: what qgemm_codebook would launch. */
 QG_API int qg_plan(qg_wtype t, int layout, int act, int scale_dtype, int64_t group,
             int64_t M, int64_t N, int64_t K, int plan[5]);
 

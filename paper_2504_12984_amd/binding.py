@@ -18,7 +18,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("QGEMM_LIB") or os.path.join(_HERE, "libqgemm.so")
 
 QG_OK, QG_EINVAL, QG_EUNSUPPORTED, QG_EHIP = 0, -1, -2, -3
-QG_UINT, QG_INT, QG_FLOAT = 0, 1, 2
+QG_UINT, QG_INT, QG_FLOAT, QG_CODEBOOK = 0, 1, 2, 3
 QG_F16, QG_BF16, QG_E8M0 = 0, 1, 2
 QG_LAYOUT_TILE128x64 = 0
 QG_LAYOUT_TILE128x64_R32 = 1
@@ -26,7 +26,8 @@ QG_LAYOUT_TILE128x64_I8 = 2
 TILE_K, TILE_N = 128, 64
 
 EXPORTS = ("qg_status_string", "qg_last_error", "qg_canonical_bytes", "qgemm_packed_bytes",
-           "qg_pack_codes", "repack", "qdequant", "qgemm", "qgemm_noalloc", "qgemm_a8", "qg_set_knob", "qg_plan", "qg_probe_stream_read",
+           "qg_pack_codes", "repack", "qdequant", "qgemm", "qgemm_noalloc", "qgemm_a8", "qdequant_codebook", "qgemm_codebook",
+           "qg_set_knob", "qg_plan", "qg_probe_stream_read",
            "qg_probe_mfma")
 
 
@@ -82,6 +83,10 @@ def _load() -> ctypes.CDLL:
     lib.qgemm_noalloc.argtypes = lib.qgemm.argtypes
     lib.qgemm_a8.restype = i32
     lib.qgemm_a8.argtypes = [vp, vp, vp, vp, vp, QgWType, i32, i32, i64, i64, i64, i64, vp, vp]
+    lib.qdequant_codebook.restype = i32
+    lib.qdequant_codebook.argtypes = [vp, vp, vp, i32, i32, i32, i64, i64, i64, vp, vp]
+    lib.qgemm_codebook.restype = i32
+    lib.qgemm_codebook.argtypes = [vp, vp, vp, vp, i32, i32, i32, i64, i64, i64, i64, vp, vp]
     lib.qg_set_knob.restype = i32
     lib.qg_plan.argtypes = [QgWType, i32, i32, i32, i64, i64, i64, i64, ctypes.POINTER(ctypes.c_int32)]
     lib.qg_plan.restype = i32
@@ -278,6 +283,71 @@ class BoundQgemmA8:
         rc = _lib.qgemm_a8(*self._args)
         if rc != QG_OK:
             raise QgError("qgemm_a8", rc)
+        return self.out
+
+
+def _check_codebook(codebook: torch.Tensor, bits: int):
+    if not (1 <= bits <= 8):
+        raise ValueError("bits must be 1..8")
+    if codebook.dtype != torch.float16 or tuple(codebook.shape) != (1 << bits,):
+        raise ValueError("codebook must be fp16 [2^bits]")
+
+
+def qdequant_codebook(packed: torch.Tensor, codebook: torch.Tensor, scales: torch.Tensor, bits: int, act: torch.dtype,
+                      group: int, K: int, N: int) -> torch.Tensor:
+    """W_out[K,N] = rne_act(codebook[code] * scale); `packed` = repack of WType(QG_CODEBOOK, bits)."""
+    _check_codebook(codebook, bits)
+    out = torch.empty((K, N), dtype=act, device=packed.device)
+    rc = _lib.qdequant_codebook(_ptr(packed, "packed"), _ptr(codebook, "codebook"), _ptr(scales, "scales"), bits,
+                                _DT[act], _DT[scales.dtype], group, K, N, _ptr(out, "out"), _stream())
+    _check("qdequant_codebook", rc)
+    return out
+
+
+def qgemm_codebook(A: torch.Tensor, packed: torch.Tensor, codebook: torch.Tensor, scales: torch.Tensor, bits: int,
+                   group: int, N: int, out: torch.Tensor | None = None) -> torch.Tensor:
+    """C[M,N] = A[M,K] . rne_act(codebook[code] * scale); dtype of A is the activation dtype."""
+    if A.dim() != 2 or A.dtype not in _DT:
+        raise ValueError("A must be [M,K] fp16 or bf16")
+    _check_codebook(codebook, bits)
+    M, K = A.shape
+    rows = K // group if group > 0 else 1
+    if scales.dtype not in _DT or tuple(scales.shape) != (rows, N):
+        raise ValueError("scales must be [K/group, N] fp16 or bf16")
+    if out is None:
+        out = torch.empty((M, N), dtype=A.dtype, device=A.device)
+    rc = _lib.qgemm_codebook(_ptr(A, "A"), _ptr(packed, "packed"), _ptr(codebook, "codebook"), _ptr(scales, "scales"), bits,
+                             _DT[A.dtype], _DT[scales.dtype], group, M, N, K, _ptr(out, "C"), _stream())
+    _check("qgemm_codebook", rc)
+    return out
+
+
+class BoundQgemmCodebook:
+    """One qgemm_codebook call with its arguments checked and marshalled once (see BoundQgemm)."""
+
+    def __init__(self, A: torch.Tensor, packed: torch.Tensor, codebook: torch.Tensor, scales: torch.Tensor, bits: int,
+                 group: int, N: int, out: torch.Tensor, stream: int | None = None):
+        if A.dim() != 2 or A.dtype not in _DT:
+            raise ValueError("A must be [M,K] fp16 or bf16")
+        _check_codebook(codebook, bits)
+        M, K = A.shape
+        rows = K // group if group > 0 else 1
+        if scales.dtype not in _DT or tuple(scales.shape) != (rows, N):
+            raise ValueError("scales must be [K/group, N] fp16 or bf16")
+        if tuple(out.shape) != (M, N) or out.dtype != A.dtype:
+            raise ValueError("out must be [M,N] of A's dtype")
+        vp, i32, i64 = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64
+        self._keep = (A, packed, codebook, scales, out)
+        self.out = out
+        self._args = (vp(_ptr(A, "A")), vp(_ptr(packed, "packed")), vp(_ptr(codebook, "codebook")),
+                      vp(_ptr(scales, "scales")), i32(bits), i32(_DT[A.dtype]), i32(_DT[scales.dtype]),
+                      i64(group), i64(M), i64(N), i64(K), vp(_ptr(out, "C")),
+                      vp(_stream() if stream is None else stream))
+
+    def __call__(self) -> torch.Tensor:
+        rc = _lib.qgemm_codebook(*self._args)
+        if rc != QG_OK:
+            raise QgError("qgemm_codebook", rc)
         return self.out
 
 

@@ -24,12 +24,19 @@ int launch_repack(const uint8_t*, int, int, int, uint32_t, int, int, uint8_t*, h
 QG_FOR_ALL_WT(QG_DECL)
 #undef QG_DECL
 int large_launch_wt14(const GemmParams&, int, int, hipStream_t);
+// codebook indices of 1..8 bits: kernel-side weight types WT_LUT0 .. WT_LUT0 + 7
+#define QG_FOR_ALL_LUT(X) X(15) X(16) X(17) X(18) X(19) X(20) X(21) X(22)
+#define QG_DECL(i)                                                            \
+  int dequant_launch_wt##i(const DequantParams&, int, hipStream_t);           \
+  int decode_launch_wt##i(const GemmParams&, int, int, hipStream_t);
+QG_FOR_ALL_LUT(QG_DECL)
+#undef QG_DECL
 #define QG_DECL_A8(b) int a8_launch_bits##b(const A8Params&, int, int, hipStream_t);
 QG_DECL_A8(1) QG_DECL_A8(2) QG_DECL_A8(3) QG_DECL_A8(4) QG_DECL_A8(5) QG_DECL_A8(6) QG_DECL_A8(7) QG_DECL_A8(8)
 #undef QG_DECL_A8
 typedef int (*a8_fn)(const A8Params&, int, int, hipStream_t);
 static const a8_fn kA8[8] = {a8_launch_bits1, a8_launch_bits2, a8_launch_bits3, a8_launch_bits4,
-                             a8_launch_bits5, a8_launch_bits6, a8_launch_bits7, a8_launch_bits8};      // WT_DENSE16: weights already de-quantised
+                             a8_launch_bits5, a8_launch_bits6, a8_launch_bits7, a8_launch_bits8};
 
 typedef int (*dq_fn)(const DequantParams&, int, hipStream_t);
 typedef int (*gm_fn)(const GemmParams&, int, int, hipStream_t);
@@ -44,6 +51,12 @@ static const gm_fn kLarge32[NUM_WT] = {QG_FOR_ALL_WT(QG_ENT)};
 #undef QG_ENT
 #define QG_ENT(i) decode_launch_wt##i,
 static const gm_fn kDecode[NUM_WT] = {QG_FOR_ALL_WT(QG_ENT)};
+#undef QG_ENT
+#define QG_ENT(i) dequant_launch_wt##i,
+static const dq_fn kDequantLut[NUM_LUT] = {QG_FOR_ALL_LUT(QG_ENT)};
+#undef QG_ENT
+#define QG_ENT(i) decode_launch_wt##i,
+static const gm_fn kDecodeLut[NUM_LUT] = {QG_FOR_ALL_LUT(QG_ENT)};
 #undef QG_ENT
 typedef int (*waves_fn)(int);
 #define QG_ENT(i) decode_waves_wt##i,
@@ -204,12 +217,16 @@ static bool layout_ok(int layout) { return layout == QG_LAYOUT_TILE128x64 || lay
 static bool pack_layout_ok(int layout) { return layout_ok(layout) || layout == QG_LAYOUT_TILE128x64_I8; }
 static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
+// `codebook`: the call brought a table of levels (the *_codebook entry points); a codebook weight
+// type needs one and no other type takes one.
 static int check_common(qg_wtype t, int layout, int act, int scale_dtype, int64_t group, int64_t K, int64_t N,
-                        int* wt_out, int* route_out) {
+                        int* wt_out, int* route_out, bool codebook = false) {
   if (!layout_ok(layout)) return QG_EINVAL;
   int wt = wt_index(t);
   if (wt == -2) return QG_EUNSUPPORTED;
   if (wt < 0) return QG_EINVAL;
+  if (wt_is_lut(wt) != codebook) return QG_EINVAL;
+  if (codebook && (layout != QG_LAYOUT_TILE128x64 || scale_dtype == QG_E8M0)) return QG_EUNSUPPORTED;
   if (K <= 0 || N <= 0 || K % TILE_K || N % TILE_N || K > (1 << 24) || N > (1 << 24)) return QG_EINVAL;
   if (group <= 0 || K % group) return QG_EINVAL;
   if (!((group % TILE_K) == 0 || group == 64 || group == 32)) return QG_EINVAL;
@@ -273,7 +290,7 @@ static void plan_streaming(int M, int N, int K, int group, int wt, int* variant_
   if (variant == 11 && KC > 32 && NCH > 128 && NCH < 256) variant = wt_bits(wt) <= 6 ? 10 : (NCH % 2 == 0 ? 14 : 11);
   if (knob(3) > 0) variant = knob(3);
   if (group == 32 && !mx) variant = 10 * mt + 1;   // four groups per chunk: the 4-wavefront arrangements only
-  const int waves = kDecodeWaves[wt](variant);
+  const int waves = kDecodeWaves[wt_is_lut(wt) ? 0 : wt](variant);      // the same map for every type
   // Split K over workgroups only when the column strips alone cannot fill the
   // 256 CUs, and never below 4 chunks per wavefront (2 with 16 wavefronts per strip, or with a
   // short K on at most 128 strips: K = 4096, N = 4096 .. 8192 is 15-25 % shorter with 8
@@ -308,7 +325,7 @@ static int launch_streaming(GemmParams& p, int wt, int route, int ws_mode, hipSt
     int rc = acquire_ws(ws_mode, pbytes, (size_t)NCH, st, p);
     if (rc != QG_OK) return rc;
   }
-  return kDecode[wt](p, route, variant, st);
+  return wt_is_lut(wt) ? kDecodeLut[wt - WT_LUT0](p, route, variant, st) : kDecode[wt](p, route, variant, st);
 }
 
 // Tiled kernel of the first layout: row-tile height (0 = the kernel's own choice between
@@ -379,6 +396,7 @@ static void plan_tiled(int64_t M, int64_t N, int64_t K, qg_wtype t, int* bm_out,
 // over blocks of 64 rows (forced only)
 static int plan_path(int64_t M, int64_t N, int64_t K, qg_wtype t) {
   const int bits = t.bits;
+  if (t.kind == QG_CODEBOOK) return M > 64 ? 3 : 1;      // the lookup exists in the streaming kernel only
   if (knob(0)) return knob(0);
   if (M > 64) return 2;
   // 33 .. 64 rows: the streaming kernel (4 row tiles per wavefront) re-reads A from L2 for
@@ -430,6 +448,7 @@ size_t qg_canonical_bytes(int bits, int64_t count) {
 size_t qgemm_packed_bytes(qg_wtype t, int layout, int64_t K, int64_t N) {
   if (!pack_layout_ok(layout) || wt_index(t) == -1) return 0;
   if (layout == QG_LAYOUT_TILE128x64_I8 && t.kind == QG_FLOAT) return 0;
+  if (t.kind == QG_CODEBOOK && layout != QG_LAYOUT_TILE128x64) return 0;
   if (K <= 0 || N <= 0 || K % TILE_K || N % TILE_N) return 0;
   return (size_t)(K * N * t.bits / 8);
 }
@@ -446,6 +465,7 @@ int repack(const void* canonical, qg_wtype t, int layout, int64_t K, int64_t N, 
   int wt = wt_index(t);
   if (wt == -1) return QG_EINVAL;   // any float split can be re-laid out; only the type must be well formed
   if (layout == QG_LAYOUT_TILE128x64_I8 && t.kind == QG_FLOAT) return QG_EUNSUPPORTED;   // integer weights only
+  if (t.kind == QG_CODEBOOK && layout != QG_LAYOUT_TILE128x64) return QG_EUNSUPPORTED;   // the lookup kernels read the first layout
   if (!canonical || !packed_out || canonical == packed_out) return QG_EINVAL;
   if (K <= 0 || N <= 0 || K % TILE_K || N % TILE_N || K > (1 << 24) || N > (1 << 24)) return QG_EINVAL;
   if (!aligned16(packed_out)) return QG_EINVAL;
@@ -455,18 +475,21 @@ int repack(const void* canonical, qg_wtype t, int layout, int64_t K, int64_t N, 
                        static_cast<uint8_t*>(packed_out), static_cast<hipStream_t>(stream));
 }
 
-int qdequant(const void* packed_W, const void* scales, const uint8_t* zeros, qg_wtype t, int layout, int act,
-             int scale_dtype, int64_t group, int64_t K, int64_t N, void* W_out, void* stream) {
+static int qdequant_run(const void* packed_W, const void* scales, const uint8_t* zeros, const void* codebook, bool with_codebook,
+                        qg_wtype t, int layout, int act, int scale_dtype, int64_t group, int64_t K, int64_t N, void* W_out,
+                        void* stream) {
   if (group == 0) group = K;               // 0 = one scale per output column
   int wt, route;
-  int rc = check_common(t, layout, act, scale_dtype, group, K, N, &wt, &route);
+  int rc = check_common(t, layout, act, scale_dtype, group, K, N, &wt, &route, with_codebook);
   if (rc != QG_OK) return rc;
-  if (!packed_W || !scales || !W_out) return QG_EINVAL;
-  if (!aligned16(packed_W) || !aligned16(scales) || !aligned16(W_out) || (zeros && !aligned16(zeros))) return QG_EINVAL;
+  if (!packed_W || !scales || !W_out || (with_codebook && !codebook)) return QG_EINVAL;
+  if (!aligned16(packed_W) || !aligned16(scales) || !aligned16(W_out) || (zeros && !aligned16(zeros)) ||
+      (codebook && (reinterpret_cast<uintptr_t>(codebook) & 1u))) return QG_EINVAL;
   DequantParams p;
   p.W = static_cast<const uint8_t*>(packed_W);
   p.S = static_cast<const uint16_t*>(scales);
   p.Z = zeros;
+  p.T = static_cast<const uint16_t*>(codebook);
   p.out = static_cast<uint16_t*>(W_out);
   p.layout = layout;
   p.K = (int)K; p.N = (int)N; p.group = (int)group;
@@ -475,15 +498,27 @@ int qdequant(const void* packed_W, const void* scales, const uint8_t* zeros, qg_
   p.scale_e8m0 = (scale_dtype == QG_E8M0);
   if (p.scale_e8m0 && zeros) return QG_EINVAL;       // block scales come without zero-points
   p.frag_out = 0;
+  if (wt_is_lut(wt)) return kDequantLut[wt - WT_LUT0](p, route, static_cast<hipStream_t>(stream));
   return kDequant[wt](p, route, static_cast<hipStream_t>(stream));
+}
+
+int qdequant(const void* packed_W, const void* scales, const uint8_t* zeros, qg_wtype t, int layout, int act,
+             int scale_dtype, int64_t group, int64_t K, int64_t N, void* W_out, void* stream) {
+  return qdequant_run(packed_W, scales, zeros, nullptr, false, t, layout, act, scale_dtype, group, K, N, W_out, stream);
+}
+
+int qdequant_codebook(const void* packed_W, const void* codebook, const void* scales, int bits, int act, int scale_dtype,
+                      int64_t group, int64_t K, int64_t N, void* W_out, void* stream) {
+  const qg_wtype t = {QG_CODEBOOK, bits, 0, 0};
+  return qdequant_run(packed_W, scales, nullptr, codebook, true, t, QG_LAYOUT_TILE128x64, act, scale_dtype, group, K, N, W_out, stream);
 }
 
 static int qgemm_run(const void* A, const void* packed_W, const void* scales, const uint8_t* zeros, qg_wtype t, int layout,
                      int act, int scale_dtype, int64_t group, int64_t M, int64_t N, int64_t K, void* C, void* stream,
-                     int ws_mode) {
+                     int ws_mode, const void* codebook = nullptr, bool with_codebook = false) {
   if (group == 0) group = K;               // 0 = one scale per output column
   int wt, route;
-  int rc = check_common(t, layout, act, scale_dtype, group, K, N, &wt, &route);
+  int rc = check_common(t, layout, act, scale_dtype, group, K, N, &wt, &route, with_codebook);
   if (rc != QG_OK) return rc;
   if (M < 0 || M > (1 << 24)) return QG_EINVAL;
   if (ws_mode == WS_STATIC) {
@@ -496,8 +531,9 @@ static int qgemm_run(const void* A, const void* packed_W, const void* scales, co
     if (rc != QG_OK) return rc;
   }
   if (M == 0) return QG_OK;
-  if (!A || !packed_W || !scales || !C) return QG_EINVAL;
-  if (!aligned16(A) || !aligned16(packed_W) || !aligned16(scales) || !aligned16(C) || (zeros && !aligned16(zeros))) return QG_EINVAL;
+  if (!A || !packed_W || !scales || !C || (with_codebook && !codebook)) return QG_EINVAL;
+  if (!aligned16(A) || !aligned16(packed_W) || !aligned16(scales) || !aligned16(C) || (zeros && !aligned16(zeros)) ||
+      (codebook && (reinterpret_cast<uintptr_t>(codebook) & 1u))) return QG_EINVAL;
   hipStream_t st = static_cast<hipStream_t>(stream);
   // one handle value that names a different stream in every thread: the per-stream
   // workspaces (and the stream order the shared scratch relies on) cannot be keyed by it
@@ -508,6 +544,7 @@ static int qgemm_run(const void* A, const void* packed_W, const void* scales, co
   p.W = static_cast<const uint8_t*>(packed_W);
   p.S = static_cast<const uint16_t*>(scales);
   p.Z = zeros;
+  p.T = static_cast<const uint16_t*>(codebook);
   p.C = static_cast<uint16_t*>(C);
   p.ws = nullptr; p.tickets = nullptr;
   p.M = (int)M; p.N = (int)N; p.K = (int)K; p.group = (int)group;
@@ -600,6 +637,13 @@ int qgemm_noalloc(const void* A, const void* packed_W, const void* scales, const
   return qgemm_run(A, packed_W, scales, zeros, t, layout, act, scale_dtype, group, M, N, K, C, stream, WS_STATIC);
 }
 
+int qgemm_codebook(const void* A, const void* packed_W, const void* codebook, const void* scales, int bits, int act,
+                   int scale_dtype, int64_t group, int64_t M, int64_t N, int64_t K, void* C, void* stream) {
+  const qg_wtype t = {QG_CODEBOOK, bits, 0, 0};
+  return qgemm_run(A, packed_W, scales, nullptr, t, QG_LAYOUT_TILE128x64, act, scale_dtype, group, M, N, K, C, stream,
+                   WS_PER_STREAM, codebook, true);
+}
+
 // int8 activations: wavefronts per strip, row tiles and split-K of one block of at most 64 rows
 static void plan_a8(int M, int N, int K, int* waves_out, int* splitk_out, int* cps_out) {
   const int KC = K / TILE_K, NCH = N / TILE_N;
@@ -623,6 +667,7 @@ int qgemm_a8(const int8_t* A8, const float* a_scale, const void* packed_W, const
   if (group == 0) group = K;
   int wt = wt_index(t);
   if (wt == -1) return QG_EINVAL;
+  if (t.kind == QG_CODEBOOK) return QG_EINVAL;                    // no table in this call
   if (t.kind == QG_FLOAT) return QG_EUNSUPPORTED;                 // the integer instruction multiplies integers
   if (K <= 0 || N <= 0 || K % TILE_K || N % TILE_N || K > (1 << 24) || N > (1 << 24)) return QG_EINVAL;
   if (group <= 0 || K % group) return QG_EINVAL;
@@ -687,7 +732,7 @@ int qg_probe_mfma(int bf16, int random_data, int iters, int waves_per_simd, void
 int qg_plan(qg_wtype t, int layout, int act, int scale_dtype, int64_t group, int64_t M, int64_t N, int64_t K, int plan[5]) {
   if (group == 0) group = K;               // 0 = one scale per output column
   int wt, route;
-  int rc = check_common(t, layout, act, scale_dtype, group, K, N, &wt, &route);
+  int rc = check_common(t, layout, act, scale_dtype, group, K, N, &wt, &route, t.kind == QG_CODEBOOK);
   if (rc != QG_OK) return rc;
   if (M < 1 || M > (1 << 24) || !plan) return QG_EINVAL;
   plan[0] = plan[1] = plan[2] = 0; plan[3] = 1; plan[4] = (int)(K / TILE_K);

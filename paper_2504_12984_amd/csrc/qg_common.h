@@ -73,10 +73,17 @@ __host__ __device__ constexpr int pair_n(int layout, int l, int t) { return layo
 // 0..7   integer codes of 1..8 bits (uintk; intk is stored offset-binary and
 //        differs only by a constant added to the zero-point)
 // 8..13  floats e1m1, e2m1, e2m2, e3m2, e3m3, e4m3 (3..8 bits)
+// Kernel-side indices beyond the interface's weight types:
+// 14      16-bit weights already de-quantised (the tiled kernel's pass-through)
+// 15..22  codebook indices of 1..8 bits (table lookup through LDS)
 constexpr int NUM_WT = 14;
+constexpr int WT_DENSE16 = NUM_WT;
+constexpr int WT_LUT0 = NUM_WT + 1;
+constexpr int NUM_LUT = 8;
 
-__host__ __device__ constexpr int wt_bits(int wt) { return wt < 8 ? wt + 1 : wt - 8 + 3; }
-__host__ __device__ constexpr bool wt_is_float(int wt) { return wt >= 8; }
+__host__ __device__ constexpr bool wt_is_lut(int wt) { return wt >= WT_LUT0 && wt < WT_LUT0 + NUM_LUT; }
+__host__ __device__ constexpr int wt_bits(int wt) { return wt < 8 ? wt + 1 : wt < NUM_WT ? wt - 8 + 3 : wt == WT_DENSE16 ? 16 : wt - WT_LUT0 + 1; }
+__host__ __device__ constexpr bool wt_is_float(int wt) { return wt >= 8 && wt < NUM_WT; }
 __host__ __device__ constexpr int wt_ebits(int wt) {
   return wt == 8 ? 1 : wt == 9 ? 2 : wt == 10 ? 2 : wt == 11 ? 3 : wt == 12 ? 3 : wt == 13 ? 4 : 0;
 }
@@ -86,7 +93,8 @@ __host__ __device__ constexpr int wt_mbits(int wt) { return wt < 8 ? 0 : wt_bits
 // gfx950).  Their codes sit in the lane's bytes in plain order -- code c of the lane at
 // bits [c*bits, (c+1)*bits), pair t = codes (2t, 2t+1) -- which is the order the
 // packed convert instructions read; every other type uses the two 16-bit streams.
-__host__ __device__ constexpr bool wt_natural(int wt) { return wt == 9 || wt == 11 || wt == 13; }
+// Codebook indices use the same plain order: extracting an index is then a bit-field extract.
+__host__ __device__ constexpr bool wt_natural(int wt) { return wt == 9 || wt == 11 || wt == 13 || wt_is_lut(wt); }
 
 inline int wt_index(const qg_wtype& t) {
   if (t.bits < 1 || t.bits > 8) return -1;
@@ -96,6 +104,7 @@ inline int wt_index(const qg_wtype& t) {
     int wt = 8 + t.bits - 3;
     return (wt_ebits(wt) == t.ebits) ? wt : -2;   // -2: valid split, no kernel
   }
+  if (t.kind == QG_CODEBOOK) return (t.ebits == 0 && t.mbits == 0) ? WT_LUT0 + t.bits - 1 : -1;
   return -1;
 }
 
@@ -112,6 +121,7 @@ struct DequantParams {
   const uint8_t* W;
   const uint16_t* S;
   const uint8_t* Z;
+  const uint16_t* T;   // codebook: 2^bits half-precision levels (codebook indices only, else unused)
   uint16_t* out;
   int layout;
   int K, N, group;
@@ -128,6 +138,7 @@ struct GemmParams {
   const uint8_t* W;
   const uint16_t* S;
   const uint8_t* Z;
+  const uint16_t* T;    // codebook: 2^bits half-precision levels (codebook indices only, else unused)
   uint16_t* C;
   float* ws;            // split-K partial sums
   unsigned* tickets;    // one arrival counter per output tile, zero between calls

@@ -166,12 +166,12 @@ __device__ __forceinline__ void frag_mx(const uint32_t (&r)[4 * wt_bits(WT)], co
 // ============================ per-group constants ================================
 // sraw: the lane's 16-bit scales (its NTL adjacent columns, low bits first), zraw:
 // its zero-point bytes.  Built once per (chunk, group), used by 8 or 16 pairs each.
-template <int WT, int ROUTE, int LY = 0>
+template <int WT, int ROUTE, int LY = 0, bool LUT = wt_is_lut(WT)>
 struct Decoder;
 
 // ---- integers, fp16 route:  w = ((2^e + q) - (2^e + z')) * s ------------------
 template <int WT, int LY>
-struct Decoder<WT, ROUTE_F16, LY> {
+struct Decoder<WT, ROUTE_F16, LY, false> {
   static constexpr int NTL = LayoutOf<LY>::NT;     // columns per lane
   static constexpr int BITS = wt_bits(WT);
   static constexpr bool IS_FLOAT = wt_is_float(WT);
@@ -181,6 +181,7 @@ struct Decoder<WT, ROUTE_F16, LY> {
   static constexpr int RAW = 4 * BITS;
   static constexpr bool HAS_META = true;           // scales / zero-points are loaded with every chunk
   static constexpr bool IS_MX = false;
+  static constexpr bool IS_LUT = false;
 
   struct Consts {
     h2_t s[NTL];
@@ -288,7 +289,7 @@ struct Decoder<WT, ROUTE_F16, LY> {
 
 // ---- bf16 route:  w = bf16_rne( fma(x, s, -(2^e + z') * s) ), all exact in fp32 --
 template <int WT, int LY>
-struct Decoder<WT, ROUTE_BF16, LY> {
+struct Decoder<WT, ROUTE_BF16, LY, false> {
   static constexpr int NTL = LayoutOf<LY>::NT;     // columns per lane
   static constexpr int BITS = wt_bits(WT);
   static constexpr bool IS_FLOAT = wt_is_float(WT);
@@ -298,6 +299,7 @@ struct Decoder<WT, ROUTE_BF16, LY> {
   static constexpr int RAW = 4 * BITS;
   static constexpr bool HAS_META = true;           // scales / zero-points are loaded with every chunk
   static constexpr bool IS_MX = false;
+  static constexpr bool IS_LUT = false;
 
   struct Consts {
     float s[NTL];     // integers: scale; floats: scale * 2^(15-bias)
@@ -399,6 +401,130 @@ struct Decoder<WT, ROUTE_BF16, LY> {
   }
 };
 
+// ===================================== codebook lookup ==========================================
+// The paper's closing section says a lookup instruction would accommodate codebook quantisation:
+// a code is an index into a table of 2^BITS levels.  Here the lookup is one LDS read.  Up to 4 bits
+// the table is indexed by a PAIR of codes (the two k values of one operand register, adjacent in
+// the lane's bit stream) and returns both levels, already packed the way the matrix instruction
+// reads them: a bit-field extract, an address and one 4-byte read per pair.  From 5 bits on a
+// pair table would not fit; each code is looked up by itself with a 16-bit read into its half of
+// the register.  Every entry is stored 32 times, entry e of copy c at dword 32*e + c, and lane l
+// reads copy l % 32: the 32 lanes the LDS serves together then hit 32 different banks whatever
+// their codes are.  The levels are half precision; the group scale multiplies them with the
+// one rounding of the other types (fp16: packed-half multiply; bf16: exact fp32 product, hardware
+// fp32 -> bf16 rounding).  No zero-points.
+typedef __attribute__((address_space(3))) const uint32_t* lds_u32_ptr;
+typedef __attribute__((address_space(3))) const _Float16* lds_h_ptr;
+
+template <int WT, int ROUTE, int LY>
+struct Decoder<WT, ROUTE, LY, true> {
+  static_assert(LY == 0, "codebook indices exist on the first layout");
+  static constexpr int NTL = 4;
+  static constexpr int BITS = wt_bits(WT);
+  static constexpr int RAW = 4 * BITS;
+  static constexpr bool HAS_META = true;
+  static constexpr bool IS_MX = false;
+  static constexpr bool IS_LUT = true;
+  static constexpr bool PAIRED = BITS <= 4;
+  static constexpr int IDX_BITS = PAIRED ? 2 * BITS : BITS;
+  static constexpr int ENTRIES = 1 << IDX_BITS;
+  static constexpr int TABLE_DWORDS = ENTRIES * 32;        // 32 copies
+  static constexpr int LEVELS = 1 << BITS;
+
+  struct Consts {
+    h2_t s[NTL];       // fp16 route
+    float f[NTL];      // bf16 route
+  };
+  struct Uniform {
+    uint32_t base;     // LDS byte address of entry 0 of the lane's copy
+    __device__ __forceinline__ void init() { base = 0; }
+    __device__ __forceinline__ void set_table(const uint32_t* table, int lane) {
+      base = (uint32_t)(uintptr_t)(lds_u32_ptr)table + 4u * (uint32_t)(lane & 31);
+    }
+  };
+
+  // Builds the replicated table from the 2^BITS levels, in two steps so that a kernel can start
+  // its first weight loads in between: fetch() reads this thread's level (workgroups have at
+  // least 256 threads, so one each covers the table), build() places it in `stage` (256 halves
+  // of LDS) and writes the entries to `table` (TABLE_DWORDS dwords of LDS).  Every thread of the
+  // workgroup calls both; build() contains two workgroup barriers.
+  static __device__ __forceinline__ uint32_t fetch(const uint16_t* levels, int tid) {
+    return levels[tid < LEVELS ? tid : 0];
+  }
+  static __device__ __forceinline__ void build(uint32_t* table, uint16_t* stage, uint32_t level, int tid, int nthreads) {
+    if (tid < LEVELS) stage[tid] = (uint16_t)level;
+    __syncthreads();
+    for (int i = tid; i < TABLE_DWORDS; i += nthreads) {
+      const int e = i >> 5;
+      if constexpr (PAIRED) table[i] = (uint32_t)stage[e & (LEVELS - 1)] | ((uint32_t)stage[e >> BITS] << 16);
+      else table[i] = stage[e];
+    }
+    __syncthreads();
+  }
+
+  static __device__ __forceinline__ void make_col(Consts& gc, int nt, uint2 sraw, uint32_t, int, int scale_bf16) {
+    const uint32_t sw = (nt >> 1) ? sraw.y : sraw.x;
+    const uint32_t s16 = (nt & 1) ? (sw >> 16) : (sw & 0xffffu);
+    if constexpr (ROUTE == ROUTE_F16) {
+      gc.s[nt] = as_h2(s16 | (s16 << 16));
+    } else {
+      const uint32_t from_h = __builtin_bit_cast(uint32_t, (float)__builtin_bit_cast(_Float16, (uint16_t)s16));
+      const uint32_t sel = scale_bf16 ? 0xffffffffu : 0u;
+      gc.f[nt] = __builtin_bit_cast(float, ((s16 << 16) & sel) | (from_h & ~sel));
+    }
+  }
+  static __device__ __forceinline__ void make_consts(Consts& gc, uint2 sraw, uint32_t zraw, int zbias, int scale_bf16) {
+#pragma unroll
+    for (int nt = 0; nt < NTL; ++nt) make_col(gc, nt, sraw, zraw, zbias, scale_bf16);
+  }
+
+  // LDS address of the entry that element E (IDX_BITS wide) of the lane's bit stream selects
+  template <int E>
+  static __device__ __forceinline__ uint32_t entry_addr(const uint32_t (&r)[RAW], const Uniform& u) {
+    constexpr int bit = E * IDX_BITS, w = bit >> 5, sh = bit & 31;
+    uint32_t x;
+    if constexpr (sh + IDX_BITS <= 32) x = shr<sh>(r[w]);
+    else x = (r[w] >> sh) | (r[w + 1] << (32 - sh));
+    return ((x & (uint32_t)(ENTRIES - 1)) << 7) + u.base;
+  }
+
+  // "extract" = the lookup itself (the LDS read is in flight until the value is used),
+  // "centre" = widen for the bf16 route, "round" = the one rounding multiply by the scale.
+  typedef uint32_t Mid;
+  template <int T>
+  static __device__ __forceinline__ uint32_t pair_e(const uint32_t (&r)[RAW], const Uniform& u) {
+    if constexpr (PAIRED) {
+      return *reinterpret_cast<lds_u32_ptr>(entry_addr<T>(r, u));
+    } else {
+      h2_t v;
+      v.x = *reinterpret_cast<lds_h_ptr>(entry_addr<2 * T>(r, u));
+      v.y = *reinterpret_cast<lds_h_ptr>(entry_addr<2 * T + 1>(r, u));
+      return u32(v);
+    }
+  }
+  template <int T>
+  static __device__ __forceinline__ Mid pair_s(uint32_t x, const Consts&, int) { return x; }
+  static __device__ __forceinline__ uint32_t pair_p(Mid m, const Consts& gc, int nt) {
+    const h2_t x = as_h2(m);
+    if constexpr (ROUTE == ROUTE_F16) {
+      return u32(x * gc.s[nt]);
+    } else {
+      // level * scale is exact in fp32 (11 x 11 significant bits); adding -0 keeps the sign of a zero product
+      f2_t f = {__builtin_fmaf((float)x.x, gc.f[nt], -0.0f), __builtin_fmaf((float)x.y, gc.f[nt], -0.0f)};
+      return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, b2_t));
+    }
+  }
+  template <int J, int NT>
+  static __device__ __forceinline__ void frag(const uint32_t (&r)[RAW], const Consts& gc, const Uniform& u, uint32_t (&out)[4]) {
+    constexpr int T0 = LayoutOf<0>::t0(J, NT);
+    const uint32_t x0 = pair_e<T0 + 0>(r, u), x1 = pair_e<T0 + 1>(r, u), x2 = pair_e<T0 + 2>(r, u), x3 = pair_e<T0 + 3>(r, u);
+    out[0] = pair_p(x0, gc, NT);
+    out[1] = pair_p(x1, gc, NT);
+    out[2] = pair_p(x2, gc, NT);
+    out[3] = pair_p(x3, gc, NT);
+  }
+};
+
 // ================= weights already de-quantised (the paper's prefill variant) ==================
 // For prefill-sized batches the paper decodes the quantised weight to float16 once and runs a
 // standard 16-bit matmul (Section "End-to-End Performance").  Here the de-quantiser can write its
@@ -406,13 +532,12 @@ struct Decoder<WT, ROUTE_BF16, LY> {
 // 16 pieces of 1024 bytes, piece 4*j + nt holds, for lane l at bytes [16*l, 16*l + 16), the four
 // registers the lane feeds to the matrix instruction for k-step j and sub-tile nt -- and the tiled
 // kernel then runs with this pass-through "decoder": the same kernel with the unpack removed.
-constexpr int WT_DENSE16 = NUM_WT;       // kernel-side index only, not a weight type of the interface
-
 template <int ROUTE>
 struct DenseDecoder {
   static constexpr int NTL = 4, BITS = 16, RAW = 64;
   static constexpr bool HAS_META = false;
   static constexpr bool IS_MX = false;
+  static constexpr bool IS_LUT = false;
   struct Consts {};
   struct Uniform { __device__ __forceinline__ void init() {} };
   typedef uint32_t Mid;
@@ -438,6 +563,7 @@ struct MxDecoder {
   static constexpr int NTL = 4, BITS = wt_bits(WT), RAW = 4 * BITS;
   static constexpr bool HAS_META = true;
   static constexpr bool IS_MX = true;
+  static constexpr bool IS_LUT = false;
   static_assert(WT == 9 || WT == 13, "block-scaled converts exist for e2m1 and e4m3");
   struct Consts { float s[4]; };
   struct Uniform { __device__ __forceinline__ void init() {} };

@@ -124,6 +124,12 @@ __global__ __launch_bounds__(NW * 64) void decode_kernel(GemmParams p) {
     return;
 #endif
     const int g0 = (GPC > 1) ? GPC * c : ((c >> p.gshift) & p.gmask);
+    if constexpr (D::IS_LUT) {   // codebook indices: scales only
+#pragma unroll
+      for (int g = 0; g < GPC; ++g) s.s[g] = *reinterpret_cast<const uint2*>(p.S + (int64_t)(g0 + g) * p.N + n0);
+      __builtin_amdgcn_sched_barrier(0);
+      return;
+    }
     if constexpr (MX) {          // four scale bytes (the lane's columns) per block of 32 rows, kept in the zero-point slot
 #pragma unroll
       for (int g = 0; g < GPC; ++g)
@@ -192,7 +198,7 @@ __global__ __launch_bounds__(NW * 64) void decode_kernel(GemmParams p) {
     }
 #endif
 #pragma unroll
-    for (int g = 0; g < GPC; ++g) D::make_consts(gc[g], s.s[g], s.z[g] & zmask, p.zbias, p.scale_bf16);
+    for (int g = 0; g < GPC; ++g) D::make_consts(gc[g], s.s[g], D::IS_LUT ? 0u : (s.z[g] & zmask), p.zbias, p.scale_bf16);
     static_for<4>([&](auto Jc) __attribute__((always_inline)) {
       constexpr int J = decltype(Jc)::value;
       static_for<4>([&](auto NTc) __attribute__((always_inline)) {
@@ -217,9 +223,24 @@ __global__ __launch_bounds__(NW * 64) void decode_kernel(GemmParams p) {
 
   auto chunk_of = [&](int i) __attribute__((always_inline)) { return c0 + wk + min(i, mine - 1) * NK; };
 
-  if (mine > 0) {
-    // prologue: DEPTH chunks in flight (past-the-end stages re-load my last chunk)
+  // LDS: the reduction buffer after the main loop; during it, for codebook indices, the
+  // replicated lookup table (built by all wavefronts while the first loads are in flight)
+  constexpr int RED_BYTES = NW * 16 * 64 * 4;
+  constexpr int LUT_BYTES = [] { if constexpr (D::IS_LUT) return D::TABLE_DWORDS * 4 + 512; else return 0; }();
+  __shared__ __attribute__((aligned(16))) unsigned char lds_raw[RED_BYTES > LUT_BYTES ? RED_BYTES : LUT_BYTES];
+
+  static_assert(!D::IS_LUT || NW * 64 >= 256, "one level per thread");
+  uint32_t my_level = 0;
+  if constexpr (D::IS_LUT) my_level = D::fetch(p.T, tid);
+  // prologue: DEPTH chunks in flight (past-the-end stages re-load my last chunk)
+  if (mine > 0)
     static_for<DEPTH>([&](auto Sc) __attribute__((always_inline)) { issue(Sc, chunk_of(decltype(Sc)::value)); });
+  if constexpr (D::IS_LUT) {
+    uint32_t* table = reinterpret_cast<uint32_t*>(lds_raw);
+    D::build(table, reinterpret_cast<uint16_t*>(lds_raw + D::TABLE_DWORDS * 4), my_level, tid, NW * 64);
+    u.set_table(table, l);
+  }
+  if (mine > 0) {
     int i = 0;
     // steady state: no branches, so the compiler can wait on exact load counts
     for (; i + 2 * DEPTH <= mine; i += DEPTH)
@@ -242,7 +263,8 @@ __global__ __launch_bounds__(NW * 64) void decode_kernel(GemmParams p) {
   }
 
   // ---- reduce over the NW wavefronts through LDS, one 16-row tile at a time -----------------
-  __shared__ float red[NW * 16 * 64];                      // [NW][16 column offsets][64 lanes]
+  if constexpr (D::IS_LUT) __syncthreads();                // every wavefront is done with the table
+  float* red = reinterpret_cast<float*>(lds_raw);          // [NW][16 column offsets][64 lanes]
   int* s_last = reinterpret_cast<int*>(red);               // reused once the sums are in registers
   constexpr int PER = 16 / NK;                             // column offsets per thread
   const int idx0 = PER * wk;
@@ -380,7 +402,7 @@ static int launch_variant(const GemmParams& p, int variant, hipStream_t st) {
       case 41: return launch_cfg<ROUTE, 4, 4, 2, 4>(p, st);
       default: return QG_EINVAL;
     }
-  }
+  } else {
   switch (variant) {
     case 10: return launch_cfg<ROUTE, GPC, 8, 2, 1>(p, st);
     case 11: return launch_cfg<ROUTE, GPC, 4, 2, 1>(p, st);
@@ -393,6 +415,7 @@ static int launch_variant(const GemmParams& p, int variant, hipStream_t st) {
     case 46: return launch_cfg<ROUTE, GPC, 4, 2, 4, 2>(p, st);     // 4 row tiles, 2 strips x 2
     case 41: return launch_cfg<ROUTE, GPC, 4, 2, 4>(p, st);
     default: return QG_EINVAL;
+  }
   }
 }
 

@@ -22,6 +22,14 @@ __global__ __launch_bounds__(256) void dequant_kernel(DequantParams p) {
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int KC = p.K / TILE_K;
   const int64_t chunk = (int64_t)blockIdx.x * 4 + wave;
+  typename D::Uniform u;
+  u.init();
+  if constexpr (D::IS_LUT) {       // codebook indices: the replicated lookup table, built by the whole workgroup
+    __shared__ __attribute__((aligned(16))) unsigned char lds_raw[D::TABLE_DWORDS * 4 + 512];
+    uint32_t* table = reinterpret_cast<uint32_t*>(lds_raw);
+    D::build(table, reinterpret_cast<uint16_t*>(lds_raw + D::TABLE_DWORDS * 4), D::fetch(p.T, threadIdx.x), threadIdx.x, 256);
+    u.set_table(table, l);
+  }
   if (chunk >= (int64_t)KC * (p.N / TILE_N)) return;
   const int nc = (int)(chunk / KC), kc = (int)(chunk % KC);
 
@@ -32,8 +40,6 @@ __global__ __launch_bounds__(256) void dequant_kernel(DequantParams p) {
     uint4 q = src[i * 64 + l];
     r[4 * i + 0] = q.x; r[4 * i + 1] = q.y; r[4 * i + 2] = q.z; r[4 * i + 3] = q.w;
   }
-  typename D::Uniform u;
-  u.init();
   const int n0 = TILE_N * nc + L::pair_n(l, 0);
   static_for<L::STEPS>([&](auto Jc) __attribute__((always_inline)) {
     constexpr int J = decltype(Jc)::value;
@@ -43,7 +49,8 @@ __global__ __launch_bounds__(256) void dequant_kernel(DequantParams p) {
     if constexpr (MX) {
     } else if constexpr (L::NT == 4) {
       sraw = *reinterpret_cast<const uint2*>(p.S + (int64_t)g * p.N + n0);
-      if (p.Z) zraw = *reinterpret_cast<const uint32_t*>(p.Z + (int64_t)g * p.N + n0);
+      if constexpr (!D::IS_LUT)
+        if (p.Z) zraw = *reinterpret_cast<const uint32_t*>(p.Z + (int64_t)g * p.N + n0);
     } else {
       sraw = make_uint2(*reinterpret_cast<const uint32_t*>(p.S + (int64_t)g * p.N + n0), 0u);
       if (p.Z) zraw = *reinterpret_cast<const uint16_t*>(p.Z + (int64_t)g * p.N + n0);
@@ -113,8 +120,13 @@ int QG_CAT(dequant_launch_wt, QG_WT)(const DequantParams& p, int route, hipStrea
     return QG_EUNSUPPORTED;
 #endif
   }
+#if QG_WT > 14
+  if (p.layout != 0 || !p.T) return QG_EINVAL;          // codebook indices: first layout, with a table
+  launch_ly<0>(p, route, grid, block, st);
+#else
   if (p.layout == 0) launch_ly<0>(p, route, grid, block, st);
   else               launch_ly<1>(p, route, grid, block, st);
+#endif
   return hipGetLastError() == hipSuccess ? QG_OK : QG_EHIP;
 }
 

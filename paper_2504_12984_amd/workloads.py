@@ -9,7 +9,8 @@ inputs (Section "Performance of Low-Precision Kernels", artifact appendix "Data
 sets"); the cases below are dense i.i.d. stand-ins of those shapes.
 
 Draw order per case, from numpy Generator(PCG64(seed)):  A, codes, scales, then
-(only when they are random) the zero-points, then (int8 activations only) the row scales.
+(only when they are random) the zero-points, then (int8 activations only) the row scales, then
+(codebook weights only) the table of levels.
 """
 from __future__ import annotations
 
@@ -19,7 +20,7 @@ from typing import Optional
 import numpy as np
 import torch
 
-KIND_UINT, KIND_INT, KIND_FLOAT = 0, 1, 2
+KIND_UINT, KIND_INT, KIND_FLOAT, KIND_CODEBOOK = 0, 1, 2, 3
 _TORCH = {"f16": torch.float16, "bf16": torch.bfloat16}
 E8M0_LO, E8M0_HI = 119, 130      # block-scale exponents drawn for "e8m0" scales: 2^-8 .. 2^3
 
@@ -49,6 +50,8 @@ class Case:
     def wname(self) -> str:
         if self.kind == KIND_FLOAT:
             return f"f{self.bits}e{self.ebits}m{self.mbits}"
+        if self.kind == KIND_CODEBOOK:
+            return f"cb{self.bits}"
         return ("u" if self.kind == KIND_UINT else "i") + str(self.bits)
 
 
@@ -71,6 +74,9 @@ def make_inputs(case: Case):
            a uint8 tensor of exponents (the scale is 2^(e - 127))
     zeros  numpy uint8 [K/group, N] filled with case.zero -- or, for zero == "random",
            drawn uniformly from 0 .. zero_hi per (group, column) -- or None
+    codebook  (kind KIND_CODEBOOK only) torch CPU fp16 [2^bits]: draws of N(0,1) clipped to +-3,
+           sorted -- the unevenly spaced levels a learned companding quantiser ends up with for
+           bell-shaped weights; codes are uniform indices into it
     """
     rng = np.random.Generator(np.random.PCG64(case.seed))
     A = torch.from_numpy(rng.standard_normal((case.M, case.K), dtype=np.float32))
@@ -100,6 +106,9 @@ def make_inputs(case: Case):
     out = {"A": A, "codes": codes, "scales": scales, "zeros": zeros}
     if case.a8:
         out["a_scale"] = torch.from_numpy(rng.uniform(0.02, 0.03, size=case.M).astype(np.float32))
+    if case.kind == KIND_CODEBOOK:
+        lv = np.sort(np.clip(rng.standard_normal(1 << case.bits), -3.0, 3.0)).astype(np.float32)
+        out["codebook"] = torch.from_numpy(lv).to(torch.float16)
     return out
 
 
@@ -153,6 +162,13 @@ def sweep(kind: int, bits: int, M: int = 16) -> Case:
                     seed=620 + bits)
     return Case(f"sweep_i{bits}_M{M}", M, 8192, 57344, KIND_INT, bits, group=128, zero=None,
                 scale_lo=0.002, scale_hi=0.02, seed=640 + bits)
+
+
+def codebook(bits: int, M: int = 16, act: str = "f16") -> Case:
+    """Codebook-quantised weights on the type sweep's shape: K = 8192, N = 57344, group 128."""
+    assert 1 <= bits <= 8
+    return Case(f"codebook_{bits}_M{M}", M, 8192, 57344, KIND_CODEBOOK, bits, group=128, act=act,
+                scale_dtype="f16", zero=None, seed=700 + bits)
 
 
 def shrink(case: Case, **kw) -> Case:
