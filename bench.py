@@ -98,6 +98,10 @@ def cases_for(name):
         e, mm = {4: (2, 1), 8: (4, 3)}[int(bits)]
         return [WL.Case(name, int(m), 8192, 57344 if big else 8192, WL.KIND_FLOAT, int(bits), e, mm, group=32,
                         act="bf16", scale_dtype="e8m0", zero=None, seed=700 + int(bits))]
+    if name.startswith("codebook_"):                     # codebook lookup on the type sweep's shape: codebook_4, codebook_4_M1
+        rest = name[9:]
+        bits, m = rest.split("_M") if "_M" in rest else (rest, "16")
+        return [WL.codebook(int(bits), int(m))]
     if name.startswith("sweep_"):                        # sweep_u4, sweep_i7, sweep_f6 (M = 16), sweep_u4_M8192
         kind = {"u": WL.KIND_UINT, "i": WL.KIND_INT, "f": WL.KIND_FLOAT}[name[6]]
         rest = name[7:]
@@ -132,6 +136,10 @@ def decode_lane_ops_per_element(c):
         return 2 / 4.0 + 3 * 16 / (64.0 * min(c.group, 128))
     if c.scale_dtype == "e8m0":
         return 1 / 2.0            # one scaled hardware convert per pair of codes
+    if c.kind == WL.KIND_CODEBOOK:
+        # index extract + address, the LDS read aside, + the rounding multiply: per pair of codes up to
+        # 4 bits (one read returns both levels), per code above (+ one merge of the two halves)
+        return (3 if c.bits <= 4 else 6) / 2.0 if c.act == "f16" else (7 if c.bits <= 4 else 9) / 2.0
     hw = c.kind == WL.KIND_FLOAT and (c.ebits, c.mbits) in ((2, 1), (3, 2), (4, 3))
     per_pair = (2 if hw else 3) if c.act == "f16" else (3 if hw else 4)
     return per_pair / 2.0
@@ -155,8 +163,12 @@ def cpu_baseline(case, budget_s=20.0):
         cols = np.arange(start, min(case.N, start + block))
         c0 = proc.cpu_times()
         t0 = time.perf_counter()
-        O.qgemm_from_stream(A, stream, case.kind, case.bits, case.ebits, case.mbits, S, inp["zeros"],
-                            case.group, case.K, case.N, case.act, cols=cols)
+        if case.kind == WL.KIND_CODEBOOK:
+            O.qgemm_codebook_from_stream(A, stream, case.bits, inp["codebook"].double().numpy(), S, case.group,
+                                         case.K, case.N, case.act, cols=cols)
+        else:
+            O.qgemm_from_stream(A, stream, case.kind, case.bits, case.ebits, case.mbits, S, inp["zeros"],
+                                case.group, case.K, case.N, case.act, cols=cols)
         t_used += time.perf_counter() - t0
         c1 = proc.cpu_times()
         cpu_used += (c1.user + c1.system) - (c0.user + c0.system)
@@ -192,12 +204,18 @@ class Leg:
         inps = [WL.make_inputs(c) if i else inp0 for i, c in enumerate(self.cases)]
         self.As = [x["A"].to(dev) for x in inps]
         self.a_scales = [x["a_scale"].to(dev) if c.a8 else None for x, c in zip(inps, self.cases)]
+        inp_table = inp0.get("codebook")
         del inp0, inps
         out_dt = {"f16": torch.float16, "bf16": torch.bfloat16}
         self.Cs = [torch.empty((c.M, c.N), dtype=out_dt[c.act], device=dev) for c in self.cases]
         torch.cuda.synchronize()
         # arguments marshalled once per (case, weight copy): the timed loop is foreign calls only
-        if c0.a8:
+        self.table = None
+        if c0.kind == WL.KIND_CODEBOOK:
+            table = self.table = inp_table.to(dev)
+            self.calls = [[B.BoundQgemmCodebook(A, self.packed[i], table, self.scales[i], c.bits, c.group, c.N, C)
+                           for i in range(self.copies)] for c, A, C in zip(self.cases, self.As, self.Cs)]
+        elif c0.a8:
             self.calls = [[B.BoundQgemmA8(A, a_s, self.packed[i], self.scales[i], self.zeros[i], self.wt, c.group, c.N, C)
                            for i in range(self.copies)] for c, A, a_s, C in zip(self.cases, self.As, self.a_scales, self.Cs)]
         else:
@@ -350,8 +368,11 @@ class Leg:
         import torch
         from paper_2504_12984_amd import binding as B
         c0 = self.c0
-        Wd = B.qdequant(self.packed[0], self.scales[0], self.zeros[0], self.wt, self.As[0].dtype, c0.group, c0.K, c0.N,
-                        layout=self.layout)
+        if self.table is not None:
+            Wd = B.qdequant_codebook(self.packed[0], self.table, self.scales[0], c0.bits, self.As[0].dtype, c0.group, c0.K, c0.N)
+        else:
+            Wd = B.qdequant(self.packed[0], self.scales[0], self.zeros[0], self.wt, self.As[0].dtype, c0.group, c0.K, c0.N,
+                            layout=self.layout)
         Cd = torch.empty_like(self.Cs[0])
         for _ in range(3):
             torch.matmul(self.As[0], Wd, out=Cd)

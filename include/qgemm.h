@@ -219,9 +219,9 @@ QG_API int qgemm_a8(const int8_t* A8, const float* a_scale, const void* packed_W
  *   scales / scale_dtype (QG_F16, or QG_BF16 with bf16 activations) / group / K, N / act as for
  *   qdequant and qgemm
  * The lookup is an LDS read from a table replicated over the 32 banks (up to 4 bits: one read
- * returns the two levels of a pair of codes; above: one read per code).  qgemm_codebook serves
- * any M >= 1 with the streaming kernel (rows in blocks of 64; no tiled kernel yet); workspace,
- * stream and error conventions as for qgemm.  QG_EINVAL on a null table, bits outside 1..8 and
+ * returns the two levels of a pair of codes; above: one read per code).  qgemm_codebook chooses
+ * between the streaming and the tiled kernel as qgemm does (the experiment overrides of
+ * qgemm_tuning.h apply); workspace, stream and error conventions as for qgemm.  QG_EINVAL on a null table, bits outside 1..8 and
  * on the shape / group violations of qgemm. */
 QG_API int qdequant_codebook(const void* packed_W, const void* codebook, const void* scales, int bits,
                       int act, int scale_dtype, int64_t group, int64_t K, int64_t N, void* W_out, void* stream);

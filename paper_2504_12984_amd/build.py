@@ -31,7 +31,7 @@ def _jobs():
         jobs += [(src, wt) for wt in range(NUM_WT)]
     jobs += [("qg_a8_gemm.hip", -bits) for bits in range(1, 9)]      # int8 activations: once per code width
     jobs.append(("qg_large.hip", NUM_WT))      # the tiled kernel on weights already de-quantised (pass-through decoder)
-    for src in ("qg_dequant.hip", "qg_decode_gemm.hip"):      # codebook indices of 1..8 bits (kernel-side types 15..22)
+    for src in ("qg_dequant.hip", "qg_decode_gemm.hip", "qg_large.hip"):      # codebook indices of 1..8 bits (kernel-side types 15..22)
         jobs += [(src, NUM_WT + 1 + b) for b in range(8)]
     return jobs
 

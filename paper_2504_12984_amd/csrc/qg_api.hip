@@ -28,7 +28,8 @@ int large_launch_wt14(const GemmParams&, int, int, hipStream_t);
 #define QG_FOR_ALL_LUT(X) X(15) X(16) X(17) X(18) X(19) X(20) X(21) X(22)
 #define QG_DECL(i)                                                            \
   int dequant_launch_wt##i(const DequantParams&, int, hipStream_t);           \
-  int decode_launch_wt##i(const GemmParams&, int, int, hipStream_t);
+  int decode_launch_wt##i(const GemmParams&, int, int, hipStream_t);          \
+  int large_launch_wt##i(const GemmParams&, int, int, hipStream_t);
 QG_FOR_ALL_LUT(QG_DECL)
 #undef QG_DECL
 #define QG_DECL_A8(b) int a8_launch_bits##b(const A8Params&, int, int, hipStream_t);
@@ -57,6 +58,9 @@ static const dq_fn kDequantLut[NUM_LUT] = {QG_FOR_ALL_LUT(QG_ENT)};
 #undef QG_ENT
 #define QG_ENT(i) decode_launch_wt##i,
 static const gm_fn kDecodeLut[NUM_LUT] = {QG_FOR_ALL_LUT(QG_ENT)};
+#undef QG_ENT
+#define QG_ENT(i) large_launch_wt##i,
+static const gm_fn kLargeLut[NUM_LUT] = {QG_FOR_ALL_LUT(QG_ENT)};
 #undef QG_ENT
 typedef int (*waves_fn)(int);
 #define QG_ENT(i) decode_waves_wt##i,
@@ -396,7 +400,6 @@ static void plan_tiled(int64_t M, int64_t N, int64_t K, qg_wtype t, int* bm_out,
 // over blocks of 64 rows (forced only)
 static int plan_path(int64_t M, int64_t N, int64_t K, qg_wtype t) {
   const int bits = t.bits;
-  if (t.kind == QG_CODEBOOK) return M > 64 ? 3 : 1;      // the lookup exists in the streaming kernel only
   if (knob(0)) return knob(0);
   if (M > 64) return 2;
   // 33 .. 64 rows: the streaming kernel (4 row tiles per wavefront) re-reads A from L2 for
@@ -584,7 +587,8 @@ static int qgemm_run(const void* A, const void* packed_W, const void* scales, co
     d.layout = QG_LAYOUT_TILE128x64; d.K = p.K; d.N = p.N; d.group = p.group; d.zbias = p.zbias; d.scale_bf16 = p.scale_bf16;
     d.scale_e8m0 = 0;
     d.frag_out = 1;
-    rc = kDequant[wt](d, route, st);
+    d.T = p.T;
+    rc = wt_is_lut(wt) ? kDequantLut[wt - WT_LUT0](d, route, st) : kDequant[wt](d, route, st);
     if (rc != QG_OK) return rc;
     GemmParams q = p;
     q.W = static_cast<const uint8_t*>(dense);
@@ -624,7 +628,7 @@ static int qgemm_run(const void* A, const void* packed_W, const void* scales, co
     rc = acquire_ws(ws_mode, (size_t)p.splitk * (size_t)tiles * (size_t)(bm * 256) * sizeof(float), (size_t)tiles * 4, st, p);   // a ticket per 64-column strip
     if (rc != QG_OK) return rc;
   }
-  return kLarge[wt](p, route, bm, st);
+  return wt_is_lut(wt) ? kLargeLut[wt - WT_LUT0](p, route, bm, st) : kLarge[wt](p, route, bm, st);
 }
 
 int qgemm(const void* A, const void* packed_W, const void* scales, const uint8_t* zeros, qg_wtype t, int layout,

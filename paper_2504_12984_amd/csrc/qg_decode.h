@@ -8,6 +8,8 @@
 // gfx950's (v_and_or_b32, packed-half add/mul, v_fma_mix_f32, v_cvt_pk_bf16_f32)
 // rather than the PRMT/LOP3 sequences the paper uses on NVIDIA hardware.
 #pragma once
+#include <type_traits>
+
 #include "qg_common.h"
 
 namespace qg {
@@ -220,6 +222,7 @@ struct Decoder<WT, ROUTE_F16, LY, false> {
   // The same pair in three separately schedulable phases (extract / centre or
   // re-bias / scale-and-round), so that a caller can slot them between matrix
   // instructions.
+  typedef uint32_t Ext;
   typedef h2_t Mid;
   template <int T>
   static __device__ __forceinline__ uint32_t pair_e(const uint32_t (&r)[RAW], const Uniform& u) {
@@ -343,6 +346,7 @@ struct Decoder<WT, ROUTE_BF16, LY, false> {
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, b2_t));
   }
 
+  typedef uint32_t Ext;
   typedef f2_t Mid;
   template <int T>
   static __device__ __forceinline__ uint32_t pair_e(const uint32_t (&r)[RAW], const Uniform& u) {
@@ -488,24 +492,30 @@ struct Decoder<WT, ROUTE, LY, true> {
     return ((x & (uint32_t)(ENTRIES - 1)) << 7) + u.base;
   }
 
-  // "extract" = the lookup itself (the LDS read is in flight until the value is used),
-  // "centre" = widen for the bf16 route, "round" = the one rounding multiply by the scale.
-  typedef uint32_t Mid;
+  // "extract" = the lookup itself: address arithmetic and the LDS read(s), whose results stay in
+  // flight until "round" uses them (the tiled kernel places that five matrix instructions later);
+  // "centre" has nothing to do; "round" = merge the two halves of a pair looked up code by code,
+  // then the one rounding multiply by the scale.
+  struct Two { _Float16 lo, hi; };
+  typedef typename std::conditional<PAIRED, uint32_t, Two>::type Ext;
+  typedef Ext Mid;
   template <int T>
-  static __device__ __forceinline__ uint32_t pair_e(const uint32_t (&r)[RAW], const Uniform& u) {
+  static __device__ __forceinline__ Ext pair_e(const uint32_t (&r)[RAW], const Uniform& u) {
     if constexpr (PAIRED) {
       return *reinterpret_cast<lds_u32_ptr>(entry_addr<T>(r, u));
     } else {
-      h2_t v;
-      v.x = *reinterpret_cast<lds_h_ptr>(entry_addr<2 * T>(r, u));
-      v.y = *reinterpret_cast<lds_h_ptr>(entry_addr<2 * T + 1>(r, u));
-      return u32(v);
+      Two v;
+      v.lo = *reinterpret_cast<lds_h_ptr>(entry_addr<2 * T>(r, u));
+      v.hi = *reinterpret_cast<lds_h_ptr>(entry_addr<2 * T + 1>(r, u));
+      return v;
     }
   }
   template <int T>
-  static __device__ __forceinline__ Mid pair_s(uint32_t x, const Consts&, int) { return x; }
+  static __device__ __forceinline__ Mid pair_s(Ext x, const Consts&, int) { return x; }
   static __device__ __forceinline__ uint32_t pair_p(Mid m, const Consts& gc, int nt) {
-    const h2_t x = as_h2(m);
+    h2_t x;
+    if constexpr (PAIRED) x = as_h2(m);
+    else x = (h2_t){m.lo, m.hi};
     if constexpr (ROUTE == ROUTE_F16) {
       return u32(x * gc.s[nt]);
     } else {
@@ -517,7 +527,7 @@ struct Decoder<WT, ROUTE, LY, true> {
   template <int J, int NT>
   static __device__ __forceinline__ void frag(const uint32_t (&r)[RAW], const Consts& gc, const Uniform& u, uint32_t (&out)[4]) {
     constexpr int T0 = LayoutOf<0>::t0(J, NT);
-    const uint32_t x0 = pair_e<T0 + 0>(r, u), x1 = pair_e<T0 + 1>(r, u), x2 = pair_e<T0 + 2>(r, u), x3 = pair_e<T0 + 3>(r, u);
+    const Ext x0 = pair_e<T0 + 0>(r, u), x1 = pair_e<T0 + 1>(r, u), x2 = pair_e<T0 + 2>(r, u), x3 = pair_e<T0 + 3>(r, u);
     out[0] = pair_p(x0, gc, NT);
     out[1] = pair_p(x1, gc, NT);
     out[2] = pair_p(x2, gc, NT);
@@ -540,6 +550,7 @@ struct DenseDecoder {
   static constexpr bool IS_LUT = false;
   struct Consts {};
   struct Uniform { __device__ __forceinline__ void init() {} };
+  typedef uint32_t Ext;
   typedef uint32_t Mid;
   static __device__ __forceinline__ void make_col(Consts&, int, uint2, uint32_t, int, int) {}
   template <int T>
@@ -567,6 +578,7 @@ struct MxDecoder {
   static_assert(WT == 9 || WT == 13, "block-scaled converts exist for e2m1 and e4m3");
   struct Consts { float s[4]; };
   struct Uniform { __device__ __forceinline__ void init() {} };
+  typedef uint32_t Ext;
   typedef uint32_t Mid;
   static __device__ __forceinline__ void make_col(Consts& gc, int nt, uint2, uint32_t s4, int, int) {
     gc.s[nt] = __builtin_bit_cast(float, ((s4 >> (8 * nt)) & 0xffu) << 23);

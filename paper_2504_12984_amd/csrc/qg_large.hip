@@ -225,6 +225,8 @@ __global__ __launch_bounds__(256) void large_kernel(GemmParams p, int tiles_m, i
   u.init();
 
   // ---- prologue: chunk 0's A slab into buffer 0, ring primed for chunk 1 --------------
+  uint32_t my_level = 0;
+  if constexpr (D::IS_LUT) my_level = D::fetch(p.T, tid);       // codebook indices: this thread's level of the table
   WStage wA, wB;
   w_issue(wA, kbeg);
   const int ks0 = 4 * kbeg;
@@ -244,6 +246,15 @@ __global__ __launch_bounds__(256) void large_kernel(GemmParams p, int tiles_m, i
 
   // my A fragment of row-tile mt, k-step slice j: piece b of row mt*16 + i16
   const int a_rd = i16 * 64 + 16 * (b ^ lds_swizzle(i16));
+
+  // Codebook indices: the replicated lookup table sits behind the two A buffers; the 512 bytes
+  // the build stages the levels in are borrowed from the second buffer, which nothing has
+  // written yet.  (Two workgroup barriers inside; the first loads are already in flight.)
+  if constexpr (D::IS_LUT) {
+    uint32_t* table = reinterpret_cast<uint32_t*>(lds + 2 * L::BUF);
+    D::build(table, reinterpret_cast<uint16_t*>(lds + L::BUF), my_level, tid, 256);
+    u.set_table(table, l);
+  }
 
   // Weight fragments are unpacked one k-step ahead of their use, and the unpack
   // of step J+1 is spread over the MFMAs of step J (one pair per 16-row tile),
@@ -327,7 +338,7 @@ __global__ __launch_bounds__(256) void large_kernel(GemmParams p, int tiles_m, i
       constexpr int J = decltype(Jc)::value;
       constexpr int JN = (J + 1) & 3;
       uint32_t nf[4][4];                 // fragment of k-step J+1 under construction
-      uint32_t xe[PB];
+      typename D::Ext xe[PB];
       typename D::Mid mid[PB], mid_prev[PB];
       const typename D::Consts& g = FOUR_GROUPS ? ((JN & 1) ? gn0 : gc0)
                                                 : (J < 3) ? ((TWO_GROUPS && JN >= 2) ? g1 : gc0) : gn0;
@@ -531,7 +542,9 @@ static int launch_bm(const GemmParams& p, hipStream_t st, int tn0, int tiles_n) 
   if (p.splitk > 1 && BM > 128) return QG_EINVAL;
   const int total = tiles_m * tiles_n * p.splitk;
   const int per_xcd = (total + 7) / 8;
-  const size_t lds_bytes = 2 * LargeLds<BM>::BUF;
+  typedef typename DecoderFor<QG_WT, ROUTE, MX>::type D;
+  size_t lds_bytes = 2 * LargeLds<BM>::BUF;
+  if constexpr (D::IS_LUT) lds_bytes += (size_t)D::TABLE_DWORDS * 4;      // 256-row tiles + a 32 KiB table: exactly the 160 KiB of a CU
   auto kern = large_kernel<QG_WT, ROUTE, GPC, BM, MX>;
   // raise the dynamic LDS limit once per instantiation and device
   static bool attr_done[64] = {};

@@ -99,8 +99,16 @@ def test_codebook_matmul_every_row_count(bits, M):
     case = _case(f"cb_c_{bits}_{M}", M, 1408, 320, bits, "bf16" if M % 2 else "f16", 60100 + bits + M)
     P = CbCase(case)
     plan = P.B.qg_plan(P.wtype, case.group, M, case.N, case.K)
-    assert plan["path"] == (1 if M <= 64 else 3), plan
-    assert_c_close(P.gpu_c(), P.oracle_c(), case.name)
+    assert plan["path"] == (1 if M <= 64 else 2), plan
+    ref = P.oracle_c()
+    assert_c_close(P.gpu_c(), ref, case.name)
+    P.B.qg_set_knob(0, 2)                          # the tiled kernel at every tile height, also below its usual range
+    for bm in (64, 128, 256):
+        P.B.qg_set_knob(2, bm)
+        assert_c_close(P.gpu_c(), ref, f"{case.name} tiled {bm}")
+    P.B.qg_set_knob(2, 0)
+    P.B.qg_set_knob(0, 3)                          # and the streaming kernel over blocks of 64 rows
+    assert_c_close(P.gpu_c(), ref, case.name + " row blocks")
 
 
 @pytest.mark.parametrize("variant", [10, 11, 12, 14, 15, 16])
@@ -185,6 +193,54 @@ def test_codebook_smallest_shapes(M, K, N):
     _, wbits = P.oracle_w()
     assert np.array_equal(bits_of(P.gpu_w()), wbits)
     assert_c_close(P.gpu_c(), P.oracle_c(), case.name)
+
+
+@pytest.mark.parametrize("act", ["f16", "bf16"])
+@pytest.mark.parametrize("bits", [2, 4, 6, 8])
+def test_codebook_tiled_kernel_ragged_shapes_split_k_and_one_hot(bits, act):
+    from paper_2504_12984_amd import binding as B
+    # 7 chunks (odd: the padding chunk), 3 strips (an idle wavefront), rows past M; then K in two slabs;
+    # then the de-quantise-first path
+    case = _case(f"cb_tiled_{bits}_{act}", 300, 896, 192, bits, act, 60700 + bits, group=64 if bits == 4 else 128)
+    P = CbCase(case)
+    ref = P.oracle_c()
+    assert_c_close(P.gpu_c(), ref, case.name)
+    B.qg_set_knob(0, 2); B.qg_set_knob(2, 64); B.qg_set_knob(1, 2)
+    assert_c_close(P.gpu_c(), ref, case.name + " split")
+    B.qg_set_knob(1, 0); B.qg_set_knob(2, 0)
+    B.qg_set_knob(0, 4)
+    assert_c_close(P.gpu_c(), ref, case.name + " de-quantise first")
+    B.qg_set_knob(0, 0)
+    # one-hot rows through the tiled kernel: the de-quantised weight itself (a lone -0 sums to +0)
+    K, N = 256, 128
+    c2 = _case(f"cb_tiled_onehot_{bits}_{act}", K, K, N, bits, act, 60710 + bits)
+    inp = WL.make_inputs(c2)
+    A = torch.zeros((K, K), dtype=inp["A"].dtype)
+    A[torch.arange(K), torch.arange(K)] = 1.0
+    inp["A"] = A
+    P2 = CbCase(c2, inp)
+    _, wbits = P2.oracle_w()
+    want = wbits.copy()
+    want[want == 0x8000] = 0
+    assert np.array_equal(bits_of(P2.gpu_c()), want)
+
+
+@pytest.mark.parametrize("group", [32, 64])
+def test_codebook_tiled_kernel_small_groups(group):
+    case = _case(f"cb_tiled_g{group}", 200, 1024, 256, 3, "bf16", 60750 + group, group=group, scale_dtype="bf16")
+    P = CbCase(case)
+    assert_c_close(P.gpu_c(), P.oracle_c(), case.name)
+
+
+def test_codebook_prefill_shape_full_size():
+    # K = 8192, N = 57344 (the prefill shape), 4-bit codes, M = 1024: sampled columns for all rows
+    case = WL.codebook(4, 1024)
+    P = CbCase(case)
+    plan = P.B.qg_plan(P.wtype, case.group, case.M, case.N, case.K)
+    assert plan["path"] == 2, plan
+    C = P.gpu_c()
+    cols = np.unique(np.concatenate([np.arange(4), np.arange(57340, 57344), np.random.default_rng(4).integers(0, 57344, 64)]))
+    assert_c_close(C[:, torch.from_numpy(cols).cuda()], P.oracle_c(cols=cols), case.name)
 
 
 def test_codebook_argument_checks():
