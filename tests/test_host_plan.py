@@ -213,3 +213,23 @@ def test_dequantise_first_path_plan():
     with pytest.raises(B.QgError) as e:                                            # K*N*2 bytes must stay below 2 GiB
         B.qg_plan(U4, 128, 128, 65536, 16384, act=B.QG_BF16)
     assert e.value.status == B.QG_EUNSUPPORTED
+
+
+def test_codebook_weights_plan_like_the_integer_type_and_refusals():
+    CB4, CB8 = B.WType(B.QG_CODEBOOK, 4), B.WType(B.QG_CODEBOOK, 8)
+    for M, N, K in ((1, 57344, 8192), (16, 8192, 8192), (48, 28672, 8192), (300, 8192, 4096), (4096, 57344, 8192)):
+        assert B.qg_plan(CB4, 128, M, N, K) == B.qg_plan(U4, 128, M, N, K), (M, N, K)
+        assert B.qg_plan(CB8, 64, M, N, K, act=B.QG_BF16) == B.qg_plan(U8, 64, M, N, K, act=B.QG_BF16), (M, N, K)
+    # only the first layout has lookup kernels; block scales do not combine with a table
+    assert B.qgemm_packed_bytes(CB4, 256, 128) == 256 * 128 // 2
+    assert B.qgemm_packed_bytes(CB4, 256, 128, layout=B.QG_LAYOUT_TILE128x64_R32) == 0
+    with pytest.raises(B.QgError) as e:
+        B.qg_plan(CB4, 128, 16, 8192, 8192, layout=B.QG_LAYOUT_TILE128x64_R32)
+    assert e.value.status == B.QG_EUNSUPPORTED
+    with pytest.raises(B.QgError) as e:
+        B.qg_plan(CB4, 32, 16, 8192, 8192, act=B.QG_BF16, scale_dtype=B.QG_E8M0)
+    assert e.value.status == B.QG_EUNSUPPORTED
+    for bad in (B.WType(B.QG_CODEBOOK, 0), B.WType(B.QG_CODEBOOK, 9), B.WType(B.QG_CODEBOOK, 4, 1, 2)):
+        with pytest.raises(B.QgError) as e:
+            B.qg_plan(bad, 128, 16, 8192, 8192)
+        assert e.value.status == B.QG_EINVAL
