@@ -46,6 +46,8 @@ VALU_PEAK_TLANEOPS = 256 * 4 * 16 * 2.4e9 / 1e12
 # These are CARRIED OVER from the committed profile summaries, not measured in this run.
 MEASURED_TRAFFIC = {
     "cfg2": (24.63e6, "profiles/decode_kernel_cfg2_w3a16.txt"),
+    "cfg3_i4": (125.9e6, "profiles/decode_kernel_cfg3_i2_i4_counters.txt"),
+    "cfg5_u6_M4096": (3.845e9, "profiles/large_kernel_cfg5_u6_M4096.txt"),
 }
 
 
@@ -344,7 +346,10 @@ class Leg:
         else:
             metric, unit, value = "effective_tflops", "TFLOP/s", tflops
             roof = {"bound": "mfma", "achieved": round(tflops, 1), "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
-                    "frac": round(tflops / MFMA_PEAK_TFLOPS, 4), "traffic": None,
+                    "frac": round(tflops / MFMA_PEAK_TFLOPS, 4),
+                    "traffic": MEASURED_TRAFFIC[self.name][0] if self.name in MEASURED_TRAFFIC and self.layout == 0 else None,
+                    "traffic_source": (f"carried over from {MEASURED_TRAFFIC[self.name][1]} (counter run of this command), "
+                                       "not measured in this run") if self.name in MEASURED_TRAFFIC and self.layout == 0 else None,
                     "kernel": "qg::large32_kernel" if self.layout == 1 else "qg::large_kernel",
                     "avg_launch_us": round(launch_ms * 1e3, 3), "median_launch_us_per_case": med_us,
                     "algorithmic_flops_per_launch": flops_step / launches}
