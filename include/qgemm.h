@@ -231,8 +231,10 @@ QG_API int qgemm_codebook(const void* A, const void* packed_W, const void* codeb
 /* What qgemm would launch for a shape: host arithmetic only, no GPU call, usable without
  * a device.  Arguments as for qgemm (M >= 1).  plan (host, 5 ints) receives
  *   [0] path: 1 = streaming kernel, 2 = tiled kernel, 3 = streaming kernel over blocks of 64 rows,
- *       4 = de-quantise first, then the tiled kernel on 16-bit weights (forced only)
- *   [1] wavefront arrangement of the streaming kernel (the values of knob 3), 0 on path 2
+ *       4 = de-quantise first, then the tiled kernel on 16-bit weights (forced only),
+ *       5 = matrix-vector kernel on the vector ALU, M <= 4 (forced only)
+ *   [1] wavefront arrangement of the streaming kernel (the values of knob 3), 0 on path 2; on path 5
+ *       the wavefronts per strip
  *   [2] row-tile height of the tiled kernel: 64 or 128, or 0 = whole rounds of 256-row
  *       tiles, then 128 or 256 rows for the rest (paths 2 and 4); 0 on paths 1 and 3
  *   [3] K-slabs (split-K factor; 1 = none)   [4] K-chunks of 128 per slab

@@ -29,7 +29,10 @@ extern "C" {
  *           kernel runs on those 16-bit operands with its unpack stage switched off.  Same
  *           rounded weights, same results as path 2; K*N*2 must stay below 2 GiB.  It is
  *           never chosen automatically: it is slower than the fused kernel at every M
- *           measured, 64 to 12288 rows)
+ *           measured, 64 to 12288 rows; 5 = M <= 4 only: matrix-vector kernel on the vector
+ *           ALU -- two-element dot products, partial sums added inside the wavefront with lane
+ *           permutes -- the measured alternative to the matrix-core streaming kernel; knob 3
+ *           then takes its wavefronts per strip, 4 / 8 / 16)
  *   knob 1: forced split-K factor (streaming kernel; tiled kernel with 64- or 128-row tiles)
  *   knob 2: forced row-tile height of the tiled kernel (64 / 128 / 256; 64 on the first
  *           layout only)

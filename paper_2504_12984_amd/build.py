@@ -27,7 +27,7 @@ FLAGS = ["--offload-arch=gfx950", "-std=c++20", "-O3", "-fPIC", "-fvisibility=hi
 
 def _jobs():
     jobs = [("qg_pack.hip", None), ("qg_probe.hip", None), ("qg_api.hip", None)]
-    for src in ("qg_dequant.hip", "qg_decode_gemm.hip", "qg_large.hip", "qg_large32.hip"):
+    for src in ("qg_dequant.hip", "qg_decode_gemm.hip", "qg_large.hip", "qg_large32.hip", "qg_gemv.hip"):
         jobs += [(src, wt) for wt in range(NUM_WT)]
     jobs += [("qg_a8_gemm.hip", -bits) for bits in range(1, 9)]      # int8 activations: once per code width
     jobs.append(("qg_large.hip", NUM_WT))      # the tiled kernel on weights already de-quantised (pass-through decoder)

@@ -20,7 +20,8 @@ int launch_repack(const uint8_t*, int, int, int, uint32_t, int, int, uint8_t*, h
   int decode_launch_wt##i(const GemmParams&, int, int, hipStream_t);          \
   int decode_waves_wt##i(int);                                                \
   int large_launch_wt##i(const GemmParams&, int, int, hipStream_t);          \
-  int large32_launch_wt##i(const GemmParams&, int, int, hipStream_t);
+  int large32_launch_wt##i(const GemmParams&, int, int, hipStream_t);        \
+  int gemv_launch_wt##i(const GemmParams&, int, int, hipStream_t);
 QG_FOR_ALL_WT(QG_DECL)
 #undef QG_DECL
 int large_launch_wt14(const GemmParams&, int, int, hipStream_t);
@@ -52,6 +53,9 @@ static const gm_fn kLarge32[NUM_WT] = {QG_FOR_ALL_WT(QG_ENT)};
 #undef QG_ENT
 #define QG_ENT(i) decode_launch_wt##i,
 static const gm_fn kDecode[NUM_WT] = {QG_FOR_ALL_WT(QG_ENT)};
+#undef QG_ENT
+#define QG_ENT(i) gemv_launch_wt##i,
+static const gm_fn kGemv[NUM_WT] = {QG_FOR_ALL_WT(QG_ENT)};
 #undef QG_ENT
 #define QG_ENT(i) dequant_launch_wt##i,
 static const dq_fn kDequantLut[NUM_LUT] = {QG_FOR_ALL_LUT(QG_ENT)};
@@ -317,6 +321,27 @@ static void plan_streaming(int M, int N, int K, int group, int wt, int* variant_
   *cps_out = cps;
 }
 
+// Matrix-vector kernel (forced path 5, M <= 4): wavefronts per strip and split-K.  Host arithmetic only.
+static void plan_gemv(int M, int N, int K, int group, int wt, int* waves_out, int* splitk_out, int* cps_out) {
+  const int KC = K / TILE_K, NCH = N / TILE_N;
+  // as many wavefronts per strip as leaves each two chunks: 16 on long K for one row of A, codes of up to 4 bits and one
+  // scale group per chunk (beyond that the ring does not fit the 128 registers 16 wavefronts leave each), 8 from 16 chunks on, else 4
+  // (measured: 16 pay on short slabs only -- K = 4096, or long K on at most 128 strips, where K is split;
+  // K = 8192 on 448 or 896 strips is 6-13 % shorter with 8)
+  const bool short_slabs = KC == 32 || (KC > 32 && NCH <= 128);
+  int waves = (short_slabs && wt_bits(wt) <= 4 && M == 1 && group >= TILE_K) ? 16 : (KC >= 16 ? 8 : 4);
+  if (knob(3) == 4 || knob(3) == 8 || knob(3) == 16) waves = knob(3);
+  int splitk = knob(1);
+  if (splitk <= 0) {
+    splitk = 1;
+    // K over workgroups while the strips alone leave CUs idle and every wavefront keeps two chunks
+    while (NCH * splitk < 256 && KC / (splitk * 2) >= 2 * waves) splitk *= 2;
+  }
+  if (splitk > KC) splitk = KC;
+  const int cps = (KC + splitk - 1) / splitk;
+  *waves_out = waves; *splitk_out = (KC + cps - 1) / cps; *cps_out = cps;
+}
+
 // One launch of the streaming kernel.
 static int launch_streaming(GemmParams& p, int wt, int route, int ws_mode, hipStream_t st) {
   int variant;
@@ -570,7 +595,23 @@ static int qgemm_run(const void* A, const void* packed_W, const void* scales, co
   const int path = plan_path(M, N, K, t);
   if (p.scale_e8m0 && path == 4) return QG_EUNSUPPORTED;      // the de-quantise-first path has no block-scaled variant
   if (path == 1 && M > 64) return QG_EINVAL;
-  if (path < 1 || path > 4) return QG_EINVAL;
+  if (path < 1 || path > 5) return QG_EINVAL;
+  if (path == 5) {
+    // The decode-sized product as matrix-vector products on the vector ALU (two-element dot
+    // products, partial sums added across lanes with permutes): the measured alternative to
+    // the matrix-core streaming kernel for M <= 4.  Forced only.
+    if (M > 4 || wt_is_lut(wt)) return QG_EINVAL;
+    if (p.scale_e8m0) return QG_EUNSUPPORTED;
+    int waves;
+    plan_gemv(p.M, p.N, p.K, p.group, wt, &waves, &p.splitk, &p.chunks_per_split);
+    if (p.splitk > 1) {
+      const int NCH = p.N / TILE_N;
+      const int mr = M <= 1 ? 1 : (M <= 2 ? 2 : 4);
+      rc = acquire_ws(ws_mode, (size_t)p.splitk * NCH * (size_t)(mr * TILE_N) * sizeof(float), (size_t)NCH, st, p);
+      if (rc != QG_OK) return rc;
+    }
+    return kGemv[wt](p, route, waves, st);
+  }
 
   if (path == 4) {
     // The paper's prefill variant (Section "End-to-End Performance"): de-quantise the whole
@@ -753,7 +794,13 @@ int qg_plan(qg_wtype t, int layout, int act, int scale_dtype, int64_t group, int
       for (int64_t r0 = 0; r0 < M; r0 += 64)
         if (knob(3) / 10 != row_tiles(M - r0 < 64 ? M - r0 : 64)) return QG_EINVAL;
   } else {
-    if (plan[0] < 1 || plan[0] > 4) return QG_EINVAL;
+    if (plan[0] < 1 || plan[0] > 5) return QG_EINVAL;
+    if (plan[0] == 5) {
+      if (M > 4 || wt_is_lut(wt)) return QG_EINVAL;
+      if (scale_dtype == QG_E8M0) return QG_EUNSUPPORTED;
+      plan_gemv((int)M, (int)N, (int)K, (int)group, wt, &plan[1], &plan[3], &plan[4]);
+      return QG_OK;
+    }
     if (!tiled_operands_fit(M, N, K, group, t.bits)) return QG_EUNSUPPORTED;
     qg_wtype tt = t;
     if (plan[0] == 4) {

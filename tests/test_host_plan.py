@@ -233,3 +233,20 @@ def test_codebook_weights_plan_like_the_integer_type_and_refusals():
         with pytest.raises(B.QgError) as e:
             B.qg_plan(bad, 128, 16, 8192, 8192)
         assert e.value.status == B.QG_EINVAL
+
+
+def test_matrix_vector_path_plan():
+    B.qg_set_knob(0, 5)
+    p = B.qg_plan(U3, 128, 1, 14336, 4096)
+    assert (p["path"], p["variant"]) == (5, 16) and p["splitk"] == 1        # 32 chunks, 16 wavefronts, 224 strips: K in one piece
+    assert B.qg_plan(U3, 128, 4, 14336, 4096)["variant"] == 8               # several rows: the ring of 16 wavefronts would spill
+    assert B.qg_plan(U8, 128, 1, 8192, 8192)["variant"] == 8
+    assert B.qg_plan(U4, 128, 1, 512, 512)["variant"] == 4
+    p = B.qg_plan(U4, 128, 1, 8192, 8192)
+    assert p["variant"] == 16 and p["splitk"] == 2 and p["chunks_per_slab"] == 32
+    B.qg_set_knob(3, 8)
+    assert B.qg_plan(U4, 128, 1, 8192, 8192)["variant"] == 8
+    B.qg_set_knob(3, 0)
+    with pytest.raises(B.QgError) as e:
+        B.qg_plan(U4, 128, 5, 8192, 8192)
+    assert e.value.status == B.QG_EINVAL
