@@ -32,7 +32,7 @@ extern "C" {
  *           measured, 64 to 12288 rows; 5 = M <= 4 only: matrix-vector kernel on the vector
  *           ALU -- two-element dot products, partial sums added inside the wavefront with lane
  *           permutes -- the measured alternative to the matrix-core streaming kernel; knob 3
- *           then takes its wavefronts per strip, 4 / 8 / 16)
+ *           then takes its wavefronts per strip, 4 / 8, or 16 with M = 1)
  *   knob 1: forced split-K factor (streaming kernel; tiled kernel with 64- or 128-row tiles)
  *   knob 2: forced row-tile height of the tiled kernel (64 / 128 / 256; 64 on the first
  *           layout only)

@@ -330,7 +330,7 @@ static void plan_gemv(int M, int N, int K, int group, int wt, int* waves_out, in
   // K = 8192 on 448 or 896 strips is 6-13 % shorter with 8)
   const bool short_slabs = KC == 32 || (KC > 32 && NCH <= 128);
   int waves = (short_slabs && wt_bits(wt) <= 4 && M == 1 && group >= TILE_K) ? 16 : (KC >= 16 ? 8 : 4);
-  if (knob(3) == 4 || knob(3) == 8 || knob(3) == 16) waves = knob(3);
+  if (knob(3) == 4 || knob(3) == 8 || (knob(3) == 16 && M == 1)) waves = knob(3);      // 16 wavefronts: one row only
   int splitk = knob(1);
   if (splitk <= 0) {
     splitk = 1;
@@ -606,7 +606,7 @@ static int qgemm_run(const void* A, const void* packed_W, const void* scales, co
     plan_gemv(p.M, p.N, p.K, p.group, wt, &waves, &p.splitk, &p.chunks_per_split);
     if (p.splitk > 1) {
       const int NCH = p.N / TILE_N;
-      const int mr = M <= 1 ? 1 : (M <= 2 ? 2 : 4);
+      const int mr = M <= 1 ? 1 : 4;
       rc = acquire_ws(ws_mode, (size_t)p.splitk * NCH * (size_t)(mr * TILE_N) * sizeof(float), (size_t)NCH, st, p);
       if (rc != QG_OK) return rc;
     }

@@ -39,7 +39,7 @@ __device__ __forceinline__ uint32_t pack_out2(float lo, float hi) {
   else return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, b2_t));
 }
 
-// MR = rows of A carried (1, 2 or 4; rows past M repeat row M-1 and are never stored)
+// MR = rows of A carried (1 or 4; rows past M repeat row M-1 and are never stored)
 template <int WT, int ROUTE, int GPC, int NW, int MR>
 __global__ __launch_bounds__(NW * 64) void gemv_kernel(GemmParams p) {
   typedef Decoder<WT, ROUTE> D;
@@ -214,14 +214,17 @@ static int launch_gemv(const GemmParams& p, hipStream_t st) {
 
 template <int ROUTE, int GPC>
 static int launch_gemv_shape(const GemmParams& p, int waves, hipStream_t st) {
-  const int mr = p.M <= 1 ? 1 : (p.M <= 2 ? 2 : 4);
   if (p.M > 4) return QG_EINVAL;
-#define QG_ROWS(NW_)                                                                     \
-  if (waves == NW_)                                                                      \
-    return mr == 1 ? launch_gemv<ROUTE, GPC, NW_, 1>(p, st)                              \
-         : mr == 2 ? launch_gemv<ROUTE, GPC, NW_, 2>(p, st) : launch_gemv<ROUTE, GPC, NW_, 4>(p, st);
-  QG_ROWS(4) QG_ROWS(8) QG_ROWS(16)
-#undef QG_ROWS
+  // one row of A, or four (two and three rows ride in the four-row instantiation); 16 wavefronts per
+  // strip exist for one row only (with four rows their ring does not fit the registers)
+  if (p.M <= 1) {
+    if (waves == 4) return launch_gemv<ROUTE, GPC, 4, 1>(p, st);
+    if (waves == 8) return launch_gemv<ROUTE, GPC, 8, 1>(p, st);
+    if (waves == 16) return launch_gemv<ROUTE, GPC, 16, 1>(p, st);
+    return QG_EINVAL;
+  }
+  if (waves == 4) return launch_gemv<ROUTE, GPC, 4, 4>(p, st);
+  if (waves == 8) return launch_gemv<ROUTE, GPC, 8, 4>(p, st);
   return QG_EINVAL;
 }
 

@@ -35,7 +35,7 @@ def test_gemv_every_row_count_and_wavefront_count(M, waves):
     P = Prepared(case)
     B.qg_set_knob(3, waves)
     plan = B.qg_plan(P.wtype, case.group, M, case.N, case.K)
-    assert plan["path"] == 5 and (waves == 0 or plan["variant"] == waves), plan
+    assert plan["path"] == 5 and (waves == 0 or plan["variant"] == (waves if (waves < 16 or M == 1) else 4)), plan
     assert_c_close(P.gpu_c(), P.oracle_c(), case.name)
 
 
