@@ -221,7 +221,14 @@ QG_API int qgemm_a8(const int8_t* A8, const float* a_scale, const void* packed_W
  * The lookup is an LDS read from a table replicated over the 32 banks (up to 4 bits: one read
  * returns the two levels of a pair of codes; above: one read per code).  qgemm_codebook chooses
  * between the streaming and the tiled kernel as qgemm does (the experiment overrides of
- * qgemm_tuning.h apply); workspace, stream and error conventions as for qgemm.  QG_EINVAL on a null table, bits outside 1..8 and
+ * qgemm_tuning.h apply); workspace, stream and error conventions as for qgemm.  One more choice
+ * is automatic here: codes of more than 4 bits with M >= 1024 take the paper's prefill variant
+ * (Section "End-to-End Performance": de-quantise the weight to 16 bits once, then a 16-bit
+ * matmul), which is faster for them (their code-by-code lookup does not hide between the matrix
+ * instructions).  It uses a library-owned buffer of K*N*2 bytes per (device, stream), allocated
+ * on first use and replaced after a stream synchronisation when a larger weight arrives -- so
+ * such a call may allocate and is not for graph capture; forcing the tiled kernel (knob 0 = 2)
+ * avoids it, and so does the library itself when K*N*2 reaches 2 GiB or the allocation fails.  QG_EINVAL on a null table, bits outside 1..8 and
  * on the shape / group violations of qgemm. */
 QG_API int qdequant_codebook(const void* packed_W, const void* codebook, const void* scales, int bits,
                       int act, int scale_dtype, int64_t group, int64_t K, int64_t N, void* W_out, void* stream);

@@ -27,9 +27,10 @@ extern "C" {
  *           use, replaced after a stream synchronisation when a larger weight arrives, so this
  *           path is not for graph capture and is refused by qgemm_noalloc -- then the tiled
  *           kernel runs on those 16-bit operands with its unpack stage switched off.  Same
- *           rounded weights, same results as path 2; K*N*2 must stay below 2 GiB.  It is
- *           never chosen automatically: it is slower than the fused kernel at every M
- *           measured, 64 to 12288 rows; 5 = M <= 4 only: matrix-vector kernel on the vector
+ *           rounded weights, same results as path 2; K*N*2 must stay below 2 GiB.  For the
+ *           integer and float types it is never chosen automatically: it is slower than the
+ *           fused kernel at every M measured, 64 to 12288 rows (qgemm_codebook chooses it for
+ *           codes of more than 4 bits from 1024 rows on); 5 = M <= 4 only: matrix-vector kernel on the vector
  *           ALU -- two-element dot products, partial sums added inside the wavefront with lane
  *           permutes -- the measured alternative to the matrix-core streaming kernel; knob 3
  *           then takes its wavefronts per strip, 4 / 8, or 16 with M = 1)

@@ -421,11 +421,25 @@ static void plan_tiled(int64_t M, int64_t N, int64_t K, qg_wtype t, int* bm_out,
   *cps_out = cps;
 }
 
+// The tiled kernels' 32-bit byte offsets: A, the packed weight and the scale array each below 2 GiB.
+static bool tiled_operands_fit(int64_t M, int64_t N, int64_t K, int64_t group, int bits) {
+  const uint64_t lim = 1ull << 31;
+  return (uint64_t)M * (uint64_t)K * 2u < lim && (uint64_t)K * (uint64_t)N / 8u * (uint64_t)bits < lim &&
+         (uint64_t)(K / group) * (uint64_t)N * 2u < lim;
+}
+
 // path of the first layout: 1 = streaming kernel, 2 = tiled kernel, 3 = streaming kernel
-// over blocks of 64 rows (forced only)
-static int plan_path(int64_t M, int64_t N, int64_t K, qg_wtype t) {
+// over blocks of 64 rows (forced only), 4 = de-quantise first (forced, or wide codebooks on many rows)
+static int plan_path(int64_t M, int64_t N, int64_t K, int64_t group, qg_wtype t) {
   const int bits = t.bits;
   if (knob(0)) return knob(0);
+  // Codebooks of more than 4 bits are looked up code by code (six vector instructions and two LDS
+  // reads per pair), which no longer hides between the matrix instructions of the tiled kernel: from
+  // about 1024 rows on the paper's prefill variant -- de-quantise once, then the 16-bit matmul -- is
+  // faster (6 bits on K = 8192, N = 57344: 1.04 ms against 1.09 at M = 1024, 3.22 against 4.11 at 4096,
+  // 9.22 against 12.33 at 12288).  It needs K*N*2 bytes of library-owned buffer below 2 GiB.
+  if (t.kind == QG_CODEBOOK && bits > 4 && M >= 1024 && tiled_operands_fit(M, N, K, group, bits) &&
+      (uint64_t)K * (uint64_t)N * 2u < (1ull << 31)) return 4;
   if (M > 64) return 2;
   // 33 .. 64 rows: the streaming kernel (4 row tiles per wavefront) re-reads A from L2 for
   // every 64-column strip -- measured 10 us + 2.2 us (+ 0.09 per bit above 4) per 1024 of K
@@ -441,13 +455,6 @@ static int plan_path(int64_t M, int64_t N, int64_t K, qg_wtype t) {
     if (tiled < 0.9 * streaming) return 2;          // both fits are good to about 10 %
   }
   return 1;
-}
-
-// The tiled kernels' 32-bit byte offsets: A, the packed weight and the scale array each below 2 GiB.
-static bool tiled_operands_fit(int64_t M, int64_t N, int64_t K, int64_t group, int bits) {
-  const uint64_t lim = 1ull << 31;
-  return (uint64_t)M * (uint64_t)K * 2u < lim && (uint64_t)K * (uint64_t)N / 8u * (uint64_t)bits < lim &&
-         (uint64_t)(K / group) * (uint64_t)N * 2u < lim;
 }
 
 }  // namespace qg
@@ -592,7 +599,7 @@ static int qgemm_run(const void* A, const void* packed_W, const void* scales, co
     return kLarge32[wt](p, route, knob(2), st);
   }
 
-  const int path = plan_path(M, N, K, t);
+  int path = plan_path(M, N, K, group, t);
   if (p.scale_e8m0 && path == 4) return QG_EUNSUPPORTED;      // the de-quantise-first path has no block-scaled variant
   if (path == 1 && M > 64) return QG_EINVAL;
   if (path < 1 || path > 5) return QG_EINVAL;
@@ -613,6 +620,7 @@ static int qgemm_run(const void* A, const void* packed_W, const void* scales, co
     return kGemv[wt](p, route, waves, st);
   }
 
+  void* dense = nullptr;
   if (path == 4) {
     // The paper's prefill variant (Section "End-to-End Performance"): de-quantise the whole
     // weight to 16 bits once, then a plain 16-bit matmul -- here the same tiled kernel reading
@@ -620,9 +628,11 @@ static int qgemm_run(const void* A, const void* packed_W, const void* scales, co
     const uint64_t dense_bytes = (uint64_t)K * (uint64_t)N * 2u;
     if (!fits32 || dense_bytes >= (1ull << 31)) return QG_EUNSUPPORTED;
     if (ws_mode == WS_STATIC) { g_last_error = "qgemm_noalloc: the de-quantise-first path needs a K*N*2-byte buffer"; return QG_EUNSUPPORTED; }
-    void* dense = nullptr;
     rc = get_dense_buffer((size_t)dense_bytes, st, &dense);
-    if (rc != QG_OK) return rc;
+    if (rc != QG_OK && knob(0) == 4) return rc;
+    if (rc != QG_OK) path = 2;       // chosen by the library, no memory for the buffer: the fused kernel instead
+  }
+  if (path == 4) {
     DequantParams d;
     d.W = p.W; d.S = p.S; d.Z = p.Z; d.out = static_cast<uint16_t*>(dense);
     d.layout = QG_LAYOUT_TILE128x64; d.K = p.K; d.N = p.N; d.group = p.group; d.zbias = p.zbias; d.scale_bf16 = p.scale_bf16;
@@ -785,7 +795,7 @@ int qg_plan(qg_wtype t, int layout, int act, int scale_dtype, int64_t group, int
     plan[0] = 2; plan[2] = knob(2);
     return (group == 32 || !tiled_operands_fit(M, N, K, group, t.bits)) ? QG_EUNSUPPORTED : QG_OK;
   }
-  plan[0] = plan_path(M, N, K, t);
+  plan[0] = plan_path(M, N, K, group, t);
   if (scale_dtype == QG_E8M0 && plan[0] == 4) return QG_EUNSUPPORTED;   // the de-quantise-first path has no block-scaled variant
   if (plan[0] == 1 && M > 64) return QG_EINVAL;
   if (plan[0] == 1 || plan[0] == 3) {

@@ -232,6 +232,27 @@ def test_codebook_tiled_kernel_small_groups(group):
     assert_c_close(P.gpu_c(), P.oracle_c(), case.name)
 
 
+@pytest.mark.parametrize("bits", [5, 8])
+def test_codebook_wide_codes_on_many_rows_take_the_dequantise_first_path(bits):
+    # chosen by the library from 1024 rows on; the same rounded weights, so the same tolerance (and one-hot rows bit for bit)
+    case = _case(f"cb_auto4_{bits}", 1024, 384, 192, bits, "bf16", 60800 + bits, group=128)
+    inp = WL.make_inputs(case)
+    A = inp["A"].clone()
+    A[:384] = 0
+    A[torch.arange(384), torch.arange(384)] = 1.0
+    inp["A"] = A
+    P = CbCase(case, inp)
+    assert P.B.qg_plan(P.wtype, case.group, case.M, case.N, case.K, act=P.B.QG_BF16)["path"] == 4
+    C = P.gpu_c()
+    assert_c_close(C, P.oracle_c(), case.name)
+    _, wbits = P.oracle_w()
+    want = wbits.copy()
+    want[want == 0x8000] = 0
+    assert np.array_equal(bits_of(C[:384]), want)
+    P.B.qg_set_knob(0, 2)                          # the fused kernel gives the same bits on the one-hot rows
+    assert np.array_equal(bits_of(P.gpu_c()[:384]), want)
+
+
 def test_codebook_prefill_shape_full_size():
     # K = 8192, N = 57344 (the prefill shape), 4-bit codes, M = 1024: sampled columns for all rows
     case = WL.codebook(4, 1024)

@@ -219,7 +219,17 @@ def test_codebook_weights_plan_like_the_integer_type_and_refusals():
     CB4, CB8 = B.WType(B.QG_CODEBOOK, 4), B.WType(B.QG_CODEBOOK, 8)
     for M, N, K in ((1, 57344, 8192), (16, 8192, 8192), (48, 28672, 8192), (300, 8192, 4096), (4096, 57344, 8192)):
         assert B.qg_plan(CB4, 128, M, N, K) == B.qg_plan(U4, 128, M, N, K), (M, N, K)
-        assert B.qg_plan(CB8, 64, M, N, K, act=B.QG_BF16) == B.qg_plan(U8, 64, M, N, K, act=B.QG_BF16), (M, N, K)
+        if M < 1024:
+            assert B.qg_plan(CB8, 64, M, N, K, act=B.QG_BF16) == B.qg_plan(U8, 64, M, N, K, act=B.QG_BF16), (M, N, K)
+    # wide codebooks on many rows: de-quantise first (the paper's prefill variant), while its buffer stays below 2 GiB
+    assert B.qg_plan(CB8, 128, 1024, 57344, 8192)["path"] == 4
+    assert B.qg_plan(B.WType(B.QG_CODEBOOK, 5), 128, 4096, 8192, 8192)["path"] == 4
+    assert B.qg_plan(CB8, 128, 1023, 57344, 8192)["path"] == 2
+    assert B.qg_plan(CB8, 128, 4096, 65536, 16384)["path"] == 2
+    assert B.qg_plan(CB4, 128, 4096, 57344, 8192)["path"] == 2
+    B.qg_set_knob(0, 2)
+    assert B.qg_plan(CB8, 128, 4096, 57344, 8192)["path"] == 2
+    B.qg_set_knob(0, 0)
     # only the first layout has lookup kernels; block scales do not combine with a table
     assert B.qgemm_packed_bytes(CB4, 256, 128) == 256 * 128 // 2
     assert B.qgemm_packed_bytes(CB4, 256, 128, layout=B.QG_LAYOUT_TILE128x64_R32) == 0
