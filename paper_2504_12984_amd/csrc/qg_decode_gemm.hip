@@ -165,7 +165,6 @@ __global__ __launch_bounds__(NW * 64) void decode_kernel(GemmParams p) {
 
   typename D::Uniform u;
   u.init();
-
   auto compute = [&](auto Sc) __attribute__((always_inline)) {
     constexpr int S = decltype(Sc)::value;
     Stage& s = st[S];
