@@ -54,3 +54,32 @@ def test_argument_errors_are_reported_before_anything_is_enqueued():
     assert B._lib.qdequant(None, None, None, B.WType(B.QG_FLOAT, 8, 5, 2).c(), 0, 0, 0, 128, 128, 64, None, None) == B.QG_EUNSUPPORTED
     assert B._lib.qg_pack_codes(None, 0, 8, None, None) == B.QG_EINVAL
     assert B._lib.qg_pack_codes(None, 3, 0, None, None) == B.QG_OK
+
+
+def test_codebook_and_int8_entry_points_reject_bad_arguments_on_the_host():
+    from paper_2504_12984_amd import binding as B
+    L = B._lib
+    cb = B.WType(B.QG_CODEBOOK, 4).c()
+    # codebook calls: bits out of range, null pointers, K % group, scale type combinations
+    assert L.qgemm_codebook(None, None, None, None, 0, 0, 0, 128, 1, 64, 128, None, None) == B.QG_EINVAL
+    assert L.qgemm_codebook(None, None, None, None, 9, 0, 0, 128, 1, 64, 128, None, None) == B.QG_EINVAL
+    assert L.qgemm_codebook(None, None, None, None, 4, 0, 0, 128, 1, 64, 128, None, None) == B.QG_EINVAL      # null pointers
+    assert L.qgemm_codebook(None, None, None, None, 4, 0, 0, 96, 1, 64, 128, None, None) == B.QG_EINVAL       # K % group
+    assert L.qgemm_codebook(None, None, None, None, 4, 0, B.QG_BF16, 128, 1, 64, 128, None, None) == B.QG_EUNSUPPORTED
+    assert L.qgemm_codebook(None, None, None, None, 4, 0, B.QG_E8M0, 32, 1, 64, 128, None, None) == B.QG_EUNSUPPORTED
+    assert L.qgemm_codebook(None, None, None, None, 4, 0, 0, 128, 0, 64, 128, None, None) == B.QG_OK          # M = 0: nothing to do
+    assert L.qdequant_codebook(None, None, None, 4, 0, 0, 128, 128, 64, None, None) == B.QG_EINVAL
+    assert L.qdequant_codebook(None, None, None, 4, 0, 0, 128, 100, 64, None, None) == B.QG_EINVAL
+    # the plain calls have no table: the codebook kind is an invalid argument there, and so is it for int8 activations
+    assert L.qgemm(None, None, None, None, cb, 0, 0, 0, 128, 1, 64, 128, None, None) == B.QG_EINVAL
+    assert L.qdequant(None, None, None, cb, 0, 0, 0, 128, 128, 64, None, None) == B.QG_EINVAL
+    assert L.qgemm_a8(None, None, None, None, None, cb, 0, 0, 128, 1, 64, 128, None, None) == B.QG_EINVAL
+    # repack takes the kind on the first layout only
+    assert L.repack(None, cb, 1, 128, 64, None, None) == B.QG_EUNSUPPORTED
+    assert L.repack(None, cb, 0, 128, 64, None, None) == B.QG_EINVAL                                          # null pointers
+    assert B.qgemm_packed_bytes(B.WType(B.QG_CODEBOOK, 3), 128, 64) == 3072
+    # int8 activations: float weights and group 32 have no kernel
+    u4 = B.WType(B.QG_UINT, 4).c()
+    assert L.qgemm_a8(None, None, None, None, None, B.WType(B.QG_FLOAT, 4, 2, 1).c(), 0, 0, 128, 1, 64, 128, None, None) == B.QG_EUNSUPPORTED
+    assert L.qgemm_a8(None, None, None, None, None, u4, 0, 0, 32, 1, 64, 128, None, None) == B.QG_EUNSUPPORTED
+    assert L.qgemm_a8(None, None, None, None, None, u4, 0, 0, 128, 1, 64, 128, None, None) == B.QG_EINVAL      # null pointers
