@@ -284,3 +284,29 @@ def test_codebook_argument_checks():
     with pytest.raises(B.QgError) as e:
         B.qgemm_codebook(P.d_A, P.d_packed, P.d_table, P.d_scales.to(torch.bfloat16), 4, case.group, case.N)
     assert e.value.status == B.QG_EUNSUPPORTED
+
+
+def _random_codebook_case(seed: int) -> WL.Case:
+    rng = np.random.default_rng(660000 + seed)
+    bits = int(rng.integers(1, 9))
+    long_k = seed % 2 == 1
+    K = 128 * int(rng.integers(8, 49) if long_k else rng.integers(1, 9))
+    N = 64 * int(rng.integers(1, 25))
+    M = int(rng.choice([rng.integers(1, 17), rng.integers(17, 65), rng.integers(65, 257), rng.integers(257, 641),
+                        rng.integers(1024, 1100)]))
+    groups = [g for g in (32, 64, 128, 256, 512, K)
+              if K % g == 0 and (g == K or g <= 64 or (g // 128) & (g // 128 - 1) == 0)]
+    group = int(rng.choice(groups))
+    act = str(rng.choice(["f16", "bf16"]))
+    sdt = "f16" if act == "f16" else str(rng.choice(["f16", "bf16"]))
+    return WL.Case(f"cbrand{seed}_b{bits}_M{M}_K{K}_N{N}_g{group}_{act}_{sdt}", M, K, N, CB, bits, group=group, act=act,
+                   scale_dtype=sdt, zero=None, seed=661000 + seed)
+
+
+@pytest.mark.parametrize("seed", range(32))
+def test_codebook_random_shapes_through_the_automatic_dispatch(seed):
+    # streaming kernel (every arrangement the planner picks), tiled kernel (tile heights, split-K, split launches) and,
+    # for wide codes on 1024 or more rows, the de-quantise-first path -- whatever the library chooses for the shape
+    case = _random_codebook_case(seed)
+    P = CbCase(case)
+    assert_c_close(P.gpu_c(), P.oracle_c(), case.name)
