@@ -63,7 +63,8 @@ def parse():
     ap.add_argument("--layout", type=int, default=0, help="device layout of the packed weight (0 or 1)")
     ap.add_argument("--entry", default="qgemm", choices=["qgemm", "qgemm_noalloc"])
     ap.add_argument("--path", type=int, default=0,
-                    help="force a path of qgemm (qgemm_tuning.h): 1 streaming, 2 tiled, 4 de-quantise first + 16-bit matmul")
+                    help="force a path of qgemm (qgemm_tuning.h): 1 streaming, 2 tiled, 4 de-quantise first + 16-bit matmul, "
+                         "5 matrix-vector kernel (M <= 4)")
     return ap.parse_args()
 
 
